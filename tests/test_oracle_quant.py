@@ -1,0 +1,169 @@
+"""Pins for the oracle's quantizers (Eq. 5, Eq. 6, Algorithm 1) and the
+compression-ratio accounting (Appendix A, Table 1)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import zipcache_oracle as zo
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(path):
+    with open(os.path.join(GOLDEN, path)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ---- Eq. 5 -----------------------------------------------------------------
+
+def test_hand_worked_example():
+    # x = [-1, 0, 0.5, 2], 2 bits: s = 3/3 = 1, z = -round(-1) = 1,
+    # codes = clip(round(x)+1) = [0, 1, 1 (0.5 rounds to even 0), 3]
+    x = np.array([-1.0, 0.0, 0.5, 2.0])
+    s, z = zo.quant_params(x.min(), x.max(), 2)
+    assert s == 1.0 and z == 1.0
+    codes = zo.quantize(x, s, z, 2)
+    assert list(codes) == [0, 1, 1, 3]
+    assert list(zo.dequantize(codes, s, z)) == [-1.0, 0.0, 0.0, 2.0]
+    # half-to-even: 1.5 -> 2, 2.5 -> 2
+    assert list(zo.quantize(np.array([1.5, 2.5]), 1.0, 0.0, 4)) == [2, 2]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_error_bound_half_scale(bits):
+    x = _rand((200, 64), 20 + bits) * 3 + 0.7
+    s, z = zo.quant_params(x.min(1, keepdims=True), x.max(1, keepdims=True), bits)
+    codes = zo.quantize(x, s, z, bits)
+    assert codes.min() >= 0 and codes.max() <= 2 ** bits - 1
+    assert np.all(codes == np.rint(codes))
+    err = np.abs(zo.dequantize(codes, s, z) - x)
+    assert np.all(err <= s / 2 + 1e-12)
+    # without the "- z" the bound fails (the printed Eq. 5 is shorthand)
+    assert np.any(np.abs(codes * s - x) > s / 2 + 1e-9)
+    # min maps to code 0 and max to the top code, up to one step at a rounding tie
+    assert np.all(codes.min(1) <= 1) and np.all(codes.max(1) >= 2 ** bits - 2)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_integers_on_grid_are_their_own_codes(bits):
+    top = 2 ** bits - 1
+    x = np.random.default_rng(3).integers(0, top + 1, (50, 32)).astype(float)
+    x[:, 0], x[:, 1] = 0, top
+    s, z = zo.quant_params(x.min(1, keepdims=True), x.max(1, keepdims=True), bits)
+    assert np.all(s == 1) and np.all(z == 0)
+    assert np.array_equal(zo.quantize(x, s, z, bits), x)
+    # data already on an affine grid round-trips exactly
+    y = 0.25 * x - 1.5
+    s, z = zo.quant_params(y.min(1, keepdims=True), y.max(1, keepdims=True), bits)
+    assert np.allclose(zo.dequantize(zo.quantize(y, s, z, bits), s, z), y, atol=1e-12)
+
+
+def test_degenerate_groups():
+    x = np.full((1, 3, 4), 2.3)
+    for scheme in ("channel", "cst", "token"):
+        q = zo.quantize_rows(x, 4, scheme)
+        assert np.all(np.isfinite(q.dequant())) and np.all(q.codes >= 0)
+    z = zo.quantize_rows(np.zeros((1, 3, 4)), 2, "cst")
+    assert np.all(z.chan_scale == 1.0) and np.all(z.dequant() == 0.0)
+    e = zo.quantize_rows(np.zeros((2, 0, 4)), 2, "cst")
+    assert e.codes.shape == (2, 0, 4) and np.all(e.chan_scale == 1.0)
+
+
+# ---- granularities -----------------------------------------------------------
+
+def test_channelwise_axis_and_params():
+    X = _rand((2, 30, 12), 21)
+    X[:, :, 3] *= 20  # outlier channel
+    q = zo.quantize_rows(X, 4, "channel")
+    assert q.chan_scale.shape == (2, 12) and np.all(q.tok_scale == 1) and np.all(q.tok_zero == 0)
+    for b in range(2):
+        for w in range(12):
+            col = X[b, :, w]
+            s = (col.max() - col.min()) / 15
+            assert np.isclose(q.chan_scale[b, w], s)
+            assert q.chan_zero[b, w] == -np.rint(col.min() / s)
+            assert np.all(np.abs(q.dequant()[b, :, w] - col) <= s / 2 + 1e-12)
+
+
+def test_cst_steps_match_algorithm_1():
+    X = _rand((1, 10, 6), 22)
+    X[0, 4, 1] = -9.0   # max |.| = 9 -> c = 3
+    X[0, 2, 5] = 4.0    # c = 2 if nothing larger
+    X[0, :, 5] = np.clip(X[0, :, 5], -4, 4)
+    q = zo.quantize_rows(X, 4, "cst")
+    assert q.chan_scale[0, 1] == 3.0 and q.chan_scale[0, 5] == 2.0   # square root, not max
+    assert np.all(q.chan_zero == 0)
+    Xn = X[0] / q.chan_scale[0]
+    for t in range(10):
+        s = (Xn[t].max() - Xn[t].min()) / 15
+        assert np.isclose(q.tok_scale[0, t], s)
+        assert q.tok_zero[0, t] == -np.rint(Xn[t].min() / s)
+        ref = np.clip(np.rint(Xn[t] / s) + q.tok_zero[0, t], 0, 15)
+        assert np.array_equal(q.codes[0, t], ref)
+    err = np.abs(q.dequant() - X)
+    assert np.all(err <= q.chan_scale[:, None, :] * q.tok_scale[:, :, None] / 2 + 1e-12)
+
+
+def test_cst_with_unit_channels_is_tokenwise():
+    X = _rand((2, 9, 8), 23)
+    X = X / np.abs(X).max(axis=1, keepdims=True)       # every channel has max |x| = 1 -> c = 1
+    a, b = zo.quantize_rows(X, 2, "cst"), zo.quantize_rows(X, 2, "token")
+    assert np.allclose(a.chan_scale, 1.0)
+    assert np.array_equal(a.codes, b.codes) and np.allclose(a.dequant(), b.dequant())
+
+
+def test_cst_beats_tokenwise_on_outlier_channels():
+    X = _rand((1, 64, 128), 24)
+    X[:, :, :6] *= 15
+    e_tok = np.abs(zo.quantize_rows(X, 4, "token").dequant() - X)[:, :, 6:].mean()
+    e_cst = np.abs(zo.quantize_rows(X, 4, "cst").dequant() - X)[:, :, 6:].mean()
+    assert e_cst < 0.5 * e_tok
+
+
+def test_token_rows_layout():
+    X = np.arange(2 * 3 * 4 * 5, dtype=float).reshape(2, 3, 4, 5)
+    R = zo.token_rows(X)
+    assert R.shape == (2, 4, 15)
+    assert R[1, 2, 1 * 5 + 3] == X[1, 1, 2, 3]
+    assert np.array_equal(zo.head_rows(R, 3), X)
+
+
+def test_compress_splits_by_subset():
+    K = _rand((2, 2, 12, 4), 25)
+    sal = np.array([[1, 4, 7], [0, 2, 11]])
+    reg = np.array([[i for i in range(12) if i not in s] for s in sal])
+    ch = zo.compress_tensor(K, sal, reg, 4, 2, "channel")
+    R = zo.token_rows(K)
+    assert ch.hi.bits == 4 and ch.lo.bits == 2 and ch.hi.codes.max() <= 15 and ch.lo.codes.max() <= 3
+    for b in range(2):
+        sub = R[b, sal[b]]
+        assert np.allclose(ch.hi.chan_scale[b], (sub.max(0) - sub.min(0)) / 15)  # stats of the subset only
+        assert np.all(np.abs(ch.hi.dequant()[b] - sub) <= ch.hi.chan_scale[b] / 2 + 1e-12)
+        assert np.all(np.abs(ch.lo.dequant()[b] - R[b, reg[b]]) <= ch.lo.chan_scale[b] / 2 + 1e-12)
+
+
+# ---- Appendix A / Table 1 ------------------------------------------------------
+
+def test_appendix_a_printed_ratios():
+    for name, gran, printed, dec in _rows("appendix_a_ratios.txt"):
+        r = zo.compression_ratio(gran, b=8, hd=4096, l=4096, bits_hi=4, n=32)
+        assert round(r, int(dec)) == float(printed), (name, r)
+
+
+def test_table1_parameter_counts():
+    b, hd, l, n = 8, 4096, 4096, 32
+    for gran, c_g, c_bl, c_hd in _rows("table1_param_counts.txt"):
+        expect = int(c_g) * b * hd * l / n + int(c_bl) * b * l + int(c_hd) * hd
+        assert zo.quant_param_count(gran, b, hd, l, n) == expect
+
+
+def test_published_mixed_ratios_are_bracketed():
+    for ratio, l, printed in _rows("published_mixed_ratios.txt"):
+        vals = [zo.compression_ratio("channel+cst", 8, 4096, int(l), 4, 2, float(ratio), subsets=s)
+                for s in (1, 2)]
+        assert min(abs(v - float(printed)) for v in vals) <= 0.025, (ratio, l, vals)
