@@ -1,0 +1,200 @@
+/*
+ * zipcache.h - C ABI of the MI355X (gfx950) implementation of ZipCache's
+ * data-parallel hot path (arXiv 2405.14256).
+ *
+ * Four operations, in the order Algorithm 2 (prefill) and Algorithm 3 (decode)
+ * use them:
+ *
+ *   zc_probe_saliency    Eq. 9 + Eq. 8: normalized attention score of every
+ *                        key token from a probe subset of query rows.
+ *   zc_select_salient    Algorithm 2 "Split": the k most salient tokens.
+ *   zc_quantize_pack     Eq. 5, Eq. 6, Algorithm 1: channelwise or
+ *                        channel-separable tokenwise quantization of the
+ *                        salient subset at bits_hi and of the rest at bits_lo,
+ *                        bit-packed into the cache arenas as a new chunk.
+ *   zc_decode_attention  Eq. 4 over the packed cache (de-quantized on the
+ *                        fly) plus a full-precision tail of recent tokens.
+ *
+ * General rules
+ *   - Every pointer marked "device" is GPU memory owned by the caller; every
+ *     other pointer is host memory.  The library allocates nothing, keeps no
+ *     pointer after a call returns and has no global mutable state.
+ *   - All work is enqueued on the given HIP stream (`stream` is a hipStream_t
+ *     passed as void*; NULL is the default stream).  Calls never synchronise
+ *     with the host and never read results back.
+ *   - Every function returns a zc_status.  Arguments are validated on the host
+ *     before anything is launched; a failed validation launches nothing and
+ *     leaves outputs untouched.  A launch failure returns ZC_ERR_HIP.
+ *   - Device pointers must be 16-byte aligned; tensors must have unit stride
+ *     along the last (channel) axis and all other strides multiples of 8
+ *     elements.
+ *   - Supported: head dimension D in {64, 128}; dtypes f32, f16, bf16;
+ *     code widths in {2, 4, 8}; Hq a multiple of Hkv with Hq/Hkv <= 8.
+ */
+#ifndef ZIPCACHE_H
+#define ZIPCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ZC_OK = 0,
+  ZC_ERR_INVALID_ARG = -1, /* null / misaligned pointer, bad size or stride  */
+  ZC_ERR_UNSUPPORTED = -2, /* dtype, head dim, bit width, scheme not built   */
+  ZC_ERR_WORKSPACE = -3,   /* workspace smaller than the *_workspace() size  */
+  ZC_ERR_CAPACITY = -4,    /* arena or chunk table of a zc_packed is full    */
+  ZC_ERR_HIP = -5          /* the HIP runtime refused a launch               */
+} zc_status;
+
+typedef enum { ZC_F32 = 0, ZC_F16 = 1, ZC_BF16 = 2 } zc_dtype;
+
+/* Quantization granularity of one cache tensor.
+ *   CHANNEL: one (s, z) of Eq. 5 per channel over the tokens of the subset
+ *            (the paper's choice for keys, Section 4.1).
+ *   CST:     Algorithm 1 - c_i = sqrt(max|X_i|) per channel (Eq. 6), then one
+ *            (s, z) per token over the W = H*D normalized values of its row
+ *            (the paper's choice for values).
+ *   TOKEN:   CST with c = 1 (plain tokenwise quantization, Table 1 row 3).
+ * In every scheme
+ *   x_hat[t, w] = chan_scale[w] * tok_scale[t] * (code[t, w] - tok_zero[t] - chan_zero[w])
+ * with tok_scale = 1, tok_zero = 0 for CHANNEL and chan_zero = 0 otherwise. */
+typedef enum { ZC_SCHEME_CHANNEL = 0, ZC_SCHEME_CST = 1, ZC_SCHEME_TOKEN = 2 } zc_scheme;
+
+/* Bit layout of the codes of one (batch, head) inside an arena.
+ *   ROW    (keys): slot-major rows of D codes; code of channel c sits at bit
+ *          offset c*bits of its row, little-endian (for 4 bits: channel 2j in
+ *          the low nibble of byte j).
+ *   TGROUP (values): 32-bit words indexed [block][kg][c], kg in 0..3, c the
+ *          channel, each word holding E = 32/bits codes of one channel for E
+ *          different slots; a block covers 4*E consecutive slots.  Field e
+ *          (bits e*bits .. (e+1)*bits-1) of word [blk][kg][c] belongs to slot
+ *             blk*4*E + 16*j(e) + 4*kg + e%4,
+ *          j(e) = e/4 for bits in {4, 8};  for bits == 2, j(e) = 0,2,1,3 for
+ *          e/4 = 0,1,2,3.
+ *          (Keys are contracted over channels and values over tokens, so each
+ *          tensor packs along the axis its matrix-core operand runs over.)
+ * Both layouts take B*H*cap*D*bits/8 bytes per arena. */
+typedef enum { ZC_LAYOUT_ROW = 0, ZC_LAYOUT_TGROUP = 1 } zc_layout;
+
+#define ZC_SLOT_ALIGN 64 /* every chunk starts at a multiple of this many slots */
+#define ZC_MAX_GROUP 8   /* largest supported Hq / Hkv                          */
+
+/* A strided 4-D view [B, H, L, D] of device memory; strides in elements,
+ * the D axis is contiguous. */
+typedef struct zc_tensor4 {
+  void* ptr; /* device */
+  int32_t dtype; /* zc_dtype */
+  int32_t reserved;
+  int64_t B, H, L, D;
+  int64_t sB, sH, sL;
+} zc_tensor4;
+
+/* One tensor (K or V) of the compressed cache.  The struct lives on the host;
+ * all arrays are caller-allocated.  Salient tokens go to the "hi" arena at
+ * bits_hi, the others to the "lo" arena at bits_lo.  Each zc_quantize_pack
+ * call appends one chunk: chunk_table row i = {begin_hi, len_hi, begin_lo,
+ * len_lo} in slots.  A chunk has its own channel parameters (one set per
+ * subset); slot r of the hi part of chunk i is slot begin_hi + r of the hi
+ * arena for the codes, the token parameters and the positions alike.  The K
+ * and V structs of one cache must be filled by the same sequence of calls so
+ * that their chunk tables agree. */
+typedef struct zc_packed {
+  int32_t layout;  /* zc_layout */
+  int32_t scheme;  /* zc_scheme */
+  int32_t bits_hi, bits_lo;
+  int64_t B, H, D;          /* W = H*D channels per token row */
+  int64_t cap_hi, cap_lo;   /* slots per arena, multiples of ZC_SLOT_ALIGN */
+  int64_t n_hi, n_lo;       /* slots in use (aligned end of the last chunk) */
+  uint8_t* codes_hi;        /* device, B*H*cap_hi*D*bits_hi/8 bytes */
+  uint8_t* codes_lo;        /* device */
+  float* tok_scale_hi;      /* device [B, cap_hi]; unused for CHANNEL (may be NULL) */
+  float* tok_zero_hi;
+  float* tok_scale_lo;      /* device [B, cap_lo] */
+  float* tok_zero_lo;
+  int32_t* pos_hi;          /* device [B, cap_hi] original token positions, or NULL */
+  int32_t* pos_lo;          /* device [B, cap_lo], or NULL */
+  float* chan_scale;        /* device [max_chunks, 2 (hi, lo), B, W] */
+  float* chan_zero;         /* device [max_chunks, 2, B, W] */
+  int32_t* chunk_table;     /* device [max_chunks, 4] */
+  int32_t* chunk_table_host; /* host   [max_chunks, 4], kept equal to the above */
+  int32_t n_chunks, max_chunks;
+} zc_packed;
+
+/* ---- Eq. 9 + Eq. 8 ------------------------------------------------------
+ * q [B, Hq, Lq, D], k [B, Hkv, Lk, D], same dtype.  Probe p uses query row
+ * probe_rows[p] of q (probe_pos[p] when probe_rows is NULL) and attends key
+ * columns i <= probe_pos[p]; probe_pos must be ascending (device int32 [P],
+ * values in [0, Lk)).  Logits are q.k * sm_scale (sm_scale == 0 means
+ * 1/sqrt(D)); query head h reads KV head h / (Hq/Hkv).
+ * With lse_ext == NULL each probe row is soft-maxed over its visible columns.
+ * With lse_ext (device float [B, Hq, P], natural log) the probabilities are
+ * exp(logit - lse_ext): decode-time probes whose softmax also covered tokens
+ * outside k.
+ * Output scores (device float [B, Lk]): mean over query heads of
+ *   sum_{p : probe_pos[p] >= i} A[p, i] / #{p : probe_pos[p] >= i}
+ * (0 where no probe sees column i).  scores_per_head (device float
+ * [B, Hq, Lk]) receives the per-head values when not NULL.
+ * The result is deterministic: no floating-point atomics are used. */
+size_t zc_probe_saliency_workspace(int64_t B, int64_t Hq, int64_t Lk, int64_t P);
+int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
+                      const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
+                      float sm_scale, const float* lse_ext,
+                      float* scores, float* scores_per_head,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Algorithm 2, Split(., p~, r%) ------------------------------------------
+ * scores: device float [B, L] (must not contain NaN).  For every batch row
+ * the k largest scores are salient; among equal scores the lower index wins.
+ * salient_idx (device int32 [B, k]) and regular_idx (device int32 [B, L-k])
+ * are both ascending; mask (device uint8 [B, L], optional) is 1 for salient.
+ * 0 <= k <= L.  Exact and deterministic. */
+size_t zc_select_salient_workspace(int64_t B, int64_t L);
+int zc_select_salient(const float* scores, int64_t B, int64_t L, int64_t k,
+                      int32_t* salient_idx, int32_t* regular_idx, uint8_t* mask,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Eq. 5, Eq. 6, Algorithm 1; the four quantizer calls of Algorithm 2 -----
+ * x [B, H, L, D] is one cache tensor.  Tokens salient_idx[b, 0..k) are
+ * quantized at out->bits_hi, tokens regular_idx[b, 0..n_reg) at out->bits_lo,
+ * each subset with its own channel statistics, by out->scheme, rounding half
+ * to even; s := 1 when max == min, c := 1 when the channel is all zero.  An
+ * empty subset gets chan_scale = 1, chan_zero = 0.  The codes are appended as
+ * chunk out->n_chunks in out->layout; positions idx + pos_offset are stored
+ * when pos arrays are present.  On success the host fields n_hi, n_lo,
+ * n_chunks and chunk_table_host are updated (the device copy is written by
+ * the enqueued work).  Index lists must hold distinct values in [0, L). */
+size_t zc_quantize_pack_workspace(int64_t B, int64_t H, int64_t D);
+int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
+                     const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
+                     zc_packed* out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Eq. 4 over the packed cache (Algorithm 3, attention line) -------------------
+ * q [B, Hq, 1, D]; Kp (ROW layout) and Vp (TGROUP layout) hold the same
+ * chunks; tail_k / tail_v [B, Hkv, >=tail_len, D] are the full-precision
+ * recent tokens (same dtype as q; may be NULL when tail_len == 0).
+ * out (device, q's dtype, [B, Hq, D]) = softmax(q.K^T * sm_scale) V over all
+ * packed tokens and the first tail_len tail tokens; lse_out (device float
+ * [B, Hq], optional) receives the natural-log normaliser of each row.
+ * Deterministic for fixed shapes. */
+size_t zc_decode_attention_workspace(int64_t B, int64_t Hq, int64_t D);
+int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
+                        const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
+                        float sm_scale, void* out, float* lse_out,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ---- helpers ------------------------------------------------------------------ */
+/* Bytes of one code arena of `cap` slots. */
+size_t zc_arena_bytes(int64_t B, int64_t H, int64_t D, int64_t cap, int32_t bits);
+/* Smallest legal capacity that holds `n_chunks` chunks totalling n tokens. */
+int64_t zc_arena_slots(int64_t n_tokens, int64_t n_chunks);
+const char* zc_status_string(int status);
+int zc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPCACHE_H */

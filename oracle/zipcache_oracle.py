@@ -149,19 +149,35 @@ def select_salient(score: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
 # Uniform quantizer (Eq. 5) and the three granularities built on it
 # --------------------------------------------------------------------------
 
+def _ratio(x, xmin, xmax, bits: int):
+    """x / s of Eq. 5 with s = (max - min) / (2^k - 1), evaluated as
+    x * (2^k - 1) / (max - min): the same real number with one rounding instead
+    of two, so that an input lying exactly halfway between two codes (frequent
+    with fp16 / bf16 data, whose values sit on a coarse grid) is still exactly
+    halfway after the division and rounds half-to-even as in exact arithmetic.
+    A group with max == min uses s = 1."""
+    x = np.asarray(x, F64)
+    rng = np.asarray(xmax, F64) - np.asarray(xmin, F64)
+    flat = rng == 0.0
+    return np.where(flat, x, x * float(2 ** bits - 1) / np.where(flat, 1.0, rng))
+
+
 def quant_params(xmin, xmax, bits: int):
     """s = (max - min) / (2^k - 1), z = -round(min / s); s := 1 if max == min."""
     xmin = np.asarray(xmin, F64)
     xmax = np.asarray(xmax, F64)
     s = (xmax - xmin) / float(2 ** bits - 1)
     s = np.where(s == 0.0, 1.0, s)
-    z = -np.rint(xmin / s)
+    z = -np.rint(_ratio(xmin, xmin, xmax, bits))
     return s, z
 
 
-def quantize(x, s, z, bits: int):
-    """clip(round(x / s) + z, 0, 2^k - 1)."""
-    return np.clip(np.rint(np.asarray(x, F64) / s) + z, 0.0, float(2 ** bits - 1))
+def quantize(x, xmin, xmax, bits: int):
+    """clip(round(x / s) + z, 0, 2^k - 1) for a group with the given extrema.
+    Returns (codes, x / s before rounding)."""
+    _, z = quant_params(xmin, xmax, bits)
+    pre = _ratio(x, xmin, xmax, bits)
+    return np.clip(np.rint(pre) + z, 0.0, float(2 ** bits - 1)), pre
 
 
 def dequantize(code, s, z):
@@ -185,7 +201,7 @@ class QuantSubset:
     chan_zero: np.ndarray    # [B, W]
     tok_scale: np.ndarray    # [B, n]
     tok_zero: np.ndarray     # [B, n]
-    pre_round: Optional[np.ndarray] = None  # x/s + z before rounding (diagnostics)
+    pre_round: Optional[np.ndarray] = None  # x/s before rounding (diagnostics)
 
     def dequant(self) -> np.ndarray:
         return (self.chan_scale[:, None, :] * self.tok_scale[:, :, None]
@@ -213,9 +229,9 @@ def quantize_rows(X: np.ndarray, bits: int, scheme: str, idx: Optional[np.ndarra
         return QuantSubset(scheme, bits, idx, np.zeros((B, 0, W)), ones_c, zeros_c, ones_t, zeros_t,
                            np.zeros((B, 0, W)))
     if scheme == "channel":
-        s, z = quant_params(X.min(axis=1), X.max(axis=1), bits)          # [B, W]
-        pre = X / s[:, None, :] + z[:, None, :]
-        codes = quantize(X, s[:, None, :], z[:, None, :], bits)
+        lo, hi = X.min(axis=1), X.max(axis=1)                            # [B, W]
+        s, z = quant_params(lo, hi, bits)
+        codes, pre = quantize(X, lo[:, None, :], hi[:, None, :], bits)
         return QuantSubset(scheme, bits, idx, codes, s, z, ones_t, zeros_t, pre)
     if scheme == "cst":
         c = np.sqrt(np.abs(X).max(axis=1))                               # [B, W]
@@ -225,9 +241,9 @@ def quantize_rows(X: np.ndarray, bits: int, scheme: str, idx: Optional[np.ndarra
     else:
         raise ValueError(scheme)
     Xn = X / c[:, None, :]
-    s, z = quant_params(Xn.min(axis=2), Xn.max(axis=2), bits)            # [B, n]
-    pre = Xn / s[:, :, None] + z[:, :, None]
-    codes = quantize(Xn, s[:, :, None], z[:, :, None], bits)
+    lo, hi = Xn.min(axis=2), Xn.max(axis=2)                              # [B, n]
+    s, z = quant_params(lo, hi, bits)
+    codes, pre = quantize(Xn, lo[:, :, None], hi[:, :, None], bits)
     return QuantSubset(scheme, bits, idx, codes, c, zeros_c, s, z, pre)
 
 

@@ -1,0 +1,345 @@
+// zc_probe_saliency: normalized attention score of every key token from a
+// probe subset of query rows (Eq. 9 substituted into Eq. 8).
+//
+// The probe rows of A = Softmax(Q_probe K^T / sqrt(d)) are never stored.  Two
+// matrix-core sweeps recompute the logits instead:
+//   k_probe_lse     one workgroup per 64 probe rows: streams 128-column K tiles
+//                   through LDS, logits come out of the MFMA as D[column][row]
+//                   so that every lane owns one probe row and keeps its running
+//                   (max, sum) in two registers; writes log-sum-exp per row.
+//   k_probe_colsum  one workgroup per 128 key columns: K fragments stay in
+//                   registers, 64-row probe tiles stream through LDS, logits
+//                   come out as D[row][column] so that every lane owns one
+//                   column and sums exp(logit - lse) over the rows in registers;
+//                   divides by the number of probes that can see the column.
+//   k_probe_mean    mean over query heads.
+// Causality: rows are sorted by position, so a column tile starts at the first
+// probe that can see it and a row tile stops at its last row's position.
+// Inputs in fp16 / bf16 use the 32x32x16 MFMA, fp32 inputs the 32x32x2 fp32 MFMA
+// (no rounding of the operands); accumulation and softmax are fp32.
+#include "zc_common.hpp"
+
+namespace zc {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+struct ProbeArgs {
+  const void* q;
+  const void* k;
+  int64_t q_sB, q_sH, q_sL, k_sB, k_sH, k_sL;
+  int B, Hq, Hkv, G, Lk, P;
+  const int32_t* probe_rows;
+  const int32_t* probe_pos;
+  float scale_log2;
+  const float* lse_in;   // natural log, [B, Hq, P]
+  float* lse_out;
+  float* per_head;       // [B, Hq, Lk]
+};
+
+// One 16-byte operand chunk per lane: a single 32x32x16 MFMA for 16-bit types,
+// four 32x32x2 MFMAs for fp32 (element m of both half-waves forms one k pair).
+template <int DT>
+__device__ inline void mma_chunk(v16f& acc, u32x4 a, u32x4 b) {
+  if constexpr (DT == ZC_BF16) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  } else if constexpr (DT == ZC_F16) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+  } else {
+    // (the elements are extracted one by one on purpose: a loop over a[i] inside
+    // a bit-cast collapsed to element 0 with this compiler)
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  }
+}
+
+template <int DT, int D>
+struct Tile {
+  static constexpr int EB = (DT == ZC_F32) ? 4 : 2;
+  static constexpr int ROWB = D * EB;          // bytes of one row
+  static constexpr int CPR = ROWB / 16;        // 16-byte chunks per row
+  static constexpr int STRIDE = ROWB + 16;     // padded LDS row stride
+  static constexpr int NKC = ROWB / 32;        // operand chunks per lane and row
+};
+
+// Row index inside a 32x32 MFMA result held by accumulator register v of a lane
+// in half-wave kh.
+__device__ inline int acc_row(int v, int kh) { return 8 * (v >> 2) + 4 * kh + (v & 3); }
+
+template <int DT, int D>
+__global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
+  using T = Tile<DT, D>;
+  __shared__ __align__(16) uint8_t Qs[64 * T::STRIDE];
+  __shared__ __align__(16) uint8_t Ks[128 * T::STRIDE];
+  __shared__ int spos[64];
+  __shared__ float sm[4][64], sz[4][64];
+
+  const int rb0 = blockIdx.x * 64, hq = blockIdx.y, b = blockIdx.z, hk = hq / a.G;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
+  const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
+  const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
+
+  for (int i = tid; i < 64 * T::CPR; i += 256) {
+    const int row = i / T::CPR, cc = i % T::CPR;
+    const int p = rb0 + row;
+    u32x4 v = {0, 0, 0, 0};
+    if (p < a.P) {
+      const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
+      v = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
+    }
+    *reinterpret_cast<u32x4*>(Qs + row * T::STRIDE + cc * 16) = v;
+  }
+  if (tid < 64) spos[tid] = (rb0 + tid < a.P) ? a.probe_pos[rb0 + tid] : -1;
+  __syncthreads();
+
+  const int nvalid = min(64, a.P - rb0);
+  const int pmax = min(spos[nvalid - 1], a.Lk - 1);
+  const int ntiles = pmax / 128 + 1;
+
+  u32x4 qf[2][T::NKC];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int kc = 0; kc < T::NKC; ++kc)
+      qf[rb][kc] = *reinterpret_cast<const u32x4*>(Qs + (rb * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+  const int myp[2] = {spos[r], spos[32 + r]};
+  float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
+
+  for (int t = 0; t < ntiles; ++t) {
+    __syncthreads();
+    for (int i = tid; i < 128 * T::CPR; i += 256) {
+      const int row = i / T::CPR, cc = i % T::CPR;
+      const int col = t * 128 + row;
+      u32x4 v = {0, 0, 0, 0};
+      if (col < a.Lk) v = *reinterpret_cast<const u32x4*>(kb + (int64_t)col * a.k_sL * T::EB + cc * 16);
+      *reinterpret_cast<u32x4*>(Ks + row * T::STRIDE + cc * 16) = v;
+    }
+    __syncthreads();
+    v16f acc[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
+#pragma unroll
+    for (int kc = 0; kc < T::NKC; ++kc) {
+      const u32x4 af = *reinterpret_cast<const u32x4*>(Ks + (w * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+      mma_chunk<DT>(acc[0], af, qf[0][kc]);
+      mma_chunk<DT>(acc[1], af, qf[1][kc]);
+    }
+    const int colb = t * 128 + w * 32;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      float sv[16];
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int col = colb + acc_row(v, kh);
+        const float s = (col <= myp[rb]) ? acc[rb][v] * a.scale_log2 : -INFINITY;
+        sv[v] = s;
+        tmax = fmaxf(tmax, s);
+      }
+      const float m_new = fmaxf(m[rb], tmax);
+      if (m_new > -INFINITY) {
+        float sum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += exp2f(sv[v] - m_new);
+        z[rb] = z[rb] * exp2f(m[rb] - m_new) + sum;
+        m[rb] = m_new;
+      }
+    }
+  }
+  // merge the two half-waves, then the four waves
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const float mo = __shfl_xor(m[rb], 32), zo = __shfl_xor(z[rb], 32);
+    const float M = fmaxf(m[rb], mo);
+    float Z = 0.f;
+    if (M > -INFINITY) Z = z[rb] * exp2f(m[rb] - M) + zo * exp2f(mo - M);
+    if (kh == 0) { sm[w][rb * 32 + r] = M; sz[w][rb * 32 + r] = Z; }
+  }
+  __syncthreads();
+  if (tid < 64 && rb0 + tid < a.P) {
+    float M = fmaxf(fmaxf(sm[0][tid], sm[1][tid]), fmaxf(sm[2][tid], sm[3][tid]));
+    float Z = 0.f;
+    if (M > -INFINITY) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Z += sz[i][tid] * exp2f(sm[i][tid] - M);
+    }
+    a.lse_out[((int64_t)b * a.Hq + hq) * a.P + rb0 + tid] = (M + log2f(Z)) * kLn2;
+  }
+}
+
+__device__ inline int lower_bound_pos(const int32_t* pos, int n, int key) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (pos[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+template <int DT, int D>
+__global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
+  using T = Tile<DT, D>;
+  __shared__ __align__(16) uint8_t Ks[128 * T::STRIDE];
+  __shared__ __align__(16) uint8_t Qs[64 * T::STRIDE];
+  __shared__ int spos[64];
+  __shared__ float slse[64];
+  __shared__ float scol[2][128];
+
+  const int col0 = blockIdx.x * 128, hq = blockIdx.y, b = blockIdx.z, hk = hq / a.G;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
+  const int rbw = w >> 1, cbp = w & 1;
+  const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
+  const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
+  const float* lse = a.lse_in + ((int64_t)b * a.Hq + hq) * a.P;
+
+  for (int i = tid; i < 128 * T::CPR; i += 256) {
+    const int row = i / T::CPR, cc = i % T::CPR;
+    const int col = col0 + row;
+    u32x4 v = {0, 0, 0, 0};
+    if (col < a.Lk) v = *reinterpret_cast<const u32x4*>(kb + (int64_t)col * a.k_sL * T::EB + cc * 16);
+    *reinterpret_cast<u32x4*>(Ks + row * T::STRIDE + cc * 16) = v;
+  }
+  __syncthreads();
+  u32x4 kf[2][T::NKC];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int kc = 0; kc < T::NKC; ++kc)
+      kf[cb][kc] = *reinterpret_cast<const u32x4*>(Ks + ((cbp * 2 + cb) * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+
+  const int pstart = lower_bound_pos(a.probe_pos, a.P, col0);
+  float colsum[2] = {0.f, 0.f};
+
+  for (int pr = pstart; pr < a.P; pr += 64) {
+    __syncthreads();
+    for (int i = tid; i < 64 * T::CPR; i += 256) {
+      const int row = i / T::CPR, cc = i % T::CPR;
+      const int p = pr + row;
+      u32x4 v = {0, 0, 0, 0};
+      if (p < a.P) {
+        const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
+        v = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
+      }
+      *reinterpret_cast<u32x4*>(Qs + row * T::STRIDE + cc * 16) = v;
+    }
+    if (tid < 64) {
+      const int p = pr + tid;
+      spos[tid] = p < a.P ? a.probe_pos[p] : -1;
+      slse[tid] = p < a.P ? lse[p] * kLog2e : 0.f;
+    }
+    __syncthreads();
+    int rp[16];
+    float rl[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      rp[v] = spos[rbw * 32 + acc_row(v, kh)];
+      rl[v] = slse[rbw * 32 + acc_row(v, kh)];
+    }
+    v16f acc[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
+#pragma unroll
+    for (int kc = 0; kc < T::NKC; ++kc) {
+      const u32x4 af = *reinterpret_cast<const u32x4*>(Qs + (rbw * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+      mma_chunk<DT>(acc[0], af, kf[0][kc]);
+      mma_chunk<DT>(acc[1], af, kf[1][kc]);
+    }
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      const int col = col0 + (cbp * 2 + cb) * 32 + r;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float e = exp2f(acc[cb][v] * a.scale_log2 - rl[v]);
+        colsum[cb] += (col <= rp[v]) ? e : 0.f;
+      }
+    }
+  }
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    colsum[cb] += __shfl_xor(colsum[cb], 32);
+    if (kh == 0) scol[rbw][(cbp * 2 + cb) * 32 + r] = colsum[cb];
+  }
+  __syncthreads();
+  if (tid < 128 && col0 + tid < a.Lk) {
+    const int col = col0 + tid;
+    const float total = scol[0][tid] + scol[1][tid];
+    const int cnt = a.P - lower_bound_pos(a.probe_pos, a.P, col);
+    a.per_head[((int64_t)b * a.Hq + hq) * a.Lk + col] = cnt > 0 ? total / (float)cnt : 0.f;
+  }
+}
+
+__global__ void k_probe_mean(const float* __restrict__ per_head, float* __restrict__ scores, int Hq, int Lk) {
+  const int b = blockIdx.y;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Lk) return;
+  float s = 0.f;
+  for (int h = 0; h < Hq; ++h) s += per_head[((int64_t)b * Hq + h) * Lk + i];
+  scores[(int64_t)b * Lk + i] = s / (float)Hq;
+}
+
+template <int DT, int D>
+static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStream_t st) {
+  if (need_lse) {
+    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3(ceil_div(a.P, 64), a.Hq, a.B), dim3(256), 0, st, a);
+    ZC_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL((k_probe_colsum<DT, D>), dim3(ceil_div(a.Lk, 128), a.Hq, a.B), dim3(256), 0, st, a);
+  ZC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_probe_mean, dim3(ceil_div(a.Lk, 256), a.B), dim3(256), 0, st, a.per_head, scores, a.Hq, a.Lk);
+  ZC_LAUNCH_CHECK();
+  return ZC_OK;
+}
+
+}  // namespace zc
+
+using namespace zc;
+
+static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * 4, 256); }
+
+extern "C" size_t zc_probe_saliency_workspace(int64_t B, int64_t Hq, int64_t Lk, int64_t P) {
+  if (B <= 0 || Hq <= 0 || Lk <= 0 || P <= 0) return 0;
+  return lse_bytes(B, Hq, P) + (size_t)B * Hq * Lk * 4;
+}
+
+extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
+                                 const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
+                                 float sm_scale, const float* lse_ext,
+                                 float* scores, float* scores_per_head,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  int rc = zc_validate_tensor(q);
+  if (rc) return rc;
+  rc = zc_validate_tensor(k);
+  if (rc) return rc;
+  if (q->dtype != k->dtype || q->D != k->D || q->B != k->B) return ZC_ERR_INVALID_ARG;
+  if (q->H % k->H != 0) return ZC_ERR_INVALID_ARG;
+  if (P < 1 || !probe_pos || !scores || k->L < 1 || q->L < 1) return ZC_ERR_INVALID_ARG;
+  if (q->B > 65535 || q->H > 65535 || k->L > 0x7fffffff - 256) return ZC_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(probe_pos) & 3) || (reinterpret_cast<uintptr_t>(scores) & 3)) return ZC_ERR_INVALID_ARG;
+  const size_t need = zc_probe_saliency_workspace(q->B, q->H, k->L, P);
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
+
+  ProbeArgs a;
+  a.q = q->ptr; a.k = k->ptr;
+  a.q_sB = q->sB; a.q_sH = q->sH; a.q_sL = q->sL;
+  a.k_sB = k->sB; a.k_sH = k->sH; a.k_sL = k->sL;
+  a.B = (int)q->B; a.Hq = (int)q->H; a.Hkv = (int)k->H; a.G = a.Hq / a.Hkv; a.Lk = (int)k->L; a.P = P;
+  a.probe_rows = probe_rows; a.probe_pos = probe_pos;
+  a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)q->D) : sm_scale) * kLog2e;
+  float* ws_lse = reinterpret_cast<float*>(ws);
+  float* ws_ph = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + lse_bytes(q->B, q->H, P));
+  a.lse_in = lse_ext ? lse_ext : ws_lse;
+  a.lse_out = ws_lse;
+  a.per_head = scores_per_head ? scores_per_head : ws_ph;
+
+  hipStream_t st = (hipStream_t)stream;
+  const bool need_lse = lse_ext == nullptr;
+#define ZC_PROBE(DT) (q->D == 128 ? launch_probe<DT, 128>(a, need_lse, scores, st) : launch_probe<DT, 64>(a, need_lse, scores, st))
+  if (q->dtype == ZC_F32) return ZC_PROBE(ZC_F32);
+  if (q->dtype == ZC_F16) return ZC_PROBE(ZC_F16);
+  return ZC_PROBE(ZC_BF16);
+#undef ZC_PROBE
+}

@@ -27,18 +27,38 @@ def test_hand_worked_example():
     x = np.array([-1.0, 0.0, 0.5, 2.0])
     s, z = zo.quant_params(x.min(), x.max(), 2)
     assert s == 1.0 and z == 1.0
-    codes = zo.quantize(x, s, z, 2)
+    codes, _ = zo.quantize(x, x.min(), x.max(), 2)
     assert list(codes) == [0, 1, 1, 3]
     assert list(zo.dequantize(codes, s, z)) == [-1.0, 0.0, 0.0, 2.0]
-    # half-to-even: 1.5 -> 2, 2.5 -> 2
-    assert list(zo.quantize(np.array([1.5, 2.5]), 1.0, 0.0, 4)) == [2, 2]
+    # half-to-even: 1.5 -> 2, 2.5 -> 2 (extrema 0 and 15 at 4 bits give s = 1, z = 0)
+    assert list(zo.quantize(np.array([1.5, 2.5]), 0.0, 15.0, 4)[0]) == [2, 2]
+    # round first, then add z (Eq. 5): with z odd the order decides a tie.
+    # x in [-3, 12], 4 bits: s = 1, z = 3; 0.5 -> round(0.5) + 3 = 3, not round(3.5) = 4
+    assert list(zo.quantize(np.array([0.5, 1.5]), -3.0, 12.0, 4)[0]) == [3, 5]
+
+
+def test_exact_ties_survive_a_coarse_grid():
+    """Values on a bf16-like grid that sit exactly halfway between two codes
+    must round half-to-even, whatever (max - min) / (2^k - 1) rounds to."""
+    lo, hi = -1.3125, 2.34375                       # range not a multiple of 15 ulps of anything nice
+    rng = hi - lo
+    n = np.arange(0, 15)
+    x = (n + 0.5) * rng / 15                        # exact ties in real arithmetic ...
+    x = x[(x * 15 / rng) == n[: len(x)] + 0.5]      # ... keep those that are exact in floating point too
+    assert len(x) >= 3
+    codes, pre = zo.quantize(x, lo, hi, 4)
+    z = -np.rint(lo * 15 / rng)
+    assert np.array_equal(pre - np.floor(pre), np.full(len(x), 0.5))
+    lower = np.floor(pre)
+    even = np.where(lower % 2 == 0, lower, lower + 1)   # the even neighbour
+    assert np.array_equal(codes, np.clip(even + z, 0, 15))
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4, 8])
 def test_error_bound_half_scale(bits):
     x = _rand((200, 64), 20 + bits) * 3 + 0.7
     s, z = zo.quant_params(x.min(1, keepdims=True), x.max(1, keepdims=True), bits)
-    codes = zo.quantize(x, s, z, bits)
+    codes, _ = zo.quantize(x, x.min(1, keepdims=True), x.max(1, keepdims=True), bits)
     assert codes.min() >= 0 and codes.max() <= 2 ** bits - 1
     assert np.all(codes == np.rint(codes))
     err = np.abs(zo.dequantize(codes, s, z) - x)
@@ -56,11 +76,12 @@ def test_integers_on_grid_are_their_own_codes(bits):
     x[:, 0], x[:, 1] = 0, top
     s, z = zo.quant_params(x.min(1, keepdims=True), x.max(1, keepdims=True), bits)
     assert np.all(s == 1) and np.all(z == 0)
-    assert np.array_equal(zo.quantize(x, s, z, bits), x)
+    assert np.array_equal(zo.quantize(x, x.min(1, keepdims=True), x.max(1, keepdims=True), bits)[0], x)
     # data already on an affine grid round-trips exactly
     y = 0.25 * x - 1.5
     s, z = zo.quant_params(y.min(1, keepdims=True), y.max(1, keepdims=True), bits)
-    assert np.allclose(zo.dequantize(zo.quantize(y, s, z, bits), s, z), y, atol=1e-12)
+    yc, _ = zo.quantize(y, y.min(1, keepdims=True), y.max(1, keepdims=True), bits)
+    assert np.allclose(zo.dequantize(yc, s, z), y, atol=1e-12)
 
 
 def test_degenerate_groups():
