@@ -151,15 +151,38 @@ def select_salient(score: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
 
 def _ratio(x, xmin, xmax, bits: int):
     """x / s of Eq. 5 with s = (max - min) / (2^k - 1), evaluated as
-    x * (2^k - 1) / (max - min): the same real number with one rounding instead
-    of two, so that an input lying exactly halfway between two codes (frequent
-    with fp16 / bf16 data, whose values sit on a coarse grid) is still exactly
-    halfway after the division and rounds half-to-even as in exact arithmetic.
-    A group with max == min uses s = 1."""
+    x * (2^k - 1) / (max - min) (the same real number).  A group with
+    max == min uses s = 1."""
     x = np.asarray(x, F64)
     rng = np.asarray(xmax, F64) - np.asarray(xmin, F64)
     flat = rng == 0.0
     return np.where(flat, x, x * float(2 ** bits - 1) / np.where(flat, 1.0, rng))
+
+
+def _round_ratio(x, xmin, xmax, bits: int):
+    """round(x / s) of Eq. 5, half-to-even, decided in exact arithmetic.
+
+    fp16 / bf16 data sit on a coarse grid, so x / s lands exactly halfway
+    between two integers far more often than chance (for instance the minimum
+    of a token row whose maximum is its mirror image gives exactly -(2^k-1)/2).
+    Floating-point evaluation would decide those ties by its own rounding
+    noise; here every value within 1e-9 of a tie is re-evaluated as the exact
+    rational x (2^k - 1) / (max - min) of the given float64 numbers.
+    Returns (rounded, value before rounding)."""
+    from fractions import Fraction
+    pre = _ratio(x, xmin, xmax, bits)
+    out = np.array(np.rint(pre), dtype=F64)
+    frac = np.abs(pre - np.floor(pre) - 0.5)
+    near = np.argwhere(frac < 1e-9 * np.maximum(1.0, np.abs(pre)))
+    if len(near):
+        xb, lob, hib = np.broadcast_arrays(np.asarray(x, F64), np.asarray(xmin, F64), np.asarray(xmax, F64))
+        qmax = 2 ** bits - 1
+        for ix in map(tuple, near):
+            lo, hi = Fraction(float(lob[ix])), Fraction(float(hib[ix]))
+            if hi == lo:
+                continue
+            out[ix] = float(round(Fraction(float(xb[ix])) * qmax / (hi - lo)))   # half-to-even
+    return out, pre
 
 
 def quant_params(xmin, xmax, bits: int):
@@ -168,16 +191,16 @@ def quant_params(xmin, xmax, bits: int):
     xmax = np.asarray(xmax, F64)
     s = (xmax - xmin) / float(2 ** bits - 1)
     s = np.where(s == 0.0, 1.0, s)
-    z = -np.rint(_ratio(xmin, xmin, xmax, bits))
-    return s, z
+    z = -_round_ratio(xmin, xmin, xmax, bits)[0]
+    return s, z + 0.0
 
 
 def quantize(x, xmin, xmax, bits: int):
     """clip(round(x / s) + z, 0, 2^k - 1) for a group with the given extrema.
     Returns (codes, x / s before rounding)."""
     _, z = quant_params(xmin, xmax, bits)
-    pre = _ratio(x, xmin, xmax, bits)
-    return np.clip(np.rint(pre) + z, 0.0, float(2 ** bits - 1)), pre
+    r, pre = _round_ratio(x, xmin, xmax, bits)
+    return np.clip(r + z, 0.0, float(2 ** bits - 1)), pre
 
 
 def dequantize(code, s, z):

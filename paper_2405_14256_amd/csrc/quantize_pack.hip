@@ -111,6 +111,16 @@ __device__ inline float refined_div(float N, float R, float y) {
   const float r = fmaf(-q0, R, N);
   return fmaf(r, y, q0);
 }
+// x * qmax / R with the rounding error of the product x * qmax carried along, so
+// that ties stay exact for 24-bit x too (e.g. the minimum of a token row whose
+// maximum is its mirror image: exactly -qmax / 2).
+__device__ inline float refined_ratio(float x, float qmax, float R, float y) {
+  const float nh = x * qmax;
+  const float nl = fmaf(x, qmax, -nh);
+  const float q0 = nh * y;
+  const float r = fmaf(-q0, R, nh) + nl;
+  return fmaf(r, y, q0);
+}
 
 template <int DT, int BITS, int LAYOUT, bool TOKWISE>
 __global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
@@ -155,7 +165,7 @@ __global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
           float R = hi - lo;
           if (R == 0.f) R = QMAX;               // max == min: s := 1
           cs = R / QMAX;
-          cz = -rintf((lo * QMAX) / R);
+          cz = -rintf(refined_ratio(lo, QMAX, R, 1.f / R));
           p0[j][i] = 1.f / R;
           p1[j][i] = cz;
           p2[j][i] = R;
@@ -240,7 +250,7 @@ __global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
         float R = tmax[v4] - tmin[v4];
         if (R == 0.f) R = QMAX;                 // max == min: s := 1
         const float s = R / QMAX;
-        const float z = -rintf((tmin[v4] * QMAX) / R);
+        const float z = -rintf(refined_ratio(tmin[v4], QMAX, R, 1.f / R));
         rng[v4] = R;
         inv_r[v4] = 1.f / R;
         zt[v4] = z;
@@ -264,8 +274,9 @@ __global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
         for (int i = 0; i < 8; ++i) {
           // Eq. 5: round(x / s) first, then + z, then clip
           float t;
-          if constexpr (TOKWISE) t = rintf(refined_div(val[v4][j][i] * QMAX, rng[v4], inv_r[v4])) + zt[v4];
-          else t = rintf(refined_div(val[v4][j][i] * QMAX, p2[j][i], p0[j][i])) + p1[j][i];
+          if constexpr (TOKWISE) t = rintf(refined_ratio(val[v4][j][i], QMAX, rng[v4], inv_r[v4])) + zt[v4];
+          else if constexpr (DT == ZC_F32) t = rintf(refined_ratio(val[v4][j][i], QMAX, p2[j][i], p0[j][i])) + p1[j][i];
+          else t = rintf(refined_div(val[v4][j][i] * QMAX, p2[j][i], p0[j][i])) + p1[j][i];   // x * qmax is exact
           t = __builtin_amdgcn_fmed3f(t, 0.f, QMAX);
           code[i] = tv ? (uint32_t)t : 0u;
         }

@@ -38,20 +38,31 @@ def test_hand_worked_example():
 
 
 def test_exact_ties_survive_a_coarse_grid():
-    """Values on a bf16-like grid that sit exactly halfway between two codes
-    must round half-to-even, whatever (max - min) / (2^k - 1) rounds to."""
-    lo, hi = -1.3125, 2.34375                       # range not a multiple of 15 ulps of anything nice
-    rng = hi - lo
-    n = np.arange(0, 15)
-    x = (n + 0.5) * rng / 15                        # exact ties in real arithmetic ...
-    x = x[(x * 15 / rng) == n[: len(x)] + 0.5]      # ... keep those that are exact in floating point too
-    assert len(x) >= 3
+    """Inputs on a dyadic grid that sit exactly halfway between two codes must
+    round half-to-even even when s = (max - min) / (2^k - 1) is not representable.
+    Range 0.625 at 4 bits: s = 1/24, x / s = 24 x, z = -round(-0.25 * 24) = 6."""
+    lo, hi = -0.25, 0.375
+    x = np.array([1, 3, 5, -1, -3]) / 16.0          # 24 x = 1.5, 4.5, 7.5, -1.5, -4.5
     codes, pre = zo.quantize(x, lo, hi, 4)
-    z = -np.rint(lo * 15 / rng)
-    assert np.array_equal(pre - np.floor(pre), np.full(len(x), 0.5))
-    lower = np.floor(pre)
-    even = np.where(lower % 2 == 0, lower, lower + 1)   # the even neighbour
-    assert np.array_equal(codes, np.clip(even + z, 0, 15))
+    assert zo.quant_params(lo, hi, 4)[1] == 6.0
+    assert list(codes) == [2 + 6, 4 + 6, 8 + 6, -2 + 6, -4 + 6]
+    # a family of ranges 5 * 2^-e * m (s not representable): ties at x = (2n+1) R / 30
+    for m in (3, 7, 11, 13):
+        R = 5.0 * m / 64
+        xs = np.array([(2 * n + 1) * R / 30 for n in (1, 4, 7)])        # exact dyadic values
+        c, _ = zo.quantize(xs, 0.0, R, 4)
+        assert list(c) == [2, 4, 8]
+
+
+def test_mirror_image_row_has_an_exact_zero_point():
+    """max = -min makes min/s exactly -(2^k-1)/2 in real arithmetic, whatever
+    the float products round to: z = 8 (half-to-even) at 4 bits, 2 at 2 bits."""
+    for v in (1.0 / 3.0, 0.1, 2.7182818284590451, 1e-3 / 7):
+        x = np.array([-v, 0.25 * v, v])
+        assert zo.quant_params(x.min(), x.max(), 4)[1] == 8.0
+        assert zo.quant_params(x.min(), x.max(), 2)[1] == 2.0
+        codes, _ = zo.quantize(x, x.min(), x.max(), 4)
+        assert codes[0] == 0 and codes[2] == 15
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4, 8])
