@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZipCache hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch of the
+LLaMA3-8B-shaped layer at 4k context (the configuration the metric is quoted
+on): probe saliency -> salient split -> quantize-pack K and V -> the
+configuration's decode steps over the packed cache, the full-precision tail
+growing one token per step and being re-compressed after 100 tokens
+(probe saliency with the decode-time normalisers, split, quantize-pack).
+All inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is decode tokens per second of the whole step
+(compression included).  `roofline` describes the dominant kernel (packed
+decode attention): algorithmic bytes per launch over the average launch
+duration measured with HIP events.  `cpu_baseline` times the float64 oracle on
+the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2405_14256_amd import binding as zb          # noqa: E402
+from paper_2405_14256_amd import probes                 # noqa: E402
+from paper_2405_14256_amd.workloads import WORKLOADS, make_decode_step, make_prefill, to_f64  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+FLUSH_INTERVAL = 100
+
+
+class HotPath:
+    """Pre-allocated buffers and the call sequence of one step."""
+
+    def __init__(self, w, device="cuda", k_scheme="channel", v_scheme="cst"):
+        self.w = w
+        dev = torch.device(device)
+        inp = make_prefill(w)
+        self.cpu_inputs = inp
+        self.Q, self.K, self.V = (inp[n].to(dev) for n in ("Q", "K", "V"))
+        self.pos_np = probes.probe_positions(w.L, w.probe_ratio, w.seed)
+        self.pos = torch.from_numpy(self.pos_np).to(dev)
+        self.k = w.k_salient
+        S = w.decode_steps
+        self.S = S
+        dec = [make_decode_step(w, j) for j in range(S)]
+        self.cpu_decode = dec
+        # q of all steps as one [B, Hq, S, d] view; new keys / values of all steps laid out
+        # where the tail view will find them: [B, Hkv, S, d]
+        self.q_all = torch.stack([d["q"] for d in dec], dim=2).contiguous().to(dev)
+        self.tail_k = torch.stack([d["k_new"] for d in dec], dim=2).contiguous().to(dev)
+        self.tail_v = torch.stack([d["v_new"] for d in dec], dim=2).contiguous().to(dev)
+        self.n_flush = S // FLUSH_INTERVAL
+        self.k_tail = int(np.floor(w.salient_ratio * FLUSH_INTERVAL + 1e-9))
+        lib = zb.load()
+        cap_hi = lib.zc_arena_slots(self.k + self.n_flush * self.k_tail, 1 + self.n_flush)
+        cap_lo = lib.zc_arena_slots(w.L - self.k + self.n_flush * (FLUSH_INTERVAL - self.k_tail), 1 + self.n_flush)
+        mk = lambda scheme, layout: zb.PackedTensor(w.B, w.Hkv, w.d, cap_hi, cap_lo, w.bits_hi, w.bits_lo, scheme,
+                                                    layout, max_chunks=1 + self.n_flush, device=device, store_pos=True)
+        self.Kp, self.Vp = mk(k_scheme, zb.ZC_LAYOUT_ROW), mk(v_scheme, zb.ZC_LAYOUT_TGROUP)
+        f32 = dict(dtype=torch.float32, device=dev)
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.scores = torch.empty(w.B, w.L, **f32)
+        self.sal = torch.empty(w.B, self.k, **i32)
+        self.reg = torch.empty(w.B, w.L - self.k, **i32)
+        self.out = torch.empty(S, w.B, w.Hq, w.d, dtype=w.torch_dtype, device=dev)
+        self.lse = torch.empty(S, w.B, w.Hq, **f32)
+        self.probe_off_np = probes.decode_probe_offsets(FLUSH_INTERVAL, seed=w.seed)
+        self.probe_off = torch.from_numpy(self.probe_off_np).to(dev)
+        self.tail_scores = torch.empty(w.B, FLUSH_INTERVAL, **f32)
+        self.sal_t = torch.empty(w.B, self.k_tail, **i32)
+        self.reg_t = torch.empty(w.B, FLUSH_INTERVAL - self.k_tail, **i32)
+        self.lse_p = torch.empty(w.B, w.Hq, len(self.probe_off_np), **f32)
+        self.flush_rows = []
+        for f in range(self.n_flush):
+            r = (self.probe_off + f * FLUSH_INTERVAL).to(torch.int32)
+            self.flush_rows.append((r, r.long()))
+        self.decode_events = None     # filled by step(timed=True)
+        self.stage_events = None
+
+    # -- algorithmic traffic ---------------------------------------------------------
+    def decode_bytes(self, n_hi: int, n_lo: int, n_chunks: int, tail_len: int) -> float:
+        w = self.w
+        eb = 4 if w.dtype == "fp32" else 2
+        codes = 2 * w.B * w.W * (w.bits_hi * n_hi + w.bits_lo * n_lo) / 8          # K and V codes
+        tok = 8 * w.B * (n_hi + n_lo)                                              # (s, z) per token of V
+        chan = n_chunks * 2 * w.B * w.W * (8 + 4)                                  # K: s, z; V: c (per subset)
+        tail = 2 * eb * w.B * tail_len * w.W
+        qo = 2 * w.B * w.Hq * w.d * eb
+        return codes + tok + chan + tail + qo
+
+    def quant_bytes(self) -> float:
+        """Compulsory bytes of the prefill quantize-pack of K and V: read each
+        tensor once, write codes, token parameters (V) and channel parameters."""
+        w = self.w
+        eb = 4 if w.dtype == "fp32" else 2
+        read = 2 * eb * w.B * w.L * w.W
+        codes = 2 * w.B * w.W * (w.bits_hi * self.k + w.bits_lo * (w.L - self.k)) / 8
+        tok = 8 * w.B * w.L
+        chan = 2 * w.B * w.W * (8 + 4)
+        return read + codes + tok + chan
+
+    def probe_flops(self) -> float:
+        w = self.w
+        return 2.0 * w.d * float((self.pos_np.astype(np.int64) + 1).sum()) * w.Hq * w.B
+
+    # -- one pass of the hot path ------------------------------------------------------
+    def step(self, timed: bool = False):
+        w = self.w
+        ev = (lambda: torch.cuda.Event(enable_timing=True)) if timed else None
+        rec = []
+        qrec = []
+        self.Kp.reset(); self.Vp.reset()
+        if timed:
+            e0 = ev(); e0.record()
+        zb.zc_probe_saliency(self.Q, self.K, self.pos, scores=self.scores)
+        if timed:
+            e1 = ev(); e1.record()
+        zb.zc_select_salient(self.scores, self.k, self.sal, self.reg)
+        if timed:
+            e2 = ev(); e2.record()
+        zb.zc_quantize_pack(self.K, self.sal, self.reg, self.Kp)
+        zb.zc_quantize_pack(self.V, self.sal, self.reg, self.Vp)
+        if timed:
+            e3 = ev(); e3.record()
+            self.stage_events = (e0, e1, e2, e3)
+        base, T, n_packed = 0, 0, w.L
+        for j in range(self.S):
+            T += 1
+            if timed:
+                a = ev(); a.record()
+            zb.zc_decode_attention(self.q_all[:, :, j:j + 1], self.Kp, self.Vp, self.tail_k[:, :, base:],
+                                   self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse[j])
+            if timed:
+                b = ev(); b.record()
+                hi = sum(c[1] for c in self.Kp.chunks); lo = sum(c[3] for c in self.Kp.chunks)
+                rec.append((a, b, self.decode_bytes(hi, lo, self.Kp.c.n_chunks, T)))
+            if T == FLUSH_INTERVAL:
+                rows, rows_long = self.flush_rows[base // FLUSH_INTERVAL]
+                self.lse_p.copy_(self.lse.index_select(0, rows_long).permute(1, 2, 0))
+                tk = self.tail_k[:, :, base:base + T]
+                tv = self.tail_v[:, :, base:base + T]
+                zb.zc_probe_saliency(self.q_all, tk, self.probe_off, probe_rows=rows, lse_ext=self.lse_p,
+                                     scores=self.tail_scores)
+                zb.zc_select_salient(self.tail_scores, self.k_tail, self.sal_t, self.reg_t)
+                zb.zc_quantize_pack(tk, self.sal_t, self.reg_t, self.Kp, pos_offset=n_packed)
+                zb.zc_quantize_pack(tv, self.sal_t, self.reg_t, self.Vp, pos_offset=n_packed)
+                n_packed += T
+                base += T
+                T = 0
+        if timed:
+            self.decode_events = rec
+
+
+def cpu_baseline(hp: HotPath, decode_sample: int = 4):
+    """The oracle, as it stands, on the host cores: the whole prefill part of
+    one step plus `decode_sample` decode steps, extrapolated to the step's
+    decode count."""
+    from oracle import zipcache_oracle as zo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    w = hp.w
+    Q, K, V = (to_f64(hp.cpu_inputs[n]) for n in ("Q", "K", "V"))
+    t0 = time.perf_counter()
+    scores, _ = zo.saliency_scores(Q, K, hp.pos_np)
+    ck, cv, sal, reg = zo.compress_prefill(K, V, scores, hp.k, w.bits_hi, w.bits_lo)
+    t1 = time.perf_counter()
+    cache = zo.StreamingCache(Hkv=w.Hkv, chunks_K=[ck], chunks_V=[cv], n_packed=w.L)
+    n = min(decode_sample, hp.S)
+    for j in range(n):
+        d = hp.cpu_decode[j]
+        cache.step(to_f64(d["q"]), to_f64(d["k_new"]), to_f64(d["v_new"]), False)
+    t2 = time.perf_counter()
+    t_step = (t1 - t0) + (t2 - t1) / n * hp.S
+    return {"value": w.B * hp.S / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"float64 numpy oracle: probe scores + split + quantize of the full {w.name} prefill "
+                      f"({t1 - t0:.2f} s) and {n} of {hp.S} decode steps ({(t2 - t1) / n:.3f} s each), "
+                      f"extrapolated to one whole step"}, sal
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_4k")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    zb.load()
+    w = WORKLOADS[args.workload]
+    hp = HotPath(w)
+
+    # ---- warm-up (eager), then capture one step in a HIP graph ------------------------
+    for _ in range(max(args.warmup, 1)):
+        hp.step()
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            hp.step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            hp.step()
+        graph.replay()
+        torch.cuda.synchronize()
+    run = graph.replay if graph is not None else hp.step
+
+    # ---- timed region: exactly K steps ---------------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = w.B * hp.S * args.steps / dt
+
+    # ---- per-kernel pass: HIP events around every launch, same steps, eager ------------------
+    n_ev = min(args.steps, 5)
+    dec_ms, dec_bytes, stage = [], [], []
+    for _ in range(n_ev):
+        hp.step(timed=True)
+        torch.cuda.synchronize()
+        for a, b, nbytes in hp.decode_events:
+            dec_ms.append(a.elapsed_time(b)); dec_bytes.append(nbytes)
+        e0, e1, e2, e3 = hp.stage_events
+        stage.append((e0.elapsed_time(e1), e1.elapsed_time(e2), e2.elapsed_time(e3)))
+    dec_avg_ms = float(np.mean(dec_ms))
+    dec_avg_bytes = float(np.mean(dec_bytes))
+    achieved = dec_avg_bytes / (dec_avg_ms * 1e-3) / 1e9
+    st = np.mean(np.array(stage), axis=0)
+    quant_gbps = hp.quant_bytes() / (st[2] * 1e-3) / 1e9
+    probe_tflops = hp.probe_flops() / (st[0] * 1e-3) / 1e12
+
+    result = {
+        "metric": "KV quantize-pack GB/s + packed decode-attn tokens/s, LLaMA3-8B shape @4k",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "fp16": "f16", "fp32": "f32"}[w.dtype], "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.B, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
+                   "seq_len": w.L, "probe_rows": int(len(hp.pos_np)), "salient_tokens": hp.k,
+                   "bits": f"{w.bits_hi}/{w.bits_lo}", "decode_steps": hp.S, "flush_interval": FLUSH_INTERVAL,
+                   "k_scheme": "channel", "v_scheme": "cst",
+                   "launch": "eager" if graph is None else "hipgraph replay of one whole step"},
+        "components": {
+            "quantize_pack_GBps": quant_gbps, "quantize_pack_ms": float(st[2]),
+            "decode_attention_tokens_per_s": w.B / (dec_avg_ms * 1e-3), "decode_attention_ms": dec_avg_ms,
+            "probe_saliency_TFLOPs": probe_tflops, "probe_saliency_ms": float(st[0]),
+            "select_ms": float(st[1]),
+            "timing": "HIP events around each call, eager launches (so launch gaps are included)"},
+        "roofline": {"bound": "hbm", "kernel": "zc_decode_attention (k_decode_partial + k_decode_combine)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "bytes_per_launch": dec_avg_bytes, "avg_launch_ms": dec_avg_ms, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"], _ = cpu_baseline(hp)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
