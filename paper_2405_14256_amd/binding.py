@@ -117,12 +117,14 @@ def tensor4(t: torch.Tensor) -> zc_tensor4:
 _ws_cache = {}
 
 
-def _workspace(nbytes: int, device) -> torch.Tensor:
-    """A per-device scratch tensor, grown on demand and reused across calls."""
-    key = str(device)
+def _workspace(nbytes: int, device, tag: str = "scratch") -> torch.Tensor:
+    """A per-device, per-operation scratch tensor, zero-filled when allocated,
+    grown on demand and reused across calls (the decode workspace must start
+    zeroed and is left zeroed by every call)."""
+    key = (str(device), tag)
     cur = _ws_cache.get(key)
     if cur is None or cur.numel() < nbytes:
-        cur = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        cur = torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
         _ws_cache[key] = cur
     return cur
 
@@ -233,7 +235,7 @@ def zc_decode_attention(q: torch.Tensor, Kp: PackedTensor, Vp: PackedTensor,
     if out is None:
         out = torch.empty(B, Hq, D, dtype=q.dtype, device=q.device)
     need = lib.zc_decode_attention_workspace(B, Hq, D)
-    ws = _workspace(need, q.device)
+    ws = _workspace(need, q.device, "decode")
     tq = tensor4(q)
     ttk = tensor4(tail_k) if tail_len else None
     ttv = tensor4(tail_v) if tail_len else None

@@ -1,0 +1,48 @@
+// Kernel argument block shared by the decode-attention kernels.
+#pragma once
+
+#include "zc_common.hpp"
+
+namespace zc {
+
+constexpr int kTailUnit = 32;    // tail tokens per work unit of the MFMA decode kernel
+constexpr int kMaxSplits = 128;
+
+struct DecArgs {
+  const void* q;
+  int64_t q_sB, q_sH;
+  int B, Hq, Hkv, G, D;
+  const uint8_t* kc[2];
+  const float* k_ts[2];
+  const float* k_tz[2];
+  const float* k_cs;
+  const float* k_cz;
+  int k_tok;
+  const uint32_t* vc[2];
+  const float* v_ts[2];
+  const float* v_tz[2];
+  const float* v_cs;
+  const float* v_cz;
+  int v_tok;
+  int64_t cap[2];
+  int bits[2];
+  const int32_t* chunk_table;
+  int n_chunks;
+  const void* tail_k;
+  const void* tail_v;
+  int64_t tk_sB, tk_sH, tk_sL, tv_sB, tv_sH, tv_sL;
+  int tail_len;
+  float scale_log2;
+  int S, n_units;
+  int* counters;   // [B, Hkv] arrival counters, zero on entry and on exit
+  float* part_m;   // [B, Hq, S]
+  float* part_z;   // [B, Hq, S]
+  float* part_o;   // [B, Hq, S, D]
+  void* out;       // [B, Hq, D], q's dtype
+  float* lse_out;  // [B, Hq] or null
+};
+
+// Defined in decode_mfma.hip: the matrix-core kernel for 2- and 4-bit caches.
+int launch_decode_mfma(const DecArgs& a, int dtype, hipStream_t st);
+
+}  // namespace zc

@@ -15,44 +15,12 @@
 // q'[c] = q[c] * cs[c] * sm_scale * log2(e), and the output is
 //   o[c] = cs[c] * ( sum_t w[t] code[t,c] - sum_t w[t] tz[t] - cz[c] * sum_t w[t] ),  w[t] = p[t] * ts[t],
 // accumulated per chunk and subset (each has its own channel parameters).
-#include "zc_common.hpp"
+#include "decode_args.hpp"
 
 namespace zc {
 
 constexpr int kDecThreads = 256;
-constexpr int kTailBlock = 16;   // tail tokens per pseudo-block
-constexpr int kMaxSplits = 128;
-
-struct DecArgs {
-  const void* q;
-  int64_t q_sB, q_sH;
-  int B, Hq, Hkv, G, D;
-  const uint8_t* kc[2];
-  const float* k_ts[2];
-  const float* k_tz[2];
-  const float* k_cs;
-  const float* k_cz;
-  int k_tok;
-  const uint32_t* vc[2];
-  const float* v_ts[2];
-  const float* v_tz[2];
-  const float* v_cs;
-  const float* v_cz;
-  int v_tok;
-  int64_t cap[2];
-  int bits[2];
-  const int32_t* chunk_table;
-  int n_chunks;
-  const void* tail_k;
-  const void* tail_v;
-  int64_t tk_sB, tk_sH, tk_sL, tv_sB, tv_sH, tv_sL;
-  int tail_len;
-  float scale_log2;
-  int S, n_units;
-  float* part_m;   // [B, Hq, S]
-  float* part_z;   // [B, Hq, S]
-  float* part_o;   // [B, Hq, S, D]
-};
+constexpr int kTailBlock = 16;   // tail tokens per unit of the generic kernel
 
 template <int D>
 struct DecShared {
@@ -375,9 +343,11 @@ static int split_cap(int64_t B, int64_t Hq) {
 
 using namespace zc;
 
+static size_t counter_bytes(int64_t B, int64_t Hq) { return (size_t)align_up64(B * Hq * 4, 256); }
+
 extern "C" size_t zc_decode_attention_workspace(int64_t B, int64_t Hq, int64_t D) {
   if (B <= 0 || Hq <= 0 || D <= 0) return 0;
-  return (size_t)B * Hq * split_cap(B, Hq) * (D + 2) * sizeof(float);
+  return counter_bytes(B, Hq) + (size_t)B * Hq * split_cap(B, Hq) * (D + 2) * sizeof(float);
 }
 
 extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
@@ -412,7 +382,8 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   const size_t need = zc_decode_attention_workspace(q->B, q->H, q->D);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
 
-  // the chunk tables must agree; count the blocks
+  // the chunk tables must agree; count the work units
+  const bool mfma_path = (Kp->bits_hi == 2 || Kp->bits_hi == 4) && (Kp->bits_lo == 2 || Kp->bits_lo == 4);
   int64_t units = 0;
   for (int ci = 0; ci < Kp->n_chunks; ++ci) {
     const int32_t* rk = Kp->chunk_table_host + 4 * ci;
@@ -421,7 +392,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
       if (rk[i] != rv[i]) return ZC_ERR_INVALID_ARG;
     units += ceil_div64(rk[1], 4 * (32 / Kp->bits_hi)) + ceil_div64(rk[3], 4 * (32 / Kp->bits_lo));
   }
-  units += ceil_div64(tail_len, kTailBlock);
+  units += ceil_div64(tail_len, mfma_path ? kTailUnit : kTailBlock);
   if (units > 0x7fffffff) return ZC_ERR_UNSUPPORTED;
 
   DecArgs a;
@@ -447,15 +418,25 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)q->D) : sm_scale) * kLog2e;
   a.n_units = (int)units;
   int S = split_cap(q->B, q->H);
-  if (S > units) S = (int)(units > 0 ? units : 1);
+  if (mfma_path) {
+    // a workgroup is four waves; give every wave about two units before splitting further
+    const int64_t want = ceil_div64(units, 8);
+    if (S > want) S = (int)(want > 0 ? want : 1);
+  } else if (S > units) {
+    S = (int)(units > 0 ? units : 1);
+  }
   a.S = S;
-  float* wsf = reinterpret_cast<float*>(ws);
   const int64_t nq = q->B * q->H;
+  a.counters = reinterpret_cast<int*>(ws);
+  float* wsf = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + counter_bytes(q->B, q->H));
   a.part_m = wsf;
   a.part_z = wsf + nq * S;
   a.part_o = wsf + 2 * nq * S;
+  a.out = out;
+  a.lse_out = lse_out;
 
   hipStream_t st = (hipStream_t)stream;
+  if (mfma_path) return launch_decode_mfma(a, q->dtype, st);
 #define ZC_DEC(DT)                                                           \
   (q->D == 128 ? launch_decode<DT, 128>(a, out, lse_out, st) : launch_decode<DT, 64>(a, out, lse_out, st))
   if (q->dtype == ZC_F32) return ZC_DEC(ZC_F32);
