@@ -112,52 +112,66 @@ class HotPath:
         w = self.w
         return 2.0 * w.d * float((self.pos_np.astype(np.int64) + 1).sum()) * w.Hq * w.B
 
-    # -- one pass of the hot path ------------------------------------------------------
-    def step(self, timed: bool = False):
-        w = self.w
-        ev = (lambda: torch.cuda.Event(enable_timing=True)) if timed else None
-        rec = []
-        qrec = []
-        self.Kp.reset(); self.Vp.reset()
-        if timed:
-            e0 = ev(); e0.record()
-        zb.zc_probe_saliency(self.Q, self.K, self.pos, scores=self.scores)
-        if timed:
-            e1 = ev(); e1.record()
-        zb.zc_select_salient(self.scores, self.k, self.sal, self.reg)
-        if timed:
-            e2 = ev(); e2.record()
-        zb.zc_quantize_pack(self.K, self.sal, self.reg, self.Kp)
-        zb.zc_quantize_pack(self.V, self.sal, self.reg, self.Vp)
-        if timed:
-            e3 = ev(); e3.record()
-            self.stage_events = (e0, e1, e2, e3)
-        base, T, n_packed = 0, 0, w.L
-        for j in range(self.S):
-            T += 1
-            if timed:
-                a = ev(); a.record()
-            zb.zc_decode_attention(self.q_all[:, :, j:j + 1], self.Kp, self.Vp, self.tail_k[:, :, base:],
-                                   self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse[j])
-            if timed:
-                b = ev(); b.record()
-                hi = sum(c[1] for c in self.Kp.chunks); lo = sum(c[3] for c in self.Kp.chunks)
-                rec.append((a, b, self.decode_bytes(hi, lo, self.Kp.c.n_chunks, T)))
-            if T == FLUSH_INTERVAL:
-                rows, rows_long = self.flush_rows[base // FLUSH_INTERVAL]
+    # -- one pass of the hot path, as a list of stages -------------------------------------
+    def stages(self):
+        """[(name, fn, n_decode_calls, decode_bytes)] in execution order.  Calling the
+        functions in order performs one whole step (host bookkeeping of the packed
+        cache included), so they can be run eagerly or captured one by one."""
+        w = self
+        out = []
+
+        def probe():
+            self.Kp.reset(); self.Vp.reset()
+            zb.zc_probe_saliency(self.Q, self.K, self.pos, scores=self.scores)
+
+        def select():
+            zb.zc_select_salient(self.scores, self.k, self.sal, self.reg)
+
+        def quantize():
+            zb.zc_quantize_pack(self.K, self.sal, self.reg, self.Kp)
+            zb.zc_quantize_pack(self.V, self.sal, self.reg, self.Vp)
+
+        out += [("probe", probe, 0, 0.0), ("select", select, 0, 0.0), ("quantize", quantize, 0, 0.0)]
+
+        def decode_range(j0, j1, base):
+            def fn():
+                nbytes = 0.0
+                for j in range(j0, j1):
+                    T = j - base + 1
+                    zb.zc_decode_attention(self.q_all[:, :, j:j + 1], self.Kp, self.Vp, self.tail_k[:, :, base:],
+                                           self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse[j])
+                    hi = sum(c[1] for c in self.Kp.chunks); lo = sum(c[3] for c in self.Kp.chunks)
+                    nbytes += self.decode_bytes(hi, lo, self.Kp.c.n_chunks, T)
+                fn.nbytes = nbytes
+            return fn
+
+        def flush_at(f):
+            def fn():
+                base = f * FLUSH_INTERVAL
+                rows, rows_long = self.flush_rows[f]
                 self.lse_p.copy_(self.lse.index_select(0, rows_long).permute(1, 2, 0))
-                tk = self.tail_k[:, :, base:base + T]
-                tv = self.tail_v[:, :, base:base + T]
+                tk = self.tail_k[:, :, base:base + FLUSH_INTERVAL]
+                tv = self.tail_v[:, :, base:base + FLUSH_INTERVAL]
                 zb.zc_probe_saliency(self.q_all, tk, self.probe_off, probe_rows=rows, lse_ext=self.lse_p,
                                      scores=self.tail_scores)
                 zb.zc_select_salient(self.tail_scores, self.k_tail, self.sal_t, self.reg_t)
+                n_packed = self.w.L + base
                 zb.zc_quantize_pack(tk, self.sal_t, self.reg_t, self.Kp, pos_offset=n_packed)
                 zb.zc_quantize_pack(tv, self.sal_t, self.reg_t, self.Vp, pos_offset=n_packed)
-                n_packed += T
-                base += T
-                T = 0
-        if timed:
-            self.decode_events = rec
+            return fn
+
+        j = 0
+        for f in range(self.n_flush):
+            out.append(("decode", decode_range(j, (f + 1) * FLUSH_INTERVAL, f * FLUSH_INTERVAL), FLUSH_INTERVAL, None))
+            out.append(("flush", flush_at(f), 0, 0.0))
+            j = (f + 1) * FLUSH_INTERVAL
+        if j < self.S:
+            out.append(("decode", decode_range(j, self.S, self.n_flush * FLUSH_INTERVAL), self.S - j, None))
+        return out
+
+    def step(self):
+        for _, fn, _, _ in self.stages():
+            fn()
 
 
 def cpu_baseline(hp: HotPath, decode_sample: int = 4):
@@ -208,11 +222,12 @@ def main():
     w = WORKLOADS[args.workload]
     hp = HotPath(w)
 
-    # ---- warm-up (eager), then capture one step in a HIP graph ------------------------
+    # ---- warm-up (eager), then capture every stage of the step in its own HIP graph ----------
     for _ in range(max(args.warmup, 1)):
         hp.step()
     torch.cuda.synchronize()
-    graph = None
+    stages = hp.stages()
+    runners = []
     if not args.no_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -220,39 +235,46 @@ def main():
             hp.step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            hp.step()
-        graph.replay()
+        for name, fn, ncalls, _ in stages:      # captured in execution order: the host-side
+            g = torch.cuda.CUDAGraph()          # cache bookkeeping advances as in a real step
+            with torch.cuda.graph(g):
+                fn()
+            runners.append(g.replay)
         torch.cuda.synchronize()
-    run = graph.replay if graph is not None else hp.step
+        for r in runners:
+            r()
+        torch.cuda.synchronize()
+    else:
+        runners = [fn for _, fn, _, _ in stages]
+        hp.step()
+    dec_bytes_step = sum(getattr(fn, "nbytes", 0.0) for name, fn, _, _ in stages if name == "decode")
+    n_dec = sum(nc for name, _, nc, _ in stages if name == "decode")
 
-    # ---- timed region: exactly K steps ---------------------------------------------------
+    # ---- timed region: exactly K steps; HIP events between the stages -----------------------
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
+    for k in range(args.steps):
+        ev[k][0].record()
+        for i, r in enumerate(runners):
+            r()
+            ev[k][i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = w.B * hp.S * args.steps / dt
 
-    # ---- per-kernel pass: HIP events around every launch, same steps, eager ------------------
-    n_ev = min(args.steps, 5)
-    dec_ms, dec_bytes, stage = [], [], []
-    for _ in range(n_ev):
-        hp.step(timed=True)
-        torch.cuda.synchronize()
-        for a, b, nbytes in hp.decode_events:
-            dec_ms.append(a.elapsed_time(b)); dec_bytes.append(nbytes)
-        e0, e1, e2, e3 = hp.stage_events
-        stage.append((e0.elapsed_time(e1), e1.elapsed_time(e2), e2.elapsed_time(e3)))
-    dec_avg_ms = float(np.mean(dec_ms))
-    dec_avg_bytes = float(np.mean(dec_bytes))
+    stage_ms = {}
+    for k in range(args.steps):
+        for i, (name, _, _, _) in enumerate(stages):
+            stage_ms[name] = stage_ms.get(name, 0.0) + ev[k][i].elapsed_time(ev[k][i + 1])
+    stage_ms = {n: v / args.steps for n, v in stage_ms.items()}
+    dec_avg_ms = stage_ms["decode"] / n_dec
+    dec_avg_bytes = dec_bytes_step / n_dec
     achieved = dec_avg_bytes / (dec_avg_ms * 1e-3) / 1e9
-    st = np.mean(np.array(stage), axis=0)
-    quant_gbps = hp.quant_bytes() / (st[2] * 1e-3) / 1e9
-    probe_tflops = hp.probe_flops() / (st[0] * 1e-3) / 1e12
+    quant_gbps = hp.quant_bytes() / (stage_ms["quantize"] * 1e-3) / 1e9
+    probe_tflops = hp.probe_flops() / (stage_ms["probe"] * 1e-3) / 1e12
+    graph = None if args.no_graph else True
 
     result = {
         "metric": "KV quantize-pack GB/s + packed decode-attn tokens/s, LLaMA3-8B shape @4k",
@@ -263,16 +285,16 @@ def main():
                    "seq_len": w.L, "probe_rows": int(len(hp.pos_np)), "salient_tokens": hp.k,
                    "bits": f"{w.bits_hi}/{w.bits_lo}", "decode_steps": hp.S, "flush_interval": FLUSH_INTERVAL,
                    "k_scheme": "channel", "v_scheme": "cst",
-                   "launch": "eager" if graph is None else "hipgraph replay of one whole step"},
+                   "launch": "eager" if graph is None else "hipgraph replay, one graph per stage of the step"},
         "components": {
-            "quantize_pack_GBps": quant_gbps, "quantize_pack_ms": float(st[2]),
-            "decode_attention_tokens_per_s": w.B / (dec_avg_ms * 1e-3), "decode_attention_ms": dec_avg_ms,
-            "probe_saliency_TFLOPs": probe_tflops, "probe_saliency_ms": float(st[0]),
-            "select_ms": float(st[1]),
-            "timing": "HIP events around each call, eager launches (so launch gaps are included)"},
-        "roofline": {"bound": "hbm", "kernel": "zc_decode_attention (k_decode_partial + k_decode_combine)",
+            "quantize_pack_GBps": quant_gbps, "quantize_pack_ms": stage_ms["quantize"],
+            "decode_attention_tokens_per_s": w.B / (dec_avg_ms * 1e-3), "decode_attention_us_per_launch": dec_avg_ms * 1e3,
+            "probe_saliency_TFLOPs": probe_tflops, "probe_saliency_ms": stage_ms["probe"],
+            "select_ms": stage_ms["select"], "flush_ms": stage_ms.get("flush", 0.0),
+            "timing": "HIP events between the stage graphs inside the timed region"},
+        "roofline": {"bound": "hbm", "kernel": "k_decode_mfma (zc_decode_attention)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "bytes_per_launch": dec_avg_bytes, "avg_launch_ms": dec_avg_ms, "traffic": None},
+                     "bytes_per_launch": dec_avg_bytes, "avg_launch_us": dec_avg_ms * 1e3, "traffic": None},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"], _ = cpu_baseline(hp)

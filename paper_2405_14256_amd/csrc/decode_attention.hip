@@ -422,6 +422,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     // a workgroup is four waves; give every wave about two units before splitting further
     const int64_t want = ceil_div64(units, 8);
     if (S > want) S = (int)(want > 0 ? want : 1);
+    if (S > 16) S = 16;     // the last workgroup reads at most 16 partials per head
   } else if (S > units) {
     S = (int)(units > 0 ? units : 1);
   }

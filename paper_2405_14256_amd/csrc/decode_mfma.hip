@@ -3,11 +3,13 @@
 //
 // Work unit: one block of the packed cache (32 slots at 4 bits, 64 at 2 bits:
 // D*16 bytes of K codes and as many of V codes) or 32 tokens of the
-// full-precision tail.  Every wave takes a contiguous run of units and keeps
-// its own online-softmax state in registers; there is no barrier in the main
-// loop.  The four waves of a workgroup merge through LDS, the workgroups of one
-// (batch, KV head) through a partial buffer that the last workgroup to arrive
-// reduces (arrival counter, reset to zero by that workgroup).
+// full-precision tail.  A workgroup takes a contiguous run of units; for every
+// segment (chunk x subset, or the tail) in that run its four waves build the
+// query operand together, then each wave walks its share of the blocks with its
+// own online-softmax state in registers, loading block i+1 while it computes
+// block i; there is no barrier inside that loop.  The waves merge through LDS,
+// the workgroups of one (batch, KV head) through a partial buffer that the last
+// workgroup to arrive reduces (arrival counter, reset to zero by that workgroup).
 //
 // Both products run on v_mfma_f32_16x16x32_f16 with the codes as one operand:
 //   logits  D[token][n]   = sum_c code[token][c] * q'[n][c]      (A = K codes, ROW layout)
@@ -92,12 +94,18 @@ __device__ inline float grp_sum(float x) {
   return x + __shfl_xor(x, 32);
 }
 
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr int kCombineMax = 16;   // most workgroups per (batch, KV head) on this path
+
 template <int DT, int D>
 __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
   constexpr int KS = D / 32;     // k-steps of the logit product
   constexpr int NR = D / 64;     // 16-byte V loads per lane and block
   constexpr int MG = ZC_MAX_GROUP;
   __shared__ float qs[MG][D];             // q * sm_scale * log2(e)
+  __shared__ u4 sqB[KS][64];              // query operand of the current segment
+  __shared__ float ssum[2][KS][64];
   __shared__ float mO[4][MG][D];
   __shared__ float mM[4][MG], mZ[4][MG];
   __shared__ float ptile[4][MG][kTailUnit];
@@ -115,7 +123,7 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
     const int gg = i / D, c = i % D;
     qs[gg][c] = load1<DT>(a.q, (int64_t)b * a.q_sB + (int64_t)(hk * G + gg) * a.q_sH + c) * a.scale_log2;
   }
-  __syncthreads();
+  // (the first barrier of the first segment orders these writes before their readers)
 
   // running state of this wave
   float m_run = -INFINITY, z_part = 0.f;
@@ -130,17 +138,14 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
 #pragma unroll
     for (int r = 0; r < NR; ++r) Ot[gg][r] = 0.f;
 
-  const int wid = s * 4 + wave, nw = a.S * 4;
-  const int u0 = (int)((int64_t)a.n_units * wid / nw), u1 = (int)((int64_t)a.n_units * (wid + 1) / nw);
+  const int u0 = (int)((int64_t)a.n_units * s / a.S), u1 = (int)((int64_t)a.n_units * (s + 1) / a.S);
 
-  // Softmax bookkeeping shared by packed blocks and tail units.  `U` are the
-  // NT*4 dot products of this lane (tokens 16 j + 4 grp + v of the unit), `valid`
-  // their masks.  Returns the weights w (0 where masked) and updates the state.
-  // sw / a1 / a2 accumulate sum(w''), sum(w tz), sum(w).
+  // When the running maximum of a head grows, everything accumulated so far is
+  // rescaled; rare after the first blocks, so it sits behind a wave-uniform branch.
   auto rescale_to = [&](float m_new, float& sw, float& a1, float& a2, f4 (*acc)[4]) {
     const bool changed = nvalid && (m_new > m_run);
     if (__any(changed)) {
-      const float fac = (m_run > -INFINITY) ? exp2f(m_run - m_new) : 0.f;
+      const float fac = (m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
       z_part *= fac; sw *= fac; a1 *= fac; a2 *= fac;
       const float f0 = __shfl(fac, 2 * g0), f1 = __shfl(fac, 2 * g1);
 #pragma unroll
@@ -162,6 +167,52 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
     m_run = fmaxf(m_run, m_new);
   };
 
+  // The query operand of a segment, built once per workgroup: wave w computes
+  // k-step w.  MODE 4 / 2: codes of that width, q' = q cs SC in the channel order
+  // the unpacked K words have; MODE 0: the tail, q itself in natural order.
+  // Returns the operand registers and sum(q''), sum(q'' cz) over all channels.
+  auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, u4 (&qB)[KS], float& sumqq, float& sumqqcz) {
+    constexpr int MODE = decltype(mode_c)::value;
+    constexpr float SC = MODE == 4 ? 16.f : (MODE == 2 ? 4.f : 1.f);
+    __syncthreads();     // qs written; sqB / ssum of the previous segment no longer read
+    for (int ks = wave; ks < KS; ks += 4) {
+      uint32_t regs[4];
+      float sq = 0.f, sqz = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        _Float16 hv[2];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          int c;
+          if constexpr (MODE == 4) c = grp * (D / 4) + 8 * ks + i + 4 * half;
+          else if constexpr (MODE == 2) c = grp * (D / 4) + 16 * (ks >> 1) + 4 * (ks & 1) + i + 8 * half;
+          else c = 32 * ks + 8 * grp + 2 * i + half;
+          float qv = nvalid ? qs[g][c] : 0.f;
+          if constexpr (MODE != 0) qv *= kcs[c] * SC;
+          float rep;
+          hv[half] = split_part(qv, part, rep);
+          sq += rep;
+          if constexpr (MODE != 0) sqz += rep * kcz[c];
+        }
+        regs[i] = pack_h2(hv[0], hv[1]);
+      }
+      u4 t; t.x = regs[0]; t.y = regs[1]; t.z = regs[2]; t.w = regs[3];
+      sqB[ks][lane] = t;
+      ssum[0][ks][lane] = sq;
+      ssum[1][ks][lane] = sqz;
+    }
+    __syncthreads();
+    sumqq = 0.f; sumqqcz = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qB[ks] = sqB[ks][lane];
+      sumqq += ssum[0][ks][lane];
+      sumqqcz += ssum[1][ks][lane];
+    }
+    sumqq = grp_sum(sumqq);
+    sumqqcz = grp_sum(sumqqcz);
+  };
+
   int cursor = 0;
   // ---------------- packed segments --------------------------------------------------
   auto segment = [&](auto bits_c, int ci, int sub, int begin, int len, int lo, int hi) {
@@ -170,35 +221,48 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
     constexpr float SC = (BITS == 4) ? 16.f : 4.f;
     constexpr int KW = D * BITS / 128;       // 32-bit words of K codes per lane and token
     const int64_t chan_off = ((int64_t)(ci * 2 + sub) * a.B + b) * (a.Hkv * D) + hk * D;
-    const float* kcs = a.k_cs + chan_off;
-    const float* kcz = a.k_cz + chan_off;
+    const int wlo = lo + (hi - lo) * wave / 4, whi = lo + (hi - lo) * (wave + 1) / 4;
 
-    // ---- operand q' (B of the logit product) and its sums ----
-    u4 qB[KS];
-    float sumqq = 0.f, sumqqcz = 0.f;
+    const int64_t bh = (int64_t)b * a.Hkv + hk;
+    const int64_t nblk = a.cap[sub] / TB;
+    const uint8_t* kbase = a.kc[sub] + bh * a.cap[sub] * (D * BITS / 8) + grp * (KW * 4);
+    const int64_t tokbase = (int64_t)b * a.cap[sub];
+
+    struct Buf {
+      uint32_t kw[NT][KW];
+      uint4 vw[NR];
+      float4 kts[NT], ktz[NT], vts[NT], vtz[NT];
+    };
+    auto load_block = [&](int blk, Buf& bf) {
+      const int slot0 = begin + blk * TB;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint32_t regs[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        _Float16 hv[2];
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          int c;
-          if constexpr (BITS == 4) c = grp * (D / 4) + 8 * ks + i + 4 * half;
-          else c = grp * (D / 4) + 16 * (ks >> 1) + ((ks & 1) ? 4 : 0) + i + 8 * half;
-          const float qv = nvalid ? qs[g][c] * kcs[c] * SC : 0.f;
-          float rep;
-          hv[half] = split_part(qv, part, rep);
-          sumqq += rep;
-          sumqqcz += rep * kcz[c];
+      for (int j = 0; j < NT; ++j) {
+        const uint32_t* kp = reinterpret_cast<const uint32_t*>(kbase + (int64_t)(slot0 + 16 * j + n) * (D * BITS / 8));
+        if constexpr (KW == 4) { const uint4 t = *reinterpret_cast<const uint4*>(kp); bf.kw[j][0] = t.x; bf.kw[j][1] = t.y; bf.kw[j][2] = t.z; bf.kw[j][3] = t.w; }
+        else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); bf.kw[j][0] = t.x; bf.kw[j][1] = t.y; }
+        else { bf.kw[j][0] = *kp; }
+        const int64_t to = tokbase + slot0 + 16 * j + 4 * grp;
+        if (a.k_tok) {
+          bf.kts[j] = *reinterpret_cast<const float4*>(a.k_ts[sub] + to);
+          bf.ktz[j] = *reinterpret_cast<const float4*>(a.k_tz[sub] + to);
         }
-        regs[i] = pack_h2(hv[0], hv[1]);
+        if (a.v_tok) {
+          bf.vts[j] = *reinterpret_cast<const float4*>(a.v_ts[sub] + to);
+          bf.vtz[j] = *reinterpret_cast<const float4*>(a.v_tz[sub] + to);
+        }
       }
-      qB[ks].x = regs[0]; qB[ks].y = regs[1]; qB[ks].z = regs[2]; qB[ks].w = regs[3];
-    }
-    sumqq = grp_sum(sumqq);
-    sumqqcz = grp_sum(sumqqcz);
+      const uint32_t* vbase = a.vc[sub] + ((bh * nblk + slot0 / TB) * 4 + grp) * D;
+#pragma unroll
+      for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const uint4*>(vbase + 4 * (n + 16 * r));
+    };
+
+    Buf cur;
+    if (wlo < whi) load_block(wlo, cur);      // in flight while the operand is built
+
+    u4 qB[KS];
+    float sumqq, sumqqcz;
+    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, qB, sumqq, sumqqcz);
+    if (wlo >= whi) return;
     const float Aq = sumqq / SC, Bq = sumqqcz / SC;
 
     f4 acc[NR][4];
@@ -208,81 +272,60 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
       for (int j = 0; j < 4; ++j) acc[r][j] = f4{0.f, 0.f, 0.f, 0.f};
     float sw = 0.f, a1 = 0.f, a2 = 0.f;
 
-    const int64_t bh = (int64_t)b * a.Hkv + hk;
-    const int64_t nblk = a.cap[sub] / TB;
-    const uint8_t* kbase = a.kc[sub] + bh * a.cap[sub] * (D * BITS / 8) + grp * (KW * 4);
-    for (int blk = lo; blk < hi; ++blk) {
-      const int slot0 = begin + blk * TB;
+    for (int blk = wlo; blk < whi; ++blk) {
+      Buf nxt = cur;
+      if (blk + 1 < whi) load_block(blk + 1, nxt);
       const int ntok = min(TB, len - blk * TB);
-      // ---- logits ----
-      float U[NT][4];
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const uint32_t* kp = reinterpret_cast<const uint32_t*>(kbase + (int64_t)(slot0 + 16 * j + n) * (D * BITS / 8));
-        uint32_t kw[KW];
-        if constexpr (KW == 4) { const uint4 t = *reinterpret_cast<const uint4*>(kp); kw[0] = t.x; kw[1] = t.y; kw[2] = t.z; kw[3] = t.w; }
-        else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); kw[0] = t.x; kw[1] = t.y; }
-        else { kw[0] = *kp; }
-        f4 sacc = f4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (BITS == 4) {
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack4(kw[ks]), qB[ks], sacc);
-        } else {
-#pragma unroll
-          for (int wd = 0; wd < KW; ++wd) {
-            u4 ua, ub;
-            unpack2(kw[wd], ua, ub);
-            sacc = mfma16(ua, qB[2 * wd], sacc);
-            sacc = mfma16(ub, qB[2 * wd + 1], sacc);
-          }
-        }
-        // value + residual/2^11 of the two columns of this head, minus the "1" terms
-        const float own[4] = {sacc.x, sacc.y, sacc.z, sacc.w};
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const float other = xor1(own[v]);
-          const float hi_v = part ? other : own[v], lo_v = part ? own[v] : other;
-          U[j][v] = hi_v + lo_v * kLoInv - sumqq;
-        }
-      }
-      // ---- logit = ts (dot - tz Aq - Bq), mask, running max ----
+      // ---- logits: dot = (value + residual / 2^11 of the head's two columns) - the "1" terms ----
       float lg[NT][4];
       float lmax = -INFINITY;
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        const int tb = 16 * j + 4 * grp;
+        f4 sacc = f4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (BITS == 4) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack4(cur.kw[j][ks]), qB[ks], sacc);
+        } else {
+#pragma unroll
+          for (int wd = 0; wd < KW; ++wd) {
+            u4 ua, ub;
+            unpack2(cur.kw[j][wd], ua, ub);
+            sacc = mfma16(ua, qB[2 * wd], sacc);
+            sacc = mfma16(ub, qB[2 * wd + 1], sacc);
+          }
+        }
+        const float own[4] = {sacc.x, sacc.y, sacc.z, sacc.w};
         float ts[4] = {1.f, 1.f, 1.f, 1.f}, tz[4] = {0.f, 0.f, 0.f, 0.f};
         if (a.k_tok) {
-          const float4 s4 = *reinterpret_cast<const float4*>(a.k_ts[sub] + (int64_t)b * a.cap[sub] + slot0 + tb);
-          const float4 z4 = *reinterpret_cast<const float4*>(a.k_tz[sub] + (int64_t)b * a.cap[sub] + slot0 + tb);
-          ts[0] = s4.x; ts[1] = s4.y; ts[2] = s4.z; ts[3] = s4.w;
-          tz[0] = z4.x; tz[1] = z4.y; tz[2] = z4.z; tz[3] = z4.w;
+          ts[0] = cur.kts[j].x; ts[1] = cur.kts[j].y; ts[2] = cur.kts[j].z; ts[3] = cur.kts[j].w;
+          tz[0] = cur.ktz[j].x; tz[1] = cur.ktz[j].y; tz[2] = cur.ktz[j].z; tz[3] = cur.ktz[j].w;
         }
+        const int tb = 16 * j + 4 * grp;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const float x = ts[v] * (U[j][v] - tz[v] * Aq - Bq);
+          const float other = xor1(own[v]);
+          const float hi_v = part ? other : own[v], lo_v = part ? own[v] : other;
+          const float dot = hi_v + lo_v * kLoInv - sumqq;
+          const float x = ts[v] * (dot - tz[v] * Aq - Bq);
           lg[j][v] = (tb + v < ntok) ? x : -INFINITY;
           lmax = fmaxf(lmax, lg[j][v]);
         }
       }
-      const float m_new = fmaxf(m_run, grp_max(lmax));
-      rescale_to(m_new, sw, a1, a2, acc);
-      // ---- weights and the A operand of the output product ----
+      rescale_to(fmaxf(m_run, grp_max(lmax)), sw, a1, a2, acc);
+      // ---- weights w = p ts, and the A operand of the output product ----
       _Float16 wh[NT][4];
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        const int tb = 16 * j + 4 * grp;
         float ts[4] = {1.f, 1.f, 1.f, 1.f}, tz[4] = {0.f, 0.f, 0.f, 0.f};
         if (a.v_tok) {
-          const float4 s4 = *reinterpret_cast<const float4*>(a.v_ts[sub] + (int64_t)b * a.cap[sub] + slot0 + tb);
-          const float4 z4 = *reinterpret_cast<const float4*>(a.v_tz[sub] + (int64_t)b * a.cap[sub] + slot0 + tb);
-          ts[0] = s4.x; ts[1] = s4.y; ts[2] = s4.z; ts[3] = s4.w;
-          tz[0] = z4.x; tz[1] = z4.y; tz[2] = z4.z; tz[3] = z4.w;
+          ts[0] = cur.vts[j].x; ts[1] = cur.vts[j].y; ts[2] = cur.vts[j].z; ts[3] = cur.vts[j].w;
+          tz[0] = cur.vtz[j].x; tz[1] = cur.vtz[j].y; tz[2] = cur.vtz[j].z; tz[3] = cur.vtz[j].w;
         }
+        const int tb = 16 * j + 4 * grp;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const bool ok = (tb + v < ntok) && nvalid && (m_run > -INFINITY);
-          const float p = ok ? exp2f(lg[j][v] - m_run) : 0.f;
+          const float p = ok ? fast_exp2(lg[j][v] - m_run) : 0.f;
           const float w = ok ? p * ts[v] : 0.f;
           z_part += p;
           a1 += ok ? w * tz[v] : 0.f;
@@ -293,29 +336,26 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
         }
       }
       // ---- output product ----
-      const uint32_t* vbase = a.vc[sub] + ((bh * nblk + slot0 / TB) * 4 + grp) * D;
       if constexpr (BITS == 4) {
         u4 pA;
         pA.x = pack_h2(wh[0][0], wh[1][0]); pA.y = pack_h2(wh[0][1], wh[1][1]);
         pA.z = pack_h2(wh[0][2], wh[1][2]); pA.w = pack_h2(wh[0][3], wh[1][3]);
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
-          const uint4 vw = *reinterpret_cast<const uint4*>(vbase + 4 * (n + 16 * r));
-          acc[r][0] = mfma16(pA, unpack4(vw.x), acc[r][0]);
-          acc[r][1] = mfma16(pA, unpack4(vw.y), acc[r][1]);
-          acc[r][2] = mfma16(pA, unpack4(vw.z), acc[r][2]);
-          acc[r][3] = mfma16(pA, unpack4(vw.w), acc[r][3]);
+          acc[r][0] = mfma16(pA, unpack4(cur.vw[r].x), acc[r][0]);
+          acc[r][1] = mfma16(pA, unpack4(cur.vw[r].y), acc[r][1]);
+          acc[r][2] = mfma16(pA, unpack4(cur.vw[r].z), acc[r][2]);
+          acc[r][3] = mfma16(pA, unpack4(cur.vw[r].w), acc[r][3]);
         }
       } else {
-        u4 pA, pB;   // tiles (0, 1) and tiles (2, 3)
+        u4 pA, pB;   // slot tiles (0, 1) and (2, 3)
         pA.x = pack_h2(wh[0][0], wh[1][0]); pA.y = pack_h2(wh[0][1], wh[1][1]);
         pA.z = pack_h2(wh[0][2], wh[1][2]); pA.w = pack_h2(wh[0][3], wh[1][3]);
         pB.x = pack_h2(wh[2][0], wh[3][0]); pB.y = pack_h2(wh[2][1], wh[3][1]);
         pB.z = pack_h2(wh[2][2], wh[3][2]); pB.w = pack_h2(wh[2][3], wh[3][3]);
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
-          const uint4 vw = *reinterpret_cast<const uint4*>(vbase + 4 * (n + 16 * r));
-          const uint32_t ww[4] = {vw.x, vw.y, vw.z, vw.w};
+          const uint32_t ww[4] = {cur.vw[r].x, cur.vw[r].y, cur.vw[r].z, cur.vw[r].w};
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             u4 ua, ub;
@@ -325,6 +365,7 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
           }
         }
       }
+      cur = nxt;
     }
     // ---- fold the segment into O ----
     // sum_t w code = acc_value + acc_residual / 2^11 - sum_t w'',  w'' = SC w
@@ -370,27 +411,22 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
     const int seg0 = cursor;
     const int lo = max(u0, seg0) - seg0, hi = min(u1, seg0 + n_tail) - seg0;
     if (lo < hi) {
-      // operand q (no channel scale), natural channel order: register i = channels
-      // 32 ks + 8 grp + 2 i, + 1
+      const int wlo = lo + (hi - lo) * wave / 4, whi = lo + (hi - lo) * (wave + 1) / 4;
       u4 qB[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        uint32_t regs[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int c = 32 * ks + 8 * grp + 2 * i;
-          float rep;
-          const _Float16 h0 = split_part(nvalid ? qs[g][c] : 0.f, part, rep);
-          const _Float16 h1 = split_part(nvalid ? qs[g][c + 1] : 0.f, part, rep);
-          regs[i] = pack_h2(h0, h1);
-        }
-        qB[ks].x = regs[0]; qB[ks].y = regs[1]; qB[ks].z = regs[2]; qB[ks].w = regs[3];
-      }
+      float dummy0, dummy1;
+      build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, qB, dummy0, dummy1);
       const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
       const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
-      for (int tu = lo; tu < hi; ++tu) {
+      for (int tu = wlo; tu < whi; ++tu) {
         const int t0 = tu * kTailUnit;
         const int ntok = min(kTailUnit, a.tail_len - t0);
+        // values of the unit: every lane owns channels lane + 64 r (issued early)
+        float vv[NR][kTailUnit];
+#pragma unroll
+        for (int t = 0; t < kTailUnit; ++t)
+#pragma unroll
+          for (int r = 0; r < NR; ++r)
+            vv[r][t] = (t < ntok) ? load1<DT>(a.tail_v, vb + (int64_t)(t0 + t) * a.tv_sL + lane + 64 * r) : 0.f;
         float U[2][4];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -432,28 +468,30 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
             lmax = fmaxf(lmax, U[j][v]);
           }
         float dsw = 0.f, da1 = 0.f, da2 = 0.f;
-        const float m_new = fmaxf(m_run, grp_max(lmax));
-        rescale_to(m_new, dsw, da1, da2, nullptr);
+        rescale_to(fmaxf(m_run, grp_max(lmax)), dsw, da1, da2, nullptr);
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const bool ok = (16 * j + 4 * grp + v < ntok) && nvalid && (m_run > -INFINITY);
-            const float p = ok ? exp2f(U[j][v] - m_run) : 0.f;
+            const float p = ok ? fast_exp2(U[j][v] - m_run) : 0.f;
             z_part += p;
             if (nvalid && part == 0) ptile[wave][g][16 * j + 4 * grp + v] = p;
           }
-        // weighted sum of the tail values: every lane owns channels lane + 64 r
-        for (int t = 0; t < ntok; ++t) {
-          float vv[NR];
+        // weighted sum of the tail values
 #pragma unroll
-          for (int r = 0; r < NR; ++r) vv[r] = load1<DT>(a.tail_v, vb + (int64_t)(t0 + t) * a.tv_sL + lane + 64 * r);
+        for (int gg = 0; gg < MG; ++gg) {
+          if (gg < G) {
 #pragma unroll
-          for (int gg = 0; gg < MG; ++gg) {
-            if (gg < G) {
-              const float p = ptile[wave][gg][t];
+            for (int t4 = 0; t4 < kTailUnit; t4 += 4) {
+              const float4 p4 = *reinterpret_cast<const float4*>(&ptile[wave][gg][t4]);
 #pragma unroll
-              for (int r = 0; r < NR; ++r) Ot[gg][r] = fmaf(p, vv[r], Ot[gg][r]);
+              for (int r = 0; r < NR; ++r) {
+                Ot[gg][r] = fmaf(p4.x, vv[r][t4], Ot[gg][r]);
+                Ot[gg][r] = fmaf(p4.y, vv[r][t4 + 1], Ot[gg][r]);
+                Ot[gg][r] = fmaf(p4.z, vv[r][t4 + 2], Ot[gg][r]);
+                Ot[gg][r] = fmaf(p4.w, vv[r][t4 + 3], Ot[gg][r]);
+              }
             }
           }
         }
@@ -490,7 +528,7 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       if (mM[w][gg] > -INFINITY) {
-        const float f = exp2f(mM[w][gg] - M);
+        const float f = fast_exp2(mM[w][gg] - M);
         o = fmaf(mO[w][gg][c], f, o);
         z = fmaf(mZ[w][gg], f, z);
       }
@@ -519,24 +557,31 @@ __global__ __launch_bounds__(256) void k_decode_mfma(DecArgs a) {
   for (int i = tid; i < G * D; i += 256) {
     const int gg = i / D, c = i % D;
     const int64_t hq = (int64_t)b * a.Hq + hk * G + gg;
-    const float* pm = a.part_m + hq * a.S;
-    const float* pz = a.part_z + hq * a.S;
+    // all partials are requested before any is used
+    float pm[kCombineMax], pz[kCombineMax], po[kCombineMax];
+#pragma unroll
+    for (int ss = 0; ss < kCombineMax; ++ss) {
+      const bool in = ss < a.S;
+      pm[ss] = in ? a.part_m[hq * a.S + ss] : -INFINITY;
+      pz[ss] = in ? a.part_z[hq * a.S + ss] : 0.f;
+      po[ss] = in ? a.part_o[(hq * a.S + ss) * D + c] : 0.f;
+    }
     float M = -INFINITY;
-    for (int ss = 0; ss < a.S; ++ss) M = fmaxf(M, pm[ss]);
+#pragma unroll
+    for (int ss = 0; ss < kCombineMax; ++ss) M = fmaxf(M, pm[ss]);
     float o = 0.f, z = 0.f;
-    for (int ss = 0; ss < a.S; ++ss) {
-      const float ms = pm[ss];
-      if (ms > -INFINITY) {
-        const float f = exp2f(ms - M);
-        o = fmaf(a.part_o[(hq * a.S + ss) * D + c], f, o);
-        z = fmaf(pz[ss], f, z);
-      }
+#pragma unroll
+    for (int ss = 0; ss < kCombineMax; ++ss) {
+      const float f = (pm[ss] > -INFINITY) ? fast_exp2(pm[ss] - M) : 0.f;
+      o = fmaf(po[ss], f, o);
+      z = fmaf(pz[ss], f, z);
     }
     store1<DT>(a.out, hq * D + c, z > 0.f ? o / z : 0.f);
     if (a.lse_out && c == 0) a.lse_out[hq] = (M + log2f(z)) * kLn2;
   }
   if (tid == 0) a.counters[b * a.Hkv + hk] = 0;
 }
+
 
 int launch_decode_mfma(const DecArgs& a, int dtype, hipStream_t st) {
   dim3 grid(a.S, a.Hkv, a.B), block(256);
