@@ -179,12 +179,8 @@ int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
  * out (device, q's dtype, [B, Hq, D]) = softmax(q.K^T * sm_scale) V over all
  * packed tokens and the first tail_len tail tokens; lse_out (device float
  * [B, Hq], optional) receives the natural-log normaliser of each row.
- * Deterministic for fixed shapes.
- * Workspace contract: the first zc_decode_attention_workspace() bytes of ws
- * start with arrival counters that must be ZERO before the first call that
- * uses this workspace (zero the whole workspace once after allocating it);
- * every call leaves them zero again.  Calls that share a workspace must not
- * run concurrently. */
+ * Deterministic for fixed shapes.  Calls that share a workspace must not run
+ * concurrently. */
 size_t zc_decode_attention_workspace(int64_t B, int64_t Hq, int64_t D);
 int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
                         const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,

@@ -7,6 +7,8 @@ namespace zc {
 
 constexpr int kTailUnit = 32;    // tail tokens per work unit of the MFMA decode kernel
 constexpr int kMaxSplits = 128;
+constexpr int kSegCost = 3;        // cost, in blocks, charged for starting a segment (query operand)
+constexpr int kInlineChunks = 12;  // chunk-table rows that travel in the kernel arguments
 
 struct DecArgs {
   const void* q;
@@ -28,13 +30,14 @@ struct DecArgs {
   int bits[2];
   const int32_t* chunk_table;
   int n_chunks;
+  int chunks_inline;                       // 1: chunk_rows holds the whole table
+  int32_t chunk_rows[4 * kInlineChunks];   // host copy of the chunk table, passed by value
   const void* tail_k;
   const void* tail_v;
   int64_t tk_sB, tk_sH, tk_sL, tv_sB, tv_sH, tv_sL;
   int tail_len;
   float scale_log2;
   int S, n_units;
-  int* counters;   // [B, Hkv] arrival counters, zero on entry and on exit
   float* part_m;   // [B, Hq, S]
   float* part_z;   // [B, Hq, S]
   float* part_o;   // [B, Hq, S, D]

@@ -343,11 +343,9 @@ static int split_cap(int64_t B, int64_t Hq) {
 
 using namespace zc;
 
-static size_t counter_bytes(int64_t B, int64_t Hq) { return (size_t)align_up64(B * Hq * 4, 256); }
-
 extern "C" size_t zc_decode_attention_workspace(int64_t B, int64_t Hq, int64_t D) {
   if (B <= 0 || Hq <= 0 || D <= 0) return 0;
-  return counter_bytes(B, Hq) + (size_t)B * Hq * split_cap(B, Hq) * (D + 2) * sizeof(float);
+  return (size_t)B * Hq * split_cap(B, Hq) * (D + 2) * sizeof(float);
 }
 
 extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
@@ -390,9 +388,12 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     const int32_t* rv = Vp->chunk_table_host + 4 * ci;
     for (int i = 0; i < 4; ++i)
       if (rk[i] != rv[i]) return ZC_ERR_INVALID_ARG;
-    units += ceil_div64(rk[1], 4 * (32 / Kp->bits_hi)) + ceil_div64(rk[3], 4 * (32 / Kp->bits_lo));
+    const int64_t nh = ceil_div64(rk[1], 4 * (32 / Kp->bits_hi)), nl = ceil_div64(rk[3], 4 * (32 / Kp->bits_lo));
+    units += nh + nl;
+    if (mfma_path) units += (nh > 0 ? kSegCost : 0) + (nl > 0 ? kSegCost : 0);   // the MFMA kernel splits a cost line
   }
   units += ceil_div64(tail_len, mfma_path ? kTailUnit : kTailBlock);
+  if (mfma_path && tail_len > 0) units += kSegCost;
   if (units > 0x7fffffff) return ZC_ERR_UNSUPPORTED;
 
   DecArgs a;
@@ -410,6 +411,8 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   a.cap[0] = Kp->cap_hi; a.cap[1] = Kp->cap_lo;
   a.bits[0] = Kp->bits_hi; a.bits[1] = Kp->bits_lo;
   a.chunk_table = Kp->chunk_table; a.n_chunks = Kp->n_chunks;
+  a.chunks_inline = Kp->n_chunks <= kInlineChunks;
+  for (int i = 0; i < 4 * kInlineChunks; ++i) a.chunk_rows[i] = (a.chunks_inline && i < 4 * Kp->n_chunks) ? Kp->chunk_table_host[i] : 0;
   a.tail_k = tail_len ? tail_k->ptr : nullptr;
   a.tail_v = tail_len ? tail_v->ptr : nullptr;
   a.tk_sB = tail_len ? tail_k->sB : 0; a.tk_sH = tail_len ? tail_k->sH : 0; a.tk_sL = tail_len ? tail_k->sL : 0;
@@ -420,7 +423,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   int S = split_cap(q->B, q->H);
   if (mfma_path) {
     // a workgroup is four waves; give every wave about two units before splitting further
-    const int64_t want = ceil_div64(units, 8);
+    const int64_t want = ceil_div64(units, 6);
     if (S > want) S = (int)(want > 0 ? want : 1);
     if (S > 16) S = 16;     // the last workgroup reads at most 16 partials per head
   } else if (S > units) {
@@ -428,8 +431,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   }
   a.S = S;
   const int64_t nq = q->B * q->H;
-  a.counters = reinterpret_cast<int*>(ws);
-  float* wsf = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + counter_bytes(q->B, q->H));
+  float* wsf = reinterpret_cast<float*>(ws);
   a.part_m = wsf;
   a.part_z = wsf + nq * S;
   a.part_o = wsf + 2 * nq * S;

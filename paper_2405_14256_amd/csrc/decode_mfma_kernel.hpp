@@ -1,0 +1,635 @@
+// Matrix-core kernel of zc_decode_attention for 2- and 4-bit caches (Eq. 4 over
+// the packed cache, Algorithm 3's attention line).
+//
+// Work unit: one block of the packed cache (32 slots at 4 bits, 64 at 2 bits:
+// D*16 bytes of K codes and as many of V codes) or 32 tokens of the
+// full-precision tail.  A workgroup takes a contiguous run of units; for every
+// segment (chunk x subset, or the tail) in that run its four waves build the
+// query operand together, then each wave walks its share of the blocks with its
+// own online-softmax state in registers, loading block i+1 while it computes
+// block i; there is no barrier inside that loop.  The waves merge through LDS;
+// when several workgroups share one (batch, KV head) each writes a partial
+// (m, Z, o) and k_decode_reduce reduces them (a kernel boundary is the cheapest
+// device-wide release / acquire on this part: in-kernel fences cost more).
+// The run of a workgroup is cut on a cost line where every segment start counts
+// as kSegCost blocks, so that small streaming chunks do not pile up on one
+// workgroup.
+//
+// Both products run on v_mfma_f32_16x16x32_f16 with the codes as one operand:
+//   logits  D[token][n]   = sum_c code[token][c] * q'[n][c]      (A = K codes, ROW layout)
+//   output  D[n][channel] = sum_t w[n][t] * code[t][channel]     (B = V codes, TGROUP layout)
+// The 16 columns n hold the Hq/Hkv query heads of the KV head twice: the fp16
+// value of the operand (n even) and its rounding residual times 2^11 (n odd), so
+// the fp32 q and softmax weights keep about 21 bits.  A code c enters as the fp16
+// number 1 + c / SC (SC = 16 or 4) built by OR-ing its bits into the mantissa of
+// 1.0; the "1" terms are removed with the sum of the other operand (for the
+// output product that sum comes from one more MFMA against a vector of ones).
+// The packed layouts are chosen so that the 8 codes a lane feeds to one MFMA are
+// contiguous bits of one 32-bit word, and so that the lane that holds a logit is
+// the lane that must supply the corresponding softmax weight to the second MFMA.
+// De-quantization never happens per element:
+//   logit[t] = ts[t] * (dot[t] - tz[t] * sum_c q'[c] - sum_c q'[c] cz[c]),  q' = q cs sm_scale log2(e)
+//   o[c]     = cs[c] * (sum_t w[t] code[t][c] - sum_t w[t] tz[t] - cz[c] sum_t w[t]),  w = p ts
+#pragma once
+
+#include "decode_args.hpp"
+
+namespace zc {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+
+constexpr float kLoScale = 2048.f;          // residual operand is scaled by 2^11
+constexpr float kLoInv = 1.f / 2048.f;
+constexpr int kCombineMax = 16;             // most workgroups per (batch, KV head) on this path
+
+__device__ inline f4 mfma16(u4 a, u4 b, f4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
+}
+
+// fp16 bit patterns of 1 + c/16 for the eight 4-bit codes of w: register i holds
+// code i (low half) and code i + 4 (high half).
+__device__ inline u4 unpack4(uint32_t w) {
+  const uint32_t M = 0x03C003C0u, E = 0x3C003C00u;
+  u4 r;
+  r.x = ((w << 6) & M) | E;
+  r.y = ((w << 2) & M) | E;
+  r.z = ((w >> 2) & M) | E;
+  r.w = ((w >> 6) & M) | E;
+  return r;
+}
+// fp16 bit patterns of 1 + c/4 for eight of the sixteen 2-bit codes of w:
+// half 0: register i = codes (i, i + 8); half 1: register i = codes (4 + i, 12 + i).
+__device__ inline u4 unpack2(uint32_t w, int half) {
+  const uint32_t M = 0x03000300u, E = 0x3C003C00u;
+  if (half) w >>= 8;
+  u4 r;
+  r.x = ((w << 8) & M) | E;
+  r.y = ((w << 6) & M) | E;
+  r.z = ((w << 4) & M) | E;
+  r.w = ((w << 2) & M) | E;
+  return r;
+}
+
+__device__ inline uint32_t pack_h2(_Float16 lo, _Float16 hi) {
+  uint16_t a, b;
+  __builtin_memcpy(&a, &lo, 2);
+  __builtin_memcpy(&b, &hi, 2);
+  return (uint32_t)a | ((uint32_t)b << 16);
+}
+
+// Splits x into the fp16 nearest to it and the scaled residual; returns the one
+// this lane feeds (part 0: value, part 1: residual).
+__device__ inline _Float16 split_part(float x, int part) {
+  const _Float16 hi = (_Float16)x;
+  const _Float16 lo = (_Float16)((x - (float)hi) * kLoScale);
+  return part ? lo : hi;
+}
+__device__ inline _Float16 split_part(float x, int part, float& represented) {
+  const _Float16 hi = (_Float16)x;
+  const float hif = (float)hi;
+  const _Float16 lo = (_Float16)((x - hif) * kLoScale);
+  represented = hif + (float)lo * kLoInv;
+  return part ? lo : hi;
+}
+
+__device__ inline float xor1(float x) {   // value of the neighbouring lane (lane ^ 1)
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));
+}
+__device__ inline float grp_max(float x) {  // over the four 16-lane groups
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ inline float grp_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int DT, int D, bool KTOK, bool VTOK>
+__global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
+  constexpr int KS = D / 32;     // k-steps of the logit product
+  constexpr int NR = D / 64;     // 16-byte V loads per lane and block
+  constexpr int MG = ZC_MAX_GROUP;
+  __shared__ u4 sqB[KS][64];              // query operand of the current segment
+  __shared__ float ssum[2][KS][64];
+  __shared__ float mO[4][MG][D];
+  __shared__ float mM[4][MG], mZ[4][MG];
+  __shared__ float ptile[4][MG][kTailUnit];
+
+  const int s = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, grp = lane >> 4;
+  const int G = a.G;
+  const int g = n >> 1, part = n & 1;
+  const bool nvalid = n < 2 * G;
+  const int g0 = 2 * grp, g1 = 2 * grp + 1;      // heads of this lane's rows in the output tiles
+  // weights of (own, neighbour) column when a head's value and residual columns are added
+  const float c_own = part ? kLoInv : 1.f, c_oth = part ? 1.f : kLoInv;
+  const u4 ones = u4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};   // fp16 1.0 x 8
+
+  // running state of this wave
+  float m_run = -INFINITY, z_part = 0.f;
+  float O[NR][4][2];
+  float Ot[MG][NR];
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { O[r][j][0] = 0.f; O[r][j][1] = 0.f; }
+#pragma unroll
+  for (int gg = 0; gg < MG; ++gg)
+#pragma unroll
+    for (int r = 0; r < NR; ++r) Ot[gg][r] = 0.f;
+
+  // this workgroup's share of the cost line (blocks + kSegCost per segment start)
+  const int u0 = (int)((int64_t)a.n_units * s / a.S), u1 = (int)((int64_t)a.n_units * (s + 1) / a.S);
+
+  // When the running maximum of a head grows, everything accumulated so far is
+  // rescaled; rare after the first blocks, so it sits behind a wave-uniform branch.
+  auto rescale_to = [&](float m_new, float& a1, f4 (*acc)[4], f4* acc1) {
+    const bool changed = nvalid && (m_new > m_run);
+    if (__any(changed)) {
+      const float fac = (m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
+      z_part *= fac; a1 *= fac;
+      const float f0 = __shfl(fac, 2 * g0), f1 = __shfl(fac, 2 * g1);
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          O[r][j][0] *= f0; O[r][j][1] *= f1;
+          if (acc) { acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1; }
+        }
+      if (acc1) { acc1->x *= f0; acc1->y *= f0; acc1->z *= f1; acc1->w *= f1; }
+#pragma unroll 1
+      for (int gg = 0; gg < G; ++gg) {
+        const float fg = __shfl(fac, 2 * gg);
+#pragma unroll
+        for (int g2 = 0; g2 < MG; ++g2)
+          if (g2 == gg) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) Ot[g2][r] *= fg;
+          }
+      }
+    }
+    m_run = fmaxf(m_run, m_new);
+  };
+
+  // The query operand of a segment, built once per workgroup: wave w computes
+  // k-step w.  MODE 4 / 2: codes of that width, q' = q cs SC in the channel order
+  // the unpacked K words have; MODE 0: the tail, q itself in natural order.
+  // Returns the operand registers and sum(q''), sum(q'' cz) over all channels.
+  auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, u4 (&qB)[KS], float& sumqq, float& sumqqcz) {
+    constexpr int MODE = decltype(mode_c)::value;
+    constexpr float SC = MODE == 4 ? 16.f : (MODE == 2 ? 4.f : 1.f);
+    // q and the channel parameters of this lane's k-step, straight from global
+    // memory (issued together with the first block's loads by the caller)
+    float q8[8], cs8[8], cz8[8];
+    const int ks0 = wave;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { q8[i] = 0.f; cs8[i] = 1.f; cz8[i] = 0.f; }
+    if (ks0 < KS) {
+      const int64_t qoff = (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH;
+      if constexpr (MODE == 2) {
+        // slots (i, half) are channels base + 4 (ks0 & 1) + i + 8 half of a 16-channel word
+        const int base = grp * (D / 4) + 16 * (ks0 >> 1);
+        float qa[8], qb[8];
+        load8<DT>(a.q, qoff + base, qa);
+        load8<DT>(a.q, qoff + base + 8, qb);
+        const float4 ca = *reinterpret_cast<const float4*>(kcs + base + 4 * (ks0 & 1));
+        const float4 cb = *reinterpret_cast<const float4*>(kcs + base + 8 + 4 * (ks0 & 1));
+        const float4 za = *reinterpret_cast<const float4*>(kcz + base + 4 * (ks0 & 1));
+        const float4 zb = *reinterpret_cast<const float4*>(kcz + base + 8 + 4 * (ks0 & 1));
+        const float csa[4] = {ca.x, ca.y, ca.z, ca.w}, csb[4] = {cb.x, cb.y, cb.z, cb.w};
+        const float cza[4] = {za.x, za.y, za.z, za.w}, czb[4] = {zb.x, zb.y, zb.z, zb.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          q8[2 * i] = (ks0 & 1) ? qa[4 + i] : qa[i];
+          q8[2 * i + 1] = (ks0 & 1) ? qb[4 + i] : qb[i];
+          cs8[2 * i] = csa[i]; cs8[2 * i + 1] = csb[i];
+          cz8[2 * i] = cza[i]; cz8[2 * i + 1] = czb[i];
+        }
+      } else {
+        // MODE 4: slots (i, half) are channels base + i + 4 half; MODE 0: base + 2 i + half
+        const int base = (MODE == 4) ? grp * (D / 4) + 8 * ks0 : 32 * ks0 + 8 * grp;
+        float qa[8];
+        load8<DT>(a.q, qoff + base, qa);
+        float ca[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f}, za[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if constexpr (MODE == 4) {
+          const float4 c0 = *reinterpret_cast<const float4*>(kcs + base), c1 = *reinterpret_cast<const float4*>(kcs + base + 4);
+          const float4 z0 = *reinterpret_cast<const float4*>(kcz + base), z1 = *reinterpret_cast<const float4*>(kcz + base + 4);
+          ca[0] = c0.x; ca[1] = c0.y; ca[2] = c0.z; ca[3] = c0.w; ca[4] = c1.x; ca[5] = c1.y; ca[6] = c1.z; ca[7] = c1.w;
+          za[0] = z0.x; za[1] = z0.y; za[2] = z0.z; za[3] = z0.w; za[4] = z1.x; za[5] = z1.y; za[6] = z1.z; za[7] = z1.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const int e = (MODE == 4) ? i + 4 * half : 2 * i + half;
+            q8[2 * i + half] = qa[e]; cs8[2 * i + half] = ca[e]; cz8[2 * i + half] = za[e];
+          }
+      }
+    }
+    __syncthreads();     // sqB / ssum of the previous segment are no longer read
+    if (ks0 < KS) {
+      uint32_t regs[4];
+      float sq = 0.f, sqz = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        _Float16 hv[2];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const float qv = nvalid ? q8[2 * i + half] * a.scale_log2 * cs8[2 * i + half] * SC : 0.f;
+          float rep;
+          hv[half] = split_part(qv, part, rep);
+          sq += rep;
+          sqz += rep * cz8[2 * i + half];
+        }
+        regs[i] = pack_h2(hv[0], hv[1]);
+      }
+      u4 t; t.x = regs[0]; t.y = regs[1]; t.z = regs[2]; t.w = regs[3];
+      sqB[ks0][lane] = t;
+      ssum[0][ks0][lane] = sq;
+      ssum[1][ks0][lane] = sqz;
+    }
+    __syncthreads();
+    sumqq = 0.f; sumqqcz = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qB[ks] = sqB[ks][lane];
+      sumqq += ssum[0][ks][lane];
+      sumqqcz += ssum[1][ks][lane];
+    }
+    sumqq = grp_sum(sumqq);
+    sumqqcz = grp_sum(sumqqcz);
+  };
+
+  int cursor = 0;
+  // ---------------- packed segments --------------------------------------------------
+  auto segment = [&](auto bits_c, int ci, int sub, int begin, int len, int lo, int hi) {
+    constexpr int BITS = decltype(bits_c)::value;
+    constexpr int E = 32 / BITS, TB = 4 * E, NT = TB / 16, NH = NT / 2;
+    constexpr float SC = (BITS == 4) ? 16.f : 4.f;
+    constexpr int KW = D * BITS / 128;       // 32-bit words of K codes per lane and token
+    const int64_t chan_off = ((int64_t)(ci * 2 + sub) * a.B + b) * (a.Hkv * D) + hk * D;
+    const int wlo = lo + (hi - lo) * wave / 4, whi = lo + (hi - lo) * (wave + 1) / 4;
+
+    const int64_t bh = (int64_t)b * a.Hkv + hk;
+    const int64_t nblk = a.cap[sub] / TB;
+    const uint8_t* kbase = a.kc[sub] + bh * a.cap[sub] * (D * BITS / 8) + grp * (KW * 4);
+    const int64_t tokbase = (int64_t)b * a.cap[sub];
+
+    // The loop runs over half-blocks of 32 slots (two 16-slot tiles): a 4-bit block
+    // is one of them, a 2-bit block two that share the same V words.
+    struct Buf {
+      uint32_t kw[2][KW];
+      uint4 vw[NR];
+      float4 kts[2], ktz[2], vts[2], vtz[2];
+    };
+    auto load_half = [&](int hb, Buf& bf) {
+      const int blk = hb / NH, h = hb % NH;
+      const int slot0 = begin + blk * TB;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const int j = 2 * h + jj;
+        const uint32_t* kp = reinterpret_cast<const uint32_t*>(kbase + (int64_t)(slot0 + 16 * j + n) * (D * BITS / 8));
+        if constexpr (KW == 4) { const uint4 t = *reinterpret_cast<const uint4*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; bf.kw[jj][2] = t.z; bf.kw[jj][3] = t.w; }
+        else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; }
+        else { bf.kw[jj][0] = *kp; }
+        const int64_t to = tokbase + slot0 + 16 * j + 4 * grp;
+        if constexpr (KTOK) {
+          bf.kts[jj] = *reinterpret_cast<const float4*>(a.k_ts[sub] + to);
+          bf.ktz[jj] = *reinterpret_cast<const float4*>(a.k_tz[sub] + to);
+        }
+        if constexpr (VTOK) {
+          bf.vts[jj] = *reinterpret_cast<const float4*>(a.v_ts[sub] + to);
+          bf.vtz[jj] = *reinterpret_cast<const float4*>(a.v_tz[sub] + to);
+        }
+      }
+      const uint32_t* vbase = a.vc[sub] + ((bh * nblk + slot0 / TB) * 4 + grp) * D;
+#pragma unroll
+      for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const uint4*>(vbase + 4 * (n + 16 * r));
+    };
+
+    const int hlo = wlo * NH, hhi = whi * NH;
+    Buf cur;
+    if (hlo < hhi) load_half(hlo, cur);       // in flight while the operand is built
+    // channel parameters of the values, needed when the segment is folded
+    float4 vcs4[NR], vcz4[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      vcs4[r] = *reinterpret_cast<const float4*>(a.v_cs + chan_off + 4 * (n + 16 * r));
+      vcz4[r] = *reinterpret_cast<const float4*>(a.v_cz + chan_off + 4 * (n + 16 * r));
+    }
+
+    u4 qB[KS];
+    float sumqq, sumqqcz;
+    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, qB, sumqq, sumqqcz);
+    if (wlo >= whi) return;
+    const float Aq = sumqq / SC;
+    const float kconst = -(sumqq + sumqqcz / SC);     // removes the "1" terms and sum q' cz
+
+    f4 acc[NR][4];
+    f4 acc1 = f4{0.f, 0.f, 0.f, 0.f};     // sum of the weights operand (product with ones)
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[r][j] = f4{0.f, 0.f, 0.f, 0.f};
+    float a1 = 0.f;
+
+    // one half-block; MASKED only when it reaches past the end of the segment
+    auto half_block = [&](auto masked_c, const Buf& bf, int h, int ntok) {
+      constexpr bool MASKED = decltype(masked_c)::value;
+      float lg[2][4];
+      float lmax = -INFINITY;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        f4 sacc = f4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (BITS == 4) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack4(bf.kw[jj][ks]), qB[ks], sacc);
+        } else {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack2(bf.kw[jj][ks >> 1], ks & 1), qB[ks], sacc);
+        }
+        const float own[4] = {sacc.x, sacc.y, sacc.z, sacc.w};
+        const float kts[4] = {bf.kts[jj].x, bf.kts[jj].y, bf.kts[jj].z, bf.kts[jj].w};
+        const float ktz[4] = {bf.ktz[jj].x, bf.ktz[jj].y, bf.ktz[jj].z, bf.ktz[jj].w};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          float x = fmaf(xor1(own[v]), c_oth, own[v] * c_own) + kconst;
+          if constexpr (KTOK) x = kts[v] * fmaf(-ktz[v], Aq, x);
+          if constexpr (MASKED) x = (16 * jj + 4 * grp + v < ntok) ? x : -INFINITY;
+          lg[jj][v] = x;
+          lmax = fmaxf(lmax, x);
+        }
+      }
+      rescale_to(fmaxf(m_run, grp_max(lmax)), a1, acc, &acc1);
+      // weights w = p ts and the A operand of the output product
+      _Float16 wh[2][4];
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const float vts[4] = {bf.vts[jj].x, bf.vts[jj].y, bf.vts[jj].z, bf.vts[jj].w};
+        const float vtz[4] = {bf.vtz[jj].x, bf.vtz[jj].y, bf.vtz[jj].z, bf.vtz[jj].w};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float p = fast_exp2(lg[jj][v] - m_run);      // 0 for masked slots
+          float w = p;
+          if constexpr (VTOK) {
+            const bool live = !MASKED || (16 * jj + 4 * grp + v < ntok);   // parameters past the end are not written
+            w = live ? p * vts[v] : 0.f;
+            a1 = fmaf(w, live ? vtz[v] : 0.f, a1);
+          }
+          z_part += p;
+          wh[jj][v] = split_part(w * SC, part);
+        }
+      }
+      u4 pA;
+      pA.x = pack_h2(wh[0][0], wh[1][0]); pA.y = pack_h2(wh[0][1], wh[1][1]);
+      pA.z = pack_h2(wh[0][2], wh[1][2]); pA.w = pack_h2(wh[0][3], wh[1][3]);
+      acc1 = mfma16(pA, ones, acc1);
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {
+        const uint32_t ww[4] = {bf.vw[r].x, bf.vw[r].y, bf.vw[r].z, bf.vw[r].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if constexpr (BITS == 4) acc[r][j] = mfma16(pA, unpack4(ww[j]), acc[r][j]);
+          else acc[r][j] = mfma16(pA, unpack2(ww[j], h), acc[r][j]);
+        }
+      }
+    };
+
+    for (int hb = hlo; hb < hhi; ++hb) {
+      Buf nxt;
+      if (hb + 1 < hhi) load_half(hb + 1, nxt);
+      const int h = hb % NH;
+      const int ntok = len - (hb / NH) * TB - 32 * h;      // slots of this half-block inside the segment
+      if (ntok >= 32) half_block(std::false_type{}, cur, h, 32);
+      else half_block(std::true_type{}, cur, h, ntok);
+      if (hb + 1 < hhi) cur = nxt;
+    }
+    // ---- fold the segment into O ----
+    // sum_t w code = acc_value + acc_residual / 2^11 - sum_t w'';  sum_t w = sum_t w'' / SC
+    const float sw0 = acc1.x + acc1.y * kLoInv, sw1 = acc1.z + acc1.w * kLoInv;
+    float a10 = 0.f, a11 = 0.f;
+    if constexpr (VTOK) {
+      a1 = grp_sum(a1);
+      a10 = __shfl(a1, 2 * g0); a11 = __shfl(a1, 2 * g1);
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const float cs[4] = {vcs4[r].x, vcs4[r].y, vcs4[r].z, vcs4[r].w}, cz[4] = {vcz4[r].x, vcz4[r].y, vcz4[r].z, vcz4[r].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float t0 = acc[r][j].x + acc[r][j].y * kLoInv - sw0;
+        const float t1 = acc[r][j].z + acc[r][j].w * kLoInv - sw1;
+        O[r][j][0] = fmaf(cs[j], t0 - a10 - cz[j] * (sw0 / SC), O[r][j][0]);
+        O[r][j][1] = fmaf(cs[j], t1 - a11 - cz[j] * (sw1 / SC), O[r][j][1]);
+      }
+    }
+  };
+
+  for (int ci = 0; ci < a.n_chunks; ++ci) {
+    for (int sub = 0; sub < 2; ++sub) {
+      int begin, len;
+      if (a.chunks_inline) { begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1]; }
+      else { begin = a.chunk_table[4 * ci + 2 * sub]; len = a.chunk_table[4 * ci + 2 * sub + 1]; }
+      const int bits = a.bits[sub];
+      const int TB = 4 * (32 / bits);
+      const int nb = ceil_div(len, TB);
+      if (nb == 0) continue;
+      const int seg0 = cursor + kSegCost;        // the segment's blocks sit after its start-up slots
+      cursor = seg0 + nb;
+      const int lo = max(u0 - seg0, 0), hi = min(u1 - seg0, nb);
+      if (lo >= hi) continue;
+      if (bits == 4) segment(std::integral_constant<int, 4>{}, ci, sub, begin, len, lo, hi);
+      else segment(std::integral_constant<int, 2>{}, ci, sub, begin, len, lo, hi);
+    }
+  }
+
+  // ---------------- full-precision tail ------------------------------------------------
+  {
+    const int n_tail = ceil_div(a.tail_len, kTailUnit);
+    const int seg0 = cursor + kSegCost;
+    const int lo = max(u0 - seg0, 0), hi = min(u1 - seg0, n_tail);
+    if (lo < hi) {
+      const int wlo = lo + (hi - lo) * wave / 4, whi = lo + (hi - lo) * (wave + 1) / 4;
+      u4 qB[KS];
+      float dummy0, dummy1;
+      build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, qB, dummy0, dummy1);
+      const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
+      const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
+      for (int tu = wlo; tu < whi; ++tu) {
+        const int t0 = tu * kTailUnit;
+        const int ntok = min(kTailUnit, a.tail_len - t0);
+        float U[2][4];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int tok = 16 * j + n;          // row of the A operand
+          f4 s_hi = f4{0.f, 0.f, 0.f, 0.f}, s_lo = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            float kv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (tok < ntok) load8<DT>(a.tail_k, kb + (int64_t)(t0 + tok) * a.tk_sL + 32 * ks + 8 * grp, kv);
+            uint32_t rh[4], rl[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const _Float16 h0 = (_Float16)kv[2 * i], h1 = (_Float16)kv[2 * i + 1];
+              rh[i] = pack_h2(h0, h1);
+              if constexpr (DT == ZC_F32)
+                rl[i] = pack_h2((_Float16)((kv[2 * i] - (float)h0) * kLoScale), (_Float16)((kv[2 * i + 1] - (float)h1) * kLoScale));
+            }
+            u4 ah; ah.x = rh[0]; ah.y = rh[1]; ah.z = rh[2]; ah.w = rh[3];
+            s_hi = mfma16(ah, qB[ks], s_hi);
+            if constexpr (DT == ZC_F32) {
+              u4 al; al.x = rl[0]; al.y = rl[1]; al.z = rl[2]; al.w = rl[3];
+              s_lo = mfma16(al, qB[ks], s_lo);
+            }
+          }
+          // rows past the end of the tail are zeros; every lane takes part in the MFMAs
+          const float own[4] = {s_hi.x + s_lo.x * kLoInv, s_hi.y + s_lo.y * kLoInv, s_hi.z + s_lo.z * kLoInv, s_hi.w + s_lo.w * kLoInv};
+#pragma unroll
+          for (int v = 0; v < 4; ++v) U[j][v] = fmaf(xor1(own[v]), c_oth, own[v] * c_own);
+        }
+        float lmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            if (16 * j + 4 * grp + v >= ntok) U[j][v] = -INFINITY;
+            lmax = fmaxf(lmax, U[j][v]);
+          }
+        float da1 = 0.f;
+        rescale_to(fmaxf(m_run, grp_max(lmax)), da1, nullptr, nullptr);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float p = nvalid ? fast_exp2(U[j][v] - m_run) : 0.f;
+            z_part += p;
+            if (nvalid && part == 0) ptile[wave][g][16 * j + 4 * grp + v] = p;
+          }
+        // weighted sum of the tail values: every lane owns channels lane + 64 r
+#pragma unroll 1
+        for (int t8 = 0; t8 < kTailUnit; t8 += 8) {
+          float vv[NR][8];
+#pragma unroll
+          for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+              vv[r][t] = (t8 + t < ntok) ? load1<DT>(a.tail_v, vb + (int64_t)(t0 + t8 + t) * a.tv_sL + lane + 64 * r) : 0.f;
+#pragma unroll
+          for (int gg = 0; gg < MG; ++gg) {
+            if (gg < G) {
+              const float4 pa = *reinterpret_cast<const float4*>(&ptile[wave][gg][t8]);
+              const float4 pb = *reinterpret_cast<const float4*>(&ptile[wave][gg][t8 + 4]);
+              const float pp[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+              for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int t = 0; t < 8; ++t) Ot[gg][r] = fmaf(pp[t], vv[r][t], Ot[gg][r]);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // ---------------- merge the four waves --------------------------------------------------
+  const float z_tot = grp_sum(z_part);
+  if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = 4 * (n + 16 * r) + j;
+      if (g0 < G) mO[wave][g0][c] = O[r][j][0];
+      if (g1 < G) mO[wave][g1][c] = O[r][j][1];
+    }
+  __syncthreads();
+#pragma unroll
+  for (int gg = 0; gg < MG; ++gg) {
+    if (gg < G) {
+#pragma unroll
+      for (int r = 0; r < NR; ++r) mO[wave][gg][lane + 64 * r] += Ot[gg][r];
+    }
+  }
+  __syncthreads();
+
+  const bool direct = a.S == 1;
+  for (int i = tid; i < G * D; i += 256) {
+    const int gg = i / D, c = i % D;
+    float M = fmaxf(fmaxf(mM[0][gg], mM[1][gg]), fmaxf(mM[2][gg], mM[3][gg]));
+    float o = 0.f, z = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (mM[w][gg] > -INFINITY) {
+        const float f = fast_exp2(mM[w][gg] - M);
+        o = fmaf(mO[w][gg][c], f, o);
+        z = fmaf(mZ[w][gg], f, z);
+      }
+    }
+    const int64_t hq = (int64_t)b * a.Hq + hk * G + gg;
+    if (direct) {
+      store1<DT>(a.out, hq * D + c, z > 0.f ? o / z : 0.f);
+      if (a.lse_out && c == 0) a.lse_out[hq] = (M + log2f(z)) * kLn2;
+    } else {
+      a.part_o[(hq * a.S + s) * D + c] = o;
+      if (c == 0) { a.part_m[hq * a.S + s] = M; a.part_z[hq * a.S + s] = z; }
+    }
+  }
+}
+
+// Reduces the partial (m, Z, o) of the workgroups of one query head.
+template <int DT, int D>
+__global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ part_m, const float* __restrict__ part_z,
+                                                      const float* __restrict__ part_o, int S,
+                                                      void* __restrict__ out, float* __restrict__ lse_out) {
+  const int64_t hq = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
+  const int c = threadIdx.x;
+  // all partials are requested before any is used
+  float pm[kCombineMax], pz[kCombineMax], po[kCombineMax];
+#pragma unroll
+  for (int ss = 0; ss < kCombineMax; ++ss) {
+    const bool in = ss < S;
+    pm[ss] = in ? part_m[hq * S + ss] : -INFINITY;
+    pz[ss] = in ? part_z[hq * S + ss] : 0.f;
+    po[ss] = in ? part_o[(hq * S + ss) * D + c] : 0.f;
+  }
+  float M = -INFINITY;
+#pragma unroll
+  for (int ss = 0; ss < kCombineMax; ++ss) M = fmaxf(M, pm[ss]);
+  float o = 0.f, z = 0.f;
+#pragma unroll
+  for (int ss = 0; ss < kCombineMax; ++ss) {
+    const float f = (pm[ss] > -INFINITY) ? fast_exp2(pm[ss] - M) : 0.f;
+    o = fmaf(po[ss], f, o);
+    z = fmaf(pz[ss], f, z);
+  }
+  store1<DT>(out, hq * D + c, z > 0.f ? o / z : 0.f);
+  if (lse_out && c == 0) lse_out[hq] = (M + log2f(z)) * kLn2;
+}
+
+template <int DT>
+static int launch_decode_mfma_dt(const DecArgs& a, hipStream_t st) {
+  dim3 grid(a.S, a.Hkv, a.B), block(256);
+#define ZC_L(KT, VT)                                                                              \
+  do {                                                                                            \
+    if (a.D == 128) hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT>), grid, block, 0, st, a);  \
+    else hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT>), grid, block, 0, st, a);              \
+  } while (0)
+  if (a.k_tok && a.v_tok) ZC_L(true, true);
+  else if (a.k_tok) ZC_L(true, false);
+  else if (a.v_tok) ZC_L(false, true);
+  else ZC_L(false, false);
+#undef ZC_L
+  ZC_LAUNCH_CHECK();
+  if (a.S > 1) {
+    if (a.D == 128) hipLaunchKernelGGL((k_decode_reduce<DT, 128>), dim3(a.Hq, a.B), dim3(128), 0, st, a.part_m, a.part_z, a.part_o, a.S, a.out, a.lse_out);
+    else hipLaunchKernelGGL((k_decode_reduce<DT, 64>), dim3(a.Hq, a.B), dim3(64), 0, st, a.part_m, a.part_z, a.part_o, a.S, a.out, a.lse_out);
+    ZC_LAUNCH_CHECK();
+  }
+  return ZC_OK;
+}
+
+}  // namespace zc
