@@ -167,7 +167,7 @@ int zc_select_salient(const float* scores, int64_t B, int64_t L, int64_t k,
  * when pos arrays are present.  On success the host fields n_hi, n_lo,
  * n_chunks and chunk_table_host are updated (the device copy is written by
  * the enqueued work).  Index lists must hold distinct values in [0, L). */
-size_t zc_quantize_pack_workspace(int64_t B, int64_t H, int64_t D);
+size_t zc_quantize_pack_workspace(int64_t B, int64_t H, int64_t L /* tokens per call, k + n_reg */, int64_t D);
 int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
                      const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
                      zc_packed* out, void* ws, size_t ws_bytes, void* stream);

@@ -75,7 +75,7 @@ def load() -> C.CDLL:
     lib.zc_select_salient.restype = C.c_int
     lib.zc_select_salient.argtypes = [P, I64, I64, I64, P, P, P, P, SZ, P]
     lib.zc_quantize_pack_workspace.restype = SZ
-    lib.zc_quantize_pack_workspace.argtypes = [I64, I64, I64]
+    lib.zc_quantize_pack_workspace.argtypes = [I64, I64, I64, I64]
     lib.zc_quantize_pack.restype = C.c_int
     lib.zc_quantize_pack.argtypes = [T4, P, I64, P, I64, I64, PK, P, SZ, P]
     lib.zc_decode_attention_workspace.restype = SZ
@@ -214,8 +214,8 @@ def zc_quantize_pack(x: torch.Tensor, salient_idx: torch.Tensor, regular_idx: to
     B, H, _, D = x.shape
     k = int(salient_idx.shape[1]) if salient_idx is not None else 0
     n_reg = int(regular_idx.shape[1]) if regular_idx is not None else 0
-    need = lib.zc_quantize_pack_workspace(B, H, D)
-    ws = _workspace(need, x.device)
+    need = lib.zc_quantize_pack_workspace(B, H, k + n_reg, D)
+    ws = _workspace(need, x.device, "quantize")
     tx = tensor4(x)
     _check("zc_quantize_pack",
            lib.zc_quantize_pack(C.byref(tx), _ptr(salient_idx) if k else None, k,

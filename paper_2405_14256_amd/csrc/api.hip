@@ -6,11 +6,6 @@ using namespace zc;
 
 static bool bits_ok(int b) { return b == 2 || b == 4 || b == 8; }
 
-extern "C" size_t zc_quantize_pack_workspace(int64_t B, int64_t H, int64_t D) {
-  if (B <= 0 || H <= 0 || D <= 0) return 0;
-  return (size_t)B * 2 * H * D * 2 * sizeof(uint32_t);
-}
-
 extern "C" size_t zc_arena_bytes(int64_t B, int64_t H, int64_t D, int64_t cap, int32_t bits) {
   if (B <= 0 || H <= 0 || D <= 0 || cap <= 0 || bits <= 0) return 0;
   return (size_t)B * H * cap * D * bits / 8;

@@ -1,17 +1,24 @@
 // zc_quantize_pack: mixed-precision quantization and bit-packing of one cache
 // tensor (Eq. 5, Eq. 6, Algorithm 1; the four quantizer calls of Algorithm 2).
 //
-// Two sweeps over the gathered token rows:
-//   1. k_chan_stats: per-channel min / max of each subset (salient, regular),
-//      combined across workgroups with integer atomics on order-preserving
-//      keys, so the result does not depend on scheduling.
-//   2. k_quant_pack: every workgroup turns the statistics of the channels it
-//      owns into parameters (Eq. 5's s, z per channel, or Eq. 6's c), then
-//      quantizes one "unit" of E = 32/bits tokens: per-token min / max by
-//      wave reduction for the tokenwise schemes, round-half-even, clamp, and
-//      packs along channels (ROW layout) or along tokens (TGROUP layout).
-// Both sweeps read 16 bytes per lane with consecutive lanes on consecutive
-// addresses of a (token, head) row.
+// Channel statistics of a subset must be complete before any of its tokens can
+// be quantized, so the work is three launches:
+//   1. k_chan_stats     per-channel min / max over a tile of tokens of one
+//                       subset (salient or regular), written as partials - no
+//                       atomics, so the result does not depend on scheduling.
+//   2. k_chan_finalize  reduces the partials and turns them once into the
+//                       parameters the quantizer needs (Eq. 5's R = max - min,
+//                       1/R and z per channel, or Eq. 6's c and 1/c).
+//   3. k_quant_pack     a team of waves owns one "unit" of E = 32/bits tokens
+//                       (the tokens that share 32-bit words in the TGROUP
+//                       layout): all rows of a batch of tokens are requested at
+//                       once, per-token min / max by DPP wave reduction for the
+//                       tokenwise schemes, tie-exact x (2^k-1) / R, round half to
+//                       even, + z, clamp, pack along channels (ROW layout) or along
+//                       tokens (TGROUP layout).
+// Every sweep reads 16 bytes per lane with consecutive lanes on consecutive
+// addresses of a (token, head) row; the second sweep of a tensor that fits the
+// 256 MB Infinity Cache does not reach HBM.
 #include "zc_common.hpp"
 
 namespace zc {
@@ -23,6 +30,7 @@ struct QPArgs {
   const int32_t* idx[2];       // [B, n] token lists (salient, regular)
   int n[2];                    // tokens per subset
   int begin[2];                // first arena slot of this chunk
+  int bits[2];
   int64_t cap[2];
   uint8_t* codes[2];
   float* tok_scale[2];
@@ -30,7 +38,8 @@ struct QPArgs {
   int32_t* pos[2];
   float* chan_scale;           // this chunk: [2, B, W]
   float* chan_zero;
-  uint32_t* stats;             // workspace [B, 2, W, 2] keys (min, max)
+  float* partial;              // workspace [B, tiles_hi + tiles_lo, W, 2] (min, max)
+  float4* params;              // workspace [B, 2, W]: CHANNEL {1/R, z, R, -}, CST {1/c, -, -, -}
   int32_t* chunk_row;          // device chunk_table row to fill
   int64_t pos_offset;
   int tiles[2], TT;            // stats sweep tiling
@@ -38,26 +47,23 @@ struct QPArgs {
   int scheme;
 };
 
-__global__ void k_stats_init(uint32_t* stats, int64_t n_pairs) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_pairs) {
-    stats[2 * i] = 0xffffffffu;  // running min key
-    stats[2 * i + 1] = 0u;       // running max key
-  }
-}
+constexpr int kStatMaxV = 4;   // channel vectors per thread in the statistics sweep (W <= 8192)
 
-constexpr int kStatMaxV = 4;
+__host__ __device__ inline int stats_tile_tokens(int64_t total_tokens) {
+  int64_t tt = ceil_div64(total_tokens, 1024);
+  return tt < 16 ? 16 : (tt > 64 ? 64 : (int)tt);
+}
 
 template <int DT>
 __global__ __launch_bounds__(256) void k_chan_stats(QPArgs a) {
   const int b = blockIdx.y;
   int tile = blockIdx.x;
   const int sub = tile >= a.tiles[0] ? 1 : 0;
+  const int gtile = tile;
   if (sub) tile -= a.tiles[0];
   const int t0 = tile * a.TT;
   const int t1 = min(t0 + a.TT, a.n[sub]);
-  const int TX = blockDim.x, TY = blockDim.y;
-  const int x = threadIdx.x, y = threadIdx.y;
+  const int TX = blockDim.x, x = threadIdx.x;
   const int32_t* idx = a.idx[sub] + (int64_t)b * a.n[sub];
 
   float mn[kStatMaxV][8], mx[kStatMaxV][8];
@@ -66,7 +72,8 @@ __global__ __launch_bounds__(256) void k_chan_stats(QPArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) { mn[j][i] = INFINITY; mx[j][i] = -INFINITY; }
 
-  for (int t = t0 + y; t < t1; t += TY) {
+#pragma unroll 4
+  for (int t = t0; t < t1; ++t) {
     const int64_t pos = idx[t];
 #pragma unroll
     for (int j = 0; j < kStatMaxV; ++j) {
@@ -80,27 +87,19 @@ __global__ __launch_bounds__(256) void k_chan_stats(QPArgs a) {
       }
     }
   }
-  if (t0 + y >= t1) return;
-  uint32_t* st = a.stats + ((int64_t)(b * 2 + sub) * a.W) * 2;
+  float* out = a.partial + ((int64_t)b * (a.tiles[0] + a.tiles[1]) + gtile) * a.W * 2;
 #pragma unroll
   for (int j = 0; j < kStatMaxV; ++j) {
     const int v = x + j * TX;
     if (v < a.NV) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        atomicMin(&st[(v * 8 + i) * 2], float_key(mn[j][i]));
-        atomicMax(&st[(v * 8 + i) * 2 + 1], float_key(mx[j][i]));
-      }
+      float4* o4 = reinterpret_cast<float4*>(out + (int64_t)v * 16);
+      o4[0] = make_float4(mn[j][0], mx[j][0], mn[j][1], mx[j][1]);
+      o4[1] = make_float4(mn[j][2], mx[j][2], mn[j][3], mx[j][3]);
+      o4[2] = make_float4(mn[j][4], mx[j][4], mn[j][5], mx[j][5]);
+      o4[3] = make_float4(mn[j][6], mx[j][6], mn[j][7], mx[j][7]);
     }
   }
 }
-
-__device__ inline int tile_of_field_group(int bits, int jf) {
-  // Token tile (16 slots) addressed by field group jf of a TGROUP word.
-  return (bits == 2) ? ((jf & 1) * 2 + (jf >> 1)) : jf;
-}
-
-constexpr int kVPT = 2;  // channel vectors per thread in the quantize sweep
 
 // N / R from the correctly rounded reciprocal y = 1/R with one residual
 // correction.  When the true quotient is representable (in particular an exact
@@ -122,67 +121,109 @@ __device__ inline float refined_ratio(float x, float qmax, float R, float y) {
   return fmaf(r, y, q0);
 }
 
-template <int DT, int BITS, int LAYOUT, bool TOKWISE>
-__global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
-  constexpr int E = 32 / BITS;       // tokens per unit = code fields per 32-bit word
-  constexpr int NJ = E / 4;          // sub-batches of 4 tokens
-  constexpr int TB = 4 * E;          // slots per TGROUP block
-  constexpr float QMAX = (float)((1 << BITS) - 1);
-  __shared__ float red[2][4][16];    // cross-wave min / max of 4 tokens (<= 16 waves)
+// grid (ceil(W / 64), 2 subsets, B), block (64 channels, 4 tile lanes)
+__global__ __launch_bounds__(256) void k_chan_finalize(QPArgs a) {
+  __shared__ float smn[4][64], smx[4][64];
+  const int cx = threadIdx.x, ty = threadIdx.y;
+  const int w = blockIdx.x * 64 + cx, sub = blockIdx.y, b = blockIdx.z;
+  const int n = a.n[sub];
+  const float qmax = (float)((1 << a.bits[sub]) - 1);
+  float lo = INFINITY, hi = -INFINITY;
+  if (w < a.W && n > 0 && a.scheme != ZC_SCHEME_TOKEN) {
+    const int tbeg = sub ? a.tiles[0] : 0, tcnt = a.tiles[sub];
+    const float* p = a.partial + ((int64_t)b * (a.tiles[0] + a.tiles[1]) + tbeg) * a.W * 2 + (int64_t)w * 2;
+#pragma unroll 4
+    for (int t = ty; t < tcnt; t += 4) {
+      const float2 v = *reinterpret_cast<const float2*>(p + (int64_t)t * a.W * 2);
+      lo = fminf(lo, v.x); hi = fmaxf(hi, v.y);
+    }
+  }
+  smn[ty][cx] = lo; smx[ty][cx] = hi;
+  __syncthreads();
+  if (ty == 0 && w < a.W) {
+    lo = fminf(fminf(smn[0][cx], smn[1][cx]), fminf(smn[2][cx], smn[3][cx]));
+    hi = fmaxf(fmaxf(smx[0][cx], smx[1][cx]), fmaxf(smx[2][cx], smx[3][cx]));
+    float cs = 1.f, cz = 0.f;
+    float4 prm = make_float4(1.f, 0.f, 1.f, 0.f);
+    if (n > 0 && a.scheme == ZC_SCHEME_CST) {
+      float c = sqrtf(fmaxf(fabsf(lo), fabsf(hi)));       // Eq. 6
+      if (c == 0.f) c = 1.f;
+      cs = c;
+      prm.x = 1.f / c;
+    } else if (n > 0 && a.scheme == ZC_SCHEME_CHANNEL) {
+      float R = hi - lo;                                     // Eq. 5: s = R / (2^k - 1)
+      if (R == 0.f) R = qmax;                                // max == min: s := 1
+      cs = R / qmax;
+      cz = -rintf(refined_ratio(lo, qmax, R, 1.f / R));
+      prm = make_float4(1.f / R, cz, R, 0.f);
+    }
+    const int64_t o = (int64_t)(sub * a.B + b) * a.W + w;
+    a.chan_scale[o] = cs;
+    a.chan_zero[o] = cz;
+    a.params[(int64_t)(b * 2 + sub) * a.W + w] = prm;
+  }
+  if (blockIdx.x == 0 && sub == 0 && b == 0 && cx == 0 && ty == 0) {
+    a.chunk_row[0] = a.begin[0]; a.chunk_row[1] = a.n[0];
+    a.chunk_row[2] = a.begin[1]; a.chunk_row[3] = a.n[1];
+  }
+}
 
-  const int b = blockIdx.y;
-  int u = blockIdx.x;
-  const int sub = u >= a.units[0] ? 1 : 0;
-  if (sub) u -= a.units[0];
+// ---- wave64 all-reduce through DPP (no LDS traffic) --------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ inline float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+template <bool IS_MAX>
+__device__ inline float wave_allreduce(float v) {
+  auto op = [](float x, float y) { return IS_MAX ? fmaxf(x, y) : fminf(x, y); };
+  v = op(v, dpp_move<0xB1, 0xF>(v));    // quad_perm [1,0,3,2]
+  v = op(v, dpp_move<0x4E, 0xF>(v));    // quad_perm [2,3,0,1]
+  v = op(v, dpp_move<0x141, 0xF>(v));   // row_half_mirror
+  v = op(v, dpp_move<0x140, 0xF>(v));   // row_mirror: every lane of a 16-lane row has the row result
+  v = op(v, dpp_move<0x142, 0xA>(v));   // row_bcast15 into rows 1 and 3
+  v = op(v, dpp_move<0x143, 0xC>(v));   // row_bcast31 into rows 2 and 3: lane 63 has the total
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ inline int tile_of_field_group(int bits, int jf) {
+  // Slot tile (16 slots) addressed by field group jf of a TGROUP word.
+  return (bits == 2) ? ((jf & 1) * 2 + (jf >> 1)) : jf;
+}
+
+constexpr int kVPT = 2;  // channel vectors (8 channels each) per thread in the quantize sweep
+
+template <int DT, int BITS, int LAYOUT, bool TOKWISE>
+__device__ inline void quant_unit(const QPArgs& a, int sub, int u, int b, float (*red)[8][16]) {
+  constexpr int E = 32 / BITS;                       // tokens per unit = code fields per 32-bit word
+  constexpr int TBAT = (DT == ZC_F32) ? 4 : (E < 8 ? E : 8);   // tokens requested at once
+  constexpr int NBAT = E / TBAT;
+  constexpr int TB = 4 * E;                          // slots per TGROUP block
+  constexpr float QMAX = (float)((1 << BITS) - 1);
+  constexpr int RAW = (DT == ZC_F32) ? 2 : 1;        // 16-byte loads per channel vector
+
   const int blk = u >> 2, kg = u & 3;
   const int n = a.n[sub];
   const int TX = blockDim.x, x = threadIdx.x;
   const int lane = x & 63, wave = x >> 6, nwaves = TX >> 6;
   const int32_t* idx = a.idx[sub] + (int64_t)b * n;
 
-  // ---- parameters of the channels this thread owns ------------------------------
-  // CHANNEL: p0 = 1/R, p1 = z, p2 = R with R = max - min (Eq. 5: x/s = x (2^k-1) / R)
-  // tokenwise: p0 = 1/c
+  // parameters of the channels this thread owns
   float p0[kVPT][8], p1[kVPT][8], p2[kVPT][8];
   bool vvalid[kVPT];
+  int64_t xoff[kVPT];
 #pragma unroll
   for (int j = 0; j < kVPT; ++j) {
     const int v = x + j * TX;
     vvalid[j] = v < a.NV;
+    const int w = (vvalid[j] ? v : 0) * 8, h = w / a.D, c = w % a.D;
+    xoff[j] = (int64_t)b * a.sB + (int64_t)h * a.sH + c;
+    const float4* pp = a.params + (int64_t)(b * 2 + sub) * a.W + w;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float cs = 1.f, cz = 0.f;
-      p0[j][i] = 1.f; p1[j][i] = 0.f; p2[j][i] = 1.f;
-      if (vvalid[j] && n > 0 && a.scheme != ZC_SCHEME_TOKEN) {
-        const uint32_t* st = a.stats + ((int64_t)(b * 2 + sub) * a.W + v * 8 + i) * 2;
-        const float lo = key_float(st[0]), hi = key_float(st[1]);
-        if constexpr (TOKWISE) {
-          float c = sqrtf(fmaxf(fabsf(lo), fabsf(hi)));
-          if (c == 0.f) c = 1.f;
-          cs = c;
-          p0[j][i] = 1.f / c;
-        } else {
-          float R = hi - lo;
-          if (R == 0.f) R = QMAX;               // max == min: s := 1
-          cs = R / QMAX;
-          cz = -rintf(refined_ratio(lo, QMAX, R, 1.f / R));
-          p0[j][i] = 1.f / R;
-          p1[j][i] = cz;
-          p2[j][i] = R;
-        }
-      }
-      if (vvalid[j] && u == 0) {
-        const int64_t o = (int64_t)(sub * a.B + b) * a.W + v * 8 + i;
-        a.chan_scale[o] = cs;
-        a.chan_zero[o] = cz;
-      }
+      const float4 t = pp[i];
+      p0[j][i] = t.x; p1[j][i] = t.y; p2[j][i] = t.z;
     }
   }
-  if (blockIdx.x == 0 && b == 0 && x == 0) {
-    a.chunk_row[0] = a.begin[0]; a.chunk_row[1] = a.n[0];
-    a.chunk_row[2] = a.begin[1]; a.chunk_row[3] = a.n[1];
-  }
-  if (blk * TB >= n) return;  // padding unit of an empty subset: parameters only
 
   uint32_t words[kVPT][8];
 #pragma unroll
@@ -191,102 +232,117 @@ __global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
     for (int i = 0; i < 8; ++i) words[j][i] = 0u;
 
 #pragma unroll
-  for (int jf = 0; jf < NJ; ++jf) {
-    const int tile = tile_of_field_group(BITS, jf);
-    float val[4][kVPT][8];
-    int rel[4];
-    float tmin[4], tmax[4];
+  for (int bt = 0; bt < NBAT; ++bt) {
+    // slot (relative to the chunk) and source position of the batch's tokens
+    int rel[TBAT];
+    uint4 raw[TBAT][kVPT][RAW];
 #pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-      rel[v4] = blk * TB + 16 * tile + 4 * kg + v4;
-      tmin[v4] = INFINITY; tmax[v4] = -INFINITY;
-      const bool tv = rel[v4] < n;
-      const int64_t pos = tv ? idx[rel[v4]] : 0;
+    for (int t = 0; t < TBAT; ++t) {
+      const int e = bt * TBAT + t;
+      rel[t] = blk * TB + 16 * tile_of_field_group(BITS, e >> 2) + 4 * kg + (e & 3);
+      const bool tv = rel[t] < n;
+      const int64_t pos = tv ? idx[rel[t]] : 0;
 #pragma unroll
-      for (int j = 0; j < kVPT; ++j) {
-        if (tv && vvalid[j]) {
-          const int w = (x + j * TX) * 8, h = w / a.D, c = w % a.D;
-          load8<DT>(a.x, (int64_t)b * a.sB + (int64_t)h * a.sH + pos * a.sL + c, val[v4][j]);
-        } else {
+      for (int j = 0; j < kVPT; ++j)
 #pragma unroll
-          for (int i = 0; i < 8; ++i) val[v4][j][i] = 0.f;
+        for (int r = 0; r < RAW; ++r) {
+          raw[t][j][r] = make_uint4(0u, 0u, 0u, 0u);
+          if (tv && vvalid[j]) {
+            const char* src = reinterpret_cast<const char*>(a.x) + (xoff[j] + pos * a.sL) * (DT == ZC_F32 ? 4 : 2) + 16 * r;
+            raw[t][j][r] = *reinterpret_cast<const uint4*>(src);
+          }
+        }
+    }
+    auto widen = [&](int t, int j, float (&v)[8]) {
+      if constexpr (DT == ZC_F32) {
+        v[0] = __uint_as_float(raw[t][j][0].x); v[1] = __uint_as_float(raw[t][j][0].y);
+        v[2] = __uint_as_float(raw[t][j][0].z); v[3] = __uint_as_float(raw[t][j][0].w);
+        v[4] = __uint_as_float(raw[t][j][RAW - 1].x); v[5] = __uint_as_float(raw[t][j][RAW - 1].y);
+        v[6] = __uint_as_float(raw[t][j][RAW - 1].z); v[7] = __uint_as_float(raw[t][j][RAW - 1].w);
+      } else {
+        const uint32_t w4[4] = {raw[t][j][0].x, raw[t][j][0].y, raw[t][j][0].z, raw[t][j][0].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[2 * i] = half_bits_to_float<DT>(w4[i] & 0xffffu);
+          v[2 * i + 1] = half_bits_to_float<DT>(w4[i] >> 16);
         }
       }
-    }
-    float inv_r[4], rng[4], zt[4];
+    };
+
+    float rng[TBAT], inv_r[TBAT], zt[TBAT];
     if constexpr (TOKWISE) {
+      float tmin[TBAT], tmax[TBAT];
 #pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
+      for (int t = 0; t < TBAT; ++t) {
+        float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
         for (int j = 0; j < kVPT; ++j) {
           if (vvalid[j]) {
+            float v[8];
+            widen(t, j, v);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              val[v4][j][i] *= p0[j][i];
-              tmin[v4] = fminf(tmin[v4], val[v4][j][i]);
-              tmax[v4] = fmaxf(tmax[v4], val[v4][j][i]);
-            }
+            for (int i = 0; i < 8; ++i) { const float y = v[i] * p0[j][i]; lo = fminf(lo, y); hi = fmaxf(hi, y); }
           }
         }
-        tmin[v4] = wave_min(tmin[v4]);
-        tmax[v4] = wave_max(tmax[v4]);
+        tmin[t] = wave_allreduce<false>(lo);
+        tmax[t] = wave_allreduce<true>(hi);
       }
       if (nwaves > 1) {
         __syncthreads();
         if (lane == 0) {
 #pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) { red[0][v4][wave] = tmin[v4]; red[1][v4][wave] = tmax[v4]; }
+          for (int t = 0; t < TBAT; ++t) { red[0][t][wave] = tmin[t]; red[1][t][wave] = tmax[t]; }
         }
         __syncthreads();
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          float lo = red[0][v4][0], hi = red[1][v4][0];
-          for (int w = 1; w < nwaves; ++w) { lo = fminf(lo, red[0][v4][w]); hi = fmaxf(hi, red[1][v4][w]); }
-          tmin[v4] = lo; tmax[v4] = hi;
+        for (int t = 0; t < TBAT; ++t) {
+          float lo = red[0][t][0], hi = red[1][t][0];
+          for (int w = 1; w < nwaves; ++w) { lo = fminf(lo, red[0][t][w]); hi = fmaxf(hi, red[1][t][w]); }
+          tmin[t] = lo; tmax[t] = hi;
         }
       }
 #pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        float R = tmax[v4] - tmin[v4];
+      for (int t = 0; t < TBAT; ++t) {
+        float R = tmax[t] - tmin[t];
         if (R == 0.f) R = QMAX;                 // max == min: s := 1
-        const float s = R / QMAX;
-        const float z = -rintf(refined_ratio(tmin[v4], QMAX, R, 1.f / R));
-        rng[v4] = R;
-        inv_r[v4] = 1.f / R;
-        zt[v4] = z;
-        if (x == 0 && rel[v4] < n) {
-          const int64_t o = (int64_t)b * a.cap[sub] + a.begin[sub] + rel[v4];
-          a.tok_scale[sub][o] = s;
+        const float y = 1.f / R;
+        const float z = -rintf(refined_ratio(tmin[t], QMAX, R, y));
+        rng[t] = R; inv_r[t] = y; zt[t] = z;
+        if (x == 0 && rel[t] < n) {
+          const int64_t o = (int64_t)b * a.cap[sub] + a.begin[sub] + rel[t];
+          a.tok_scale[sub][o] = R / QMAX;
           a.tok_zero[sub][o] = z;
         }
       }
     }
 #pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-      const bool tv = rel[v4] < n;
+    for (int t = 0; t < TBAT; ++t) {
+      const bool tv = rel[t] < n;
       if (x == 0 && tv && a.pos[sub])
-        a.pos[sub][(int64_t)b * a.cap[sub] + a.begin[sub] + rel[v4]] = (int32_t)(idx[rel[v4]] + a.pos_offset);
+        a.pos[sub][(int64_t)b * a.cap[sub] + a.begin[sub] + rel[t]] = (int32_t)(idx[rel[t]] + a.pos_offset);
 #pragma unroll
       for (int j = 0; j < kVPT; ++j) {
         if (!vvalid[j]) continue;
+        float v[8];
+        widen(t, j, v);
         uint32_t code[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           // Eq. 5: round(x / s) first, then + z, then clip
-          float t;
-          if constexpr (TOKWISE) t = rintf(refined_ratio(val[v4][j][i], QMAX, rng[v4], inv_r[v4])) + zt[v4];
-          else if constexpr (DT == ZC_F32) t = rintf(refined_ratio(val[v4][j][i], QMAX, p2[j][i], p0[j][i])) + p1[j][i];
-          else t = rintf(refined_div(val[v4][j][i] * QMAX, p2[j][i], p0[j][i])) + p1[j][i];   // x * qmax is exact
-          t = __builtin_amdgcn_fmed3f(t, 0.f, QMAX);
-          code[i] = tv ? (uint32_t)t : 0u;
+          float q;
+          if constexpr (TOKWISE) q = rintf(refined_ratio(v[i] * p0[j][i], QMAX, rng[t], inv_r[t])) + zt[t];
+          else if constexpr (DT == ZC_F32) q = rintf(refined_ratio(v[i], QMAX, p2[j][i], p0[j][i])) + p1[j][i];
+          else q = rintf(refined_div(v[i] * QMAX, p2[j][i], p0[j][i])) + p1[j][i];   // x * qmax is exact
+          q = __builtin_amdgcn_fmed3f(q, 0.f, QMAX);
+          code[i] = tv ? (uint32_t)q : 0u;
         }
         if constexpr (LAYOUT == ZC_LAYOUT_TGROUP) {
-          const int e = 4 * jf + v4;
+          const int e = bt * TBAT + t;
 #pragma unroll
           for (int i = 0; i < 8; ++i) words[j][i] |= code[i] << (BITS * e);
         } else if (tv) {
           const int w = (x + j * TX) * 8, h = w / a.D, c = w % a.D;
-          const int64_t slot = a.begin[sub] + rel[v4];
+          const int64_t slot = a.begin[sub] + rel[t];
           uint8_t* row = a.codes[sub] + (((int64_t)b * a.H + h) * a.cap[sub] + slot) * (a.D * BITS / 8) + c * BITS / 8;
           if constexpr (BITS == 8) {
             uint2 o;
@@ -317,34 +373,53 @@ __global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
       const int64_t gblk = a.begin[sub] / TB + blk;
       uint32_t* dst = reinterpret_cast<uint32_t*>(a.codes[sub]) +
                       ((((int64_t)b * a.H + h) * nblk + gblk) * 4 + kg) * a.D + c;
-      uint4 o0 = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
-      uint4 o1 = make_uint4(words[j][4], words[j][5], words[j][6], words[j][7]);
-      reinterpret_cast<uint4*>(dst)[0] = o0;
-      reinterpret_cast<uint4*>(dst)[1] = o1;
+      reinterpret_cast<uint4*>(dst)[0] = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+      reinterpret_cast<uint4*>(dst)[1] = make_uint4(words[j][4], words[j][5], words[j][6], words[j][7]);
     }
   }
 }
 
-template <int DT, int BITS, int LAYOUT>
-static void launch_qp2(const QPArgs& a, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
-  if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, BITS, LAYOUT, true>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((k_quant_pack<DT, BITS, LAYOUT, false>), grid, block, 0, st, a);
+template <int DT, int LAYOUT, bool TOKWISE>
+__global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
+  __shared__ float red[2][8][16];    // cross-wave min / max of a batch of tokens (<= 16 waves)
+  const int b = blockIdx.y;
+  int u = blockIdx.x;
+  const int sub = u >= a.units[0] ? 1 : 0;
+  if (sub) u -= a.units[0];
+  const int bits = a.bits[sub];
+  if (bits == 4) quant_unit<DT, 4, LAYOUT, TOKWISE>(a, sub, u, b, red);
+  else if (bits == 2) quant_unit<DT, 2, LAYOUT, TOKWISE>(a, sub, u, b, red);
+  else quant_unit<DT, 8, LAYOUT, TOKWISE>(a, sub, u, b, red);
 }
-template <int DT, int BITS>
-static void launch_qp1(const QPArgs& a, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
-  if (layout == ZC_LAYOUT_ROW) launch_qp2<DT, BITS, ZC_LAYOUT_ROW>(a, tokwise, grid, block, st);
-  else launch_qp2<DT, BITS, ZC_LAYOUT_TGROUP>(a, tokwise, grid, block, st);
-}
+
 template <int DT>
-static void launch_qp0(const QPArgs& a, int bits, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
-  if (bits == 2) launch_qp1<DT, 2>(a, layout, tokwise, grid, block, st);
-  else if (bits == 4) launch_qp1<DT, 4>(a, layout, tokwise, grid, block, st);
-  else launch_qp1<DT, 8>(a, layout, tokwise, grid, block, st);
+static void launch_qp(const QPArgs& a, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
+  if (layout == ZC_LAYOUT_ROW) {
+    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, false>), grid, block, 0, st, a);
+  } else {
+    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, false>), grid, block, 0, st, a);
+  }
+}
+
+static int64_t stats_tiles(int64_t B, int64_t n_tokens, int* TT_out) {
+  const int TT = stats_tile_tokens(B * n_tokens);
+  if (TT_out) *TT_out = TT;
+  return ceil_div64(n_tokens, TT) + 1;     // two subsets: at most one extra ragged tile
 }
 
 }  // namespace zc
 
 using namespace zc;
+
+extern "C" size_t zc_quantize_pack_workspace(int64_t B, int64_t H, int64_t L, int64_t D) {
+  if (B <= 0 || H <= 0 || D <= 0 || L < 0) return 0;
+  const int64_t W = H * D;
+  const size_t params = (size_t)align_up64(B * 2 * W * (int64_t)sizeof(float4), 256);
+  const size_t partial = (size_t)B * stats_tiles(B, L, nullptr) * W * 2 * sizeof(float);
+  return params + partial;
+}
 
 extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
                                 const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
@@ -363,7 +438,7 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   const int64_t end_hi = align_up64(out->n_hi + k, ZC_SLOT_ALIGN);
   const int64_t end_lo = align_up64(out->n_lo + n_reg, ZC_SLOT_ALIGN);
   if (end_hi > out->cap_hi || end_lo > out->cap_lo) return ZC_ERR_CAPACITY;
-  const size_t need = zc_quantize_pack_workspace(x->B, x->H, x->D);
+  const size_t need = zc_quantize_pack_workspace(x->B, x->H, k + n_reg, x->D);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
 
   hipStream_t st = (hipStream_t)stream;
@@ -373,6 +448,7 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   a.idx[0] = salient_idx; a.idx[1] = regular_idx;
   a.n[0] = (int)k; a.n[1] = (int)n_reg;
   a.begin[0] = (int)out->n_hi; a.begin[1] = (int)out->n_lo;
+  a.bits[0] = out->bits_hi; a.bits[1] = out->bits_lo;
   a.cap[0] = out->cap_hi; a.cap[1] = out->cap_lo;
   a.codes[0] = out->codes_hi; a.codes[1] = out->codes_lo;
   a.tok_scale[0] = out->tok_scale_hi; a.tok_zero[0] = out->tok_zero_hi;
@@ -381,48 +457,39 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   const int64_t chunk_off = (int64_t)out->n_chunks * 2 * x->B * W;
   a.chan_scale = out->chan_scale + chunk_off;
   a.chan_zero = out->chan_zero + chunk_off;
-  a.stats = reinterpret_cast<uint32_t*>(ws);
+  a.params = reinterpret_cast<float4*>(ws);
+  a.partial = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + align_up64(x->B * 2 * W * (int64_t)sizeof(float4), 256));
   a.chunk_row = out->chunk_table + 4 * out->n_chunks;
   a.pos_offset = pos_offset;
   a.scheme = out->scheme;
+  int TT;
+  stats_tiles(x->B, k + n_reg, &TT);
+  a.TT = TT;
+  a.tiles[0] = (int)ceil_div64(k, TT);
+  a.tiles[1] = (int)ceil_div64(n_reg, TT);
+  a.units[0] = (int)ceil_div64(k, 4 * (32 / out->bits_hi)) * 4;
+  a.units[1] = (int)ceil_div64(n_reg, 4 * (32 / out->bits_lo)) * 4;
 
-  // ---- sweep 1: channel statistics ---------------------------------------------
-  if (out->scheme != ZC_SCHEME_TOKEN && (k > 0 || n_reg > 0)) {
-    const int64_t pairs = x->B * 2 * W;
-    hipLaunchKernelGGL(k_stats_init, dim3((unsigned)ceil_div64(pairs, 256)), dim3(256), 0, st, a.stats, pairs);
-    ZC_LAUNCH_CHECK();
-    int TT = (int)ceil_div64(x->B * (k + n_reg), 1024);
-    TT = TT < 16 ? 16 : (TT > 64 ? 64 : TT);
-    a.TT = TT;
-    a.tiles[0] = (int)ceil_div64(k, TT);
-    a.tiles[1] = (int)ceil_div64(n_reg, TT);
-    int TX = a.NV >= 256 ? 256 : (int)align_up64(a.NV, 64);
-    int TY = 256 / TX;
-    dim3 grid((unsigned)(a.tiles[0] + a.tiles[1]), (unsigned)x->B), block(TX, TY);
+  // ---- sweep 1: channel statistics (partials) -----------------------------------
+  if (out->scheme != ZC_SCHEME_TOKEN && a.tiles[0] + a.tiles[1] > 0) {
+    const int TX = a.NV >= 256 ? 256 : (int)align_up64(a.NV, 64);
+    dim3 grid((unsigned)(a.tiles[0] + a.tiles[1]), (unsigned)x->B), block(TX);
     if (x->dtype == ZC_F32) hipLaunchKernelGGL(k_chan_stats<ZC_F32>, grid, block, 0, st, a);
     else if (x->dtype == ZC_F16) hipLaunchKernelGGL(k_chan_stats<ZC_F16>, grid, block, 0, st, a);
     else hipLaunchKernelGGL(k_chan_stats<ZC_BF16>, grid, block, 0, st, a);
     ZC_LAUNCH_CHECK();
-  } else {
-    a.TT = 16; a.tiles[0] = a.tiles[1] = 0;
   }
-
-  // ---- sweep 2: quantize + pack, one launch per subset width ---------------------
-  const bool tokwise = out->scheme != ZC_SCHEME_CHANNEL;
-  const int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
-  for (int sub = 0; sub < 2; ++sub) {
-    const int bits = sub == 0 ? out->bits_hi : out->bits_lo;
-    const int TB = 4 * (32 / bits);
-    QPArgs s = a;
-    // each launch covers one subset: the other subset gets zero units
-    int units = (int)ceil_div64(a.n[sub], TB) * 4;
-    if (units == 0) units = 1;  // still writes the (default) channel parameters
-    s.units[0] = sub == 0 ? units : 0;
-    s.units[1] = sub == 1 ? units : 0;
-    dim3 grid((unsigned)units, (unsigned)x->B), block(TXq);
-    if (x->dtype == ZC_F32) launch_qp0<ZC_F32>(s, bits, out->layout, tokwise, grid, block, st);
-    else if (x->dtype == ZC_F16) launch_qp0<ZC_F16>(s, bits, out->layout, tokwise, grid, block, st);
-    else launch_qp0<ZC_BF16>(s, bits, out->layout, tokwise, grid, block, st);
+  // ---- parameters (also for empty subsets and the tokenwise scheme: defaults) ------
+  hipLaunchKernelGGL(k_chan_finalize, dim3((unsigned)ceil_div64(W, 64), 2, (unsigned)x->B), dim3(64, 4), 0, st, a);
+  ZC_LAUNCH_CHECK();
+  // ---- sweep 2: quantize + pack ---------------------------------------------------
+  if (a.units[0] + a.units[1] > 0) {
+    const bool tokwise = out->scheme != ZC_SCHEME_CHANNEL;
+    const int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
+    dim3 grid((unsigned)(a.units[0] + a.units[1]), (unsigned)x->B), block(TXq);
+    if (x->dtype == ZC_F32) launch_qp<ZC_F32>(a, out->layout, tokwise, grid, block, st);
+    else if (x->dtype == ZC_F16) launch_qp<ZC_F16>(a, out->layout, tokwise, grid, block, st);
+    else launch_qp<ZC_BF16>(a, out->layout, tokwise, grid, block, st);
     ZC_LAUNCH_CHECK();
   }
 
