@@ -9,9 +9,9 @@
 //   2. k_chan_finalize  reduces the partials and turns them once into the
 //                       parameters the quantizer needs (Eq. 5's R = max - min,
 //                       1/R and z per channel, or Eq. 6's c and 1/c).
-//   3. k_quant_pack     a team of waves owns one "unit" of E = 32/bits tokens
-//                       (the tokens that share 32-bit words in the TGROUP
-//                       layout): all rows of a batch of tokens are requested at
+//   3. k_quant_pack     a team of waves owns one "unit" of up to 8 tokens that
+//                       share 32-bit words (or their 16-bit halves) in the TGROUP
+//                       layout: all rows of the unit's tokens are requested at
 //                       once, per-token min / max by DPP wave reduction for the
 //                       tokenwise schemes, tie-exact x (2^k-1) / R, round half to
 //                       even, + z, clamp, pack along channels (ROW layout) or along
@@ -72,20 +72,33 @@ __global__ __launch_bounds__(256) void k_chan_stats(QPArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) { mn[j][i] = INFINITY; mx[j][i] = -INFINITY; }
 
-#pragma unroll 4
-  for (int t = t0; t < t1; ++t) {
-    const int64_t pos = idx[t];
+  for (int tb = t0; tb < t1; tb += 8) {
+    // all rows of the batch are requested before any is reduced
+    float vals[8][kStatMaxV][8];
+    bool live[8];
 #pragma unroll
-    for (int j = 0; j < kStatMaxV; ++j) {
-      const int v = x + j * TX;
-      if (v < a.NV) {
-        const int w = v * 8, h = w / a.D, c = w % a.D;
-        float vals[8];
-        load8<DT>(a.x, (int64_t)b * a.sB + (int64_t)h * a.sH + pos * a.sL + c, vals);
+    for (int t = 0; t < 8; ++t) {
+      live[t] = tb + t < t1;
+      const int64_t pos = live[t] ? idx[tb + t] : 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { mn[j][i] = fminf(mn[j][i], vals[i]); mx[j][i] = fmaxf(mx[j][i], vals[i]); }
+      for (int j = 0; j < kStatMaxV; ++j) {
+        const int v = x + j * TX;
+        if (live[t] && v < a.NV) {
+          const int w = v * 8, h = w / a.D, c = w % a.D;
+          load8<DT>(a.x, (int64_t)b * a.sB + (int64_t)h * a.sH + pos * a.sL + c, vals[t][j]);
+        }
       }
     }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+      for (int j = 0; j < kStatMaxV; ++j) {
+        const int v = x + j * TX;
+        if (live[t] && v < a.NV) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) { mn[j][i] = fminf(mn[j][i], vals[t][j][i]); mx[j][i] = fmaxf(mx[j][i], vals[t][j][i]); }
+        }
+      }
   }
   float* out = a.partial + ((int64_t)b * (a.tiles[0] + a.tiles[1]) + gtile) * a.W * 2;
 #pragma unroll
@@ -190,18 +203,20 @@ __device__ inline int tile_of_field_group(int bits, int jf) {
   return (bits == 2) ? ((jf & 1) * 2 + (jf >> 1)) : jf;
 }
 
-constexpr int kVPT = 2;  // channel vectors (8 channels each) per thread in the quantize sweep
+constexpr int kVPT = 1;  // channel vectors (8 channels each) per thread in the quantize sweep
 
 template <int DT, int BITS, int LAYOUT, bool TOKWISE>
 __device__ inline void quant_unit(const QPArgs& a, int sub, int u, int b, float (*red)[8][16]) {
-  constexpr int E = 32 / BITS;                       // tokens per unit = code fields per 32-bit word
-  constexpr int TBAT = (DT == ZC_F32) ? 4 : (E < 8 ? E : 8);   // tokens requested at once
-  constexpr int NBAT = E / TBAT;
+  constexpr int E = 32 / BITS;                       // code fields per 32-bit TGROUP word
+  constexpr int TU = E < 8 ? E : 8;                  // tokens per unit: a word, or half of a 2-bit word
+  constexpr int UW = E / TU;                         // units that share a word
+  constexpr int TBAT = (DT == ZC_F32) ? 4 : TU;      // tokens requested at once
+  constexpr int NBAT = TU / TBAT;
   constexpr int TB = 4 * E;                          // slots per TGROUP block
   constexpr float QMAX = (float)((1 << BITS) - 1);
   constexpr int RAW = (DT == ZC_F32) ? 2 : 1;        // 16-byte loads per channel vector
 
-  const int blk = u >> 2, kg = u & 3;
+  const int blk = u / (4 * UW), kg = (u / UW) & 3, hf = u % UW;     // unit = (block, k-group, part of the word)
   const int n = a.n[sub];
   const int TX = blockDim.x, x = threadIdx.x;
   const int lane = x & 63, wave = x >> 6, nwaves = TX >> 6;
@@ -238,7 +253,7 @@ __device__ inline void quant_unit(const QPArgs& a, int sub, int u, int b, float 
     uint4 raw[TBAT][kVPT][RAW];
 #pragma unroll
     for (int t = 0; t < TBAT; ++t) {
-      const int e = bt * TBAT + t;
+      const int e = hf * TU + bt * TBAT + t;
       rel[t] = blk * TB + 16 * tile_of_field_group(BITS, e >> 2) + 4 * kg + (e & 3);
       const bool tv = rel[t] < n;
       const int64_t pos = tv ? idx[rel[t]] : 0;
@@ -337,7 +352,7 @@ __device__ inline void quant_unit(const QPArgs& a, int sub, int u, int b, float 
           code[i] = tv ? (uint32_t)q : 0u;
         }
         if constexpr (LAYOUT == ZC_LAYOUT_TGROUP) {
-          const int e = bt * TBAT + t;
+          const int e = bt * TBAT + t;             // field inside this unit's part of the word
 #pragma unroll
           for (int i = 0; i < 8; ++i) words[j][i] |= code[i] << (BITS * e);
         } else if (tv) {
@@ -373,8 +388,15 @@ __device__ inline void quant_unit(const QPArgs& a, int sub, int u, int b, float 
       const int64_t gblk = a.begin[sub] / TB + blk;
       uint32_t* dst = reinterpret_cast<uint32_t*>(a.codes[sub]) +
                       ((((int64_t)b * a.H + h) * nblk + gblk) * 4 + kg) * a.D + c;
-      reinterpret_cast<uint4*>(dst)[0] = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
-      reinterpret_cast<uint4*>(dst)[1] = make_uint4(words[j][4], words[j][5], words[j][6], words[j][7]);
+      if constexpr (UW == 1) {
+        reinterpret_cast<uint4*>(dst)[0] = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
+        reinterpret_cast<uint4*>(dst)[1] = make_uint4(words[j][4], words[j][5], words[j][6], words[j][7]);
+      } else {
+        // this unit fills 16 bits of each word; the other half belongs to a neighbouring workgroup
+        uint16_t* d16 = reinterpret_cast<uint16_t*>(dst) + hf;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d16[2 * i] = (uint16_t)words[j][i];
+      }
     }
   }
 }
@@ -467,8 +489,9 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   a.TT = TT;
   a.tiles[0] = (int)ceil_div64(k, TT);
   a.tiles[1] = (int)ceil_div64(n_reg, TT);
-  a.units[0] = (int)ceil_div64(k, 4 * (32 / out->bits_hi)) * 4;
-  a.units[1] = (int)ceil_div64(n_reg, 4 * (32 / out->bits_lo)) * 4;
+  // units of min(32 / bits, 8) tokens; a TGROUP block holds 4 * (32 / bits) slots
+  a.units[0] = (int)ceil_div64(k, 4 * (32 / out->bits_hi)) * (out->bits_hi == 2 ? 8 : 4);
+  a.units[1] = (int)ceil_div64(n_reg, 4 * (32 / out->bits_lo)) * (out->bits_lo == 2 ? 8 : 4);
 
   // ---- sweep 1: channel statistics (partials) -----------------------------------
   if (out->scheme != ZC_SCHEME_TOKEN && a.tiles[0] + a.tiles[1] > 0) {

@@ -40,15 +40,32 @@ __global__ __launch_bounds__(kSelThreads) void k_select_salient(
         if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
       }
       __syncthreads();
-      if (tid == 0) {
-        int rem = need;
-        int bin = 255;
-        for (; bin > 0; --bin) {
-          if (hist[bin] >= rem) break;
-          rem -= hist[bin];
+      // suffix sums over the bins (largest digit first): thread d owns bin d
+      if (tid < 256) {
+        const int lane_ = tid & 63, wv = tid >> 6;
+        int suf = hist[tid];                         // becomes sum of bins >= tid inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_down(suf, o);
+          if (lane_ + o < 64) suf += t;
         }
-        s_prefix = prefix | ((uint32_t)bin << shift);
-        s_need = rem;
+        if (lane_ == 0) s_wave_gt[wv] = suf;         // wave totals (array reused as scratch)
+      }
+      __syncthreads();
+      if (tid < 256) {
+        const int lane_ = tid & 63, wv = tid >> 6;
+        int suf = hist[tid];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_down(suf, o);
+          if (lane_ + o < 64) suf += t;
+        }
+        for (int w2 = wv + 1; w2 < 4; ++w2) suf += s_wave_gt[w2];
+        const int above = suf - hist[tid];           // elements in bins > tid
+        if (above < need && suf >= need) {           // exactly one bin satisfies this
+          s_prefix = prefix | ((uint32_t)tid << shift);
+          s_need = need - above;
+        }
       }
       __syncthreads();
       prefix = s_prefix;
