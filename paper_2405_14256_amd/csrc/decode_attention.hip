@@ -388,7 +388,8 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     const int32_t* rv = Vp->chunk_table_host + 4 * ci;
     for (int i = 0; i < 4; ++i)
       if (rk[i] != rv[i]) return ZC_ERR_INVALID_ARG;
-    const int64_t nh = ceil_div64(rk[1], 4 * (32 / Kp->bits_hi)), nl = ceil_div64(rk[3], 4 * (32 / Kp->bits_lo));
+    int64_t nh = ceil_div64(rk[1], 4 * (32 / Kp->bits_hi)), nl = ceil_div64(rk[3], 4 * (32 / Kp->bits_lo));
+    if (mfma_path) { nh = ceil_div64(rk[1], 32); nl = ceil_div64(rk[3], 32); }   // half-blocks of 32 slots
     units += nh + nl;
     if (mfma_path) units += (nh > 0 ? kSegCost : 0) + (nl > 0 ? kSegCost : 0);   // the MFMA kernel splits a cost line
   }
@@ -425,7 +426,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     // a workgroup is four waves; give every wave about two units before splitting further
     const int64_t want = ceil_div64(units, 6);
     if (S > want) S = (int)(want > 0 ? want : 1);
-    if (S > 16) S = 16;     // the last workgroup reads at most 16 partials per head
+    if (S > 32) S = 32;     // the reduce kernel reads at most 32 partials per head
   } else if (S > units) {
     S = (int)(units > 0 ? units : 1);
   }

@@ -12,8 +12,8 @@
 // (m, Z, o) and k_decode_reduce reduces them (a kernel boundary is the cheapest
 // device-wide release / acquire on this part: in-kernel fences cost more).
 // The run of a workgroup is cut on a cost line where every segment start counts
-// as kSegCost blocks, so that small streaming chunks do not pile up on one
-// workgroup.
+// as kSegCost half-blocks (a half-block is 32 slots: equal compute at either bit
+// width), so that small streaming chunks do not pile up on one workgroup.
 //
 // Both products run on v_mfma_f32_16x16x32_f16 with the codes as one operand:
 //   logits  D[token][n]   = sum_c code[token][c] * q'[n][c]      (A = K codes, ROW layout)
@@ -42,7 +42,7 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
 constexpr float kLoScale = 2048.f;          // residual operand is scaled by 2^11
 constexpr float kLoInv = 1.f / 2048.f;
-constexpr int kCombineMax = 16;             // most workgroups per (batch, KV head) on this path
+constexpr int kCombineMax = 32;             // most workgroups per (batch, KV head) on this path
 
 __device__ inline f4 mfma16(u4 a, u4 b, f4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
@@ -272,7 +272,8 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     constexpr float SC = (BITS == 4) ? 16.f : 4.f;
     constexpr int KW = D * BITS / 128;       // 32-bit words of K codes per lane and token
     const int64_t chan_off = ((int64_t)(ci * 2 + sub) * a.B + b) * (a.Hkv * D) + hk * D;
-    const int wlo = lo + (hi - lo) * wave / 4, whi = lo + (hi - lo) * (wave + 1) / 4;
+    // lo, hi: this workgroup's range of the segment in half-blocks; split over the waves
+    const int hlo = lo + (hi - lo) * wave / 4, hhi = lo + (hi - lo) * (wave + 1) / 4;
 
     const int64_t bh = (int64_t)b * a.Hkv + hk;
     const int64_t nblk = a.cap[sub] / TB;
@@ -311,7 +312,6 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
       for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const uint4*>(vbase + 4 * (n + 16 * r));
     };
 
-    const int hlo = wlo * NH, hhi = whi * NH;
     Buf cur;
     if (hlo < hhi) load_half(hlo, cur);       // in flight while the operand is built
     // channel parameters of the values, needed when the segment is folded
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     u4 qB[KS];
     float sumqq, sumqqcz;
     build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, qB, sumqq, sumqqcz);
-    if (wlo >= whi) return;
+    if (hlo >= hhi) return;
     const float Aq = sumqq / SC;
     const float kconst = -(sumqq + sumqqcz / SC);     // removes the "1" terms and sum q' cz
 
@@ -436,9 +436,9 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
       else { begin = a.chunk_table[4 * ci + 2 * sub]; len = a.chunk_table[4 * ci + 2 * sub + 1]; }
       const int bits = a.bits[sub];
       const int TB = 4 * (32 / bits);
-      const int nb = ceil_div(len, TB);
+      const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
       if (nb == 0) continue;
-      const int seg0 = cursor + kSegCost;        // the segment's blocks sit after its start-up slots
+      const int seg0 = cursor + kSegCost;        // the segment's half-blocks sit after its start-up slots
       cursor = seg0 + nb;
       const int lo = max(u0 - seg0, 0), hi = min(u1 - seg0, nb);
       if (lo >= hi) continue;
