@@ -7,6 +7,7 @@ namespace zc {
 
 constexpr int kTailUnit = 32;    // tail tokens per work unit of the MFMA decode kernel
 constexpr int kMaxSplits = 128;
+constexpr int kTailSplits = 8;    // most workgroups per (batch, KV head) that share the tail
 constexpr int kSegCost = 3;        // cost, in blocks, charged for starting a segment (query operand)
 constexpr int kInlineChunks = 12;  // chunk-table rows that travel in the kernel arguments
 
@@ -37,7 +38,8 @@ struct DecArgs {
   int64_t tk_sB, tk_sH, tk_sL, tv_sB, tv_sH, tv_sL;
   int tail_len;
   float scale_log2;
-  int S, n_units;
+  int S, n_units;  // workgroups per (batch, KV head); length of the packed cache's cost line
+  int S_packed;    // the first S_packed workgroups split the packed cache, the others the tail
   float* part_m;   // [B, Hq, S]
   float* part_z;   // [B, Hq, S]
   float* part_o;   // [B, Hq, S, D]

@@ -345,7 +345,7 @@ using namespace zc;
 
 extern "C" size_t zc_decode_attention_workspace(int64_t B, int64_t Hq, int64_t D) {
   if (B <= 0 || Hq <= 0 || D <= 0) return 0;
-  return (size_t)B * Hq * split_cap(B, Hq) * (D + 2) * sizeof(float);
+  return (size_t)B * Hq * (split_cap(B, Hq) + kTailSplits) * (D + 2) * sizeof(float);
 }
 
 extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
@@ -393,8 +393,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     units += nh + nl;
     if (mfma_path) units += (nh > 0 ? kSegCost : 0) + (nl > 0 ? kSegCost : 0);   // the MFMA kernel splits a cost line
   }
-  units += ceil_div64(tail_len, mfma_path ? kTailUnit : kTailBlock);
-  if (mfma_path && tail_len > 0) units += kSegCost;
+  if (!mfma_path) units += ceil_div64(tail_len, kTailBlock);   // the MFMA kernel gives the tail workgroups of its own
   if (units > 0x7fffffff) return ZC_ERR_UNSUPPORTED;
 
   DecArgs a;
@@ -422,11 +421,19 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)q->D) : sm_scale) * kLog2e;
   a.n_units = (int)units;
   int S = split_cap(q->B, q->H);
+  a.S_packed = 0;
   if (mfma_path) {
-    // a workgroup is four waves; give every wave about two units before splitting further
+    // tail: one wave per unit of kTailUnit tokens, four waves per workgroup
+    int TW = (int)ceil_div64(ceil_div64(tail_len, kTailUnit), 4);
+    if (TW > kTailSplits) TW = kTailSplits;
+    // packed cache: give every wave about two units before splitting further;
+    // the reduce kernel reads at most 32 partials per head
     const int64_t want = ceil_div64(units, 6);
-    if (S > want) S = (int)(want > 0 ? want : 1);
-    if (S > 32) S = 32;     // the reduce kernel reads at most 32 partials per head
+    if (S > want) S = (int)want;
+    if (S > 32 - TW) S = 32 - TW;
+    if (S + TW == 0) S = 1;          // empty cache: one workgroup writes the zeros
+    a.S_packed = S;
+    S += TW;
   } else if (S > units) {
     S = (int)(units > 0 ? units : 1);
   }

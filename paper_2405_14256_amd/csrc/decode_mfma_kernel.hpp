@@ -1,19 +1,20 @@
 // Matrix-core kernel of zc_decode_attention for 2- and 4-bit caches (Eq. 4 over
 // the packed cache, Algorithm 3's attention line).
 //
-// Work unit: one block of the packed cache (32 slots at 4 bits, 64 at 2 bits:
-// D*16 bytes of K codes and as many of V codes) or 32 tokens of the
-// full-precision tail.  A workgroup takes a contiguous run of units; for every
-// segment (chunk x subset, or the tail) in that run its four waves build the
-// query operand together, then each wave walks its share of the blocks with its
-// own online-softmax state in registers, loading block i+1 while it computes
-// block i; there is no barrier inside that loop.  The waves merge through LDS;
-// when several workgroups share one (batch, KV head) each writes a partial
-// (m, Z, o) and k_decode_reduce reduces them (a kernel boundary is the cheapest
-// device-wide release / acquire on this part: in-kernel fences cost more).
-// The run of a workgroup is cut on a cost line where every segment start counts
-// as kSegCost half-blocks (a half-block is 32 slots: equal compute at either bit
-// width), so that small streaming chunks do not pile up on one workgroup.
+// The packed cache is a cost line of half-blocks (32 slots: 512 B x D/32 of K
+// codes and as many of V codes, equal compute at either bit width) in which
+// every segment (chunk x subset) start also counts as kSegCost half-blocks, so
+// that small streaming chunks do not pile up on one workgroup.  The first
+// S_packed workgroups of a (batch, KV head) cut that line into equal runs; for
+// every segment in its run the four waves of a workgroup build the query operand
+// together, then each wave walks its share of the half-blocks with its own
+// online-softmax state in registers, loading half-block i+1 while it computes
+// half-block i; there is no barrier inside that loop.  The full-precision tail
+// goes to workgroups of its own (one wave per 32 tokens), off the critical path
+// of the packed ones.  The waves merge through LDS; when several workgroups
+// share one (batch, KV head) each writes a partial (m, Z, o) and
+// k_decode_reduce reduces them (a kernel boundary is the cheapest device-wide
+// release / acquire on this part: in-kernel fences cost more).
 //
 // Both products run on v_mfma_f32_16x16x32_f16 with the codes as one operand:
 //   logits  D[token][n]   = sum_c code[token][c] * q'[n][c]      (A = K codes, ROW layout)
@@ -107,6 +108,38 @@ __device__ inline float grp_sum(float x) {
 }
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Eight consecutive elements of a tensor of dtype DT, as loaded (the conversion
+// to float happens where they are used, so that many loads can be in flight).
+template <int DT> struct Raw8 { uint4 a; };
+template <> struct Raw8<ZC_F32> { uint4 a, b; };
+template <int DT>
+__device__ inline Raw8<DT> raw_load8(const void* base, int64_t off, bool valid) {
+  Raw8<DT> r;
+  const uint4 zero = uint4{0u, 0u, 0u, 0u};
+  if constexpr (DT == ZC_F32) {
+    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(base) + off);
+    r.a = valid ? p[0] : zero;
+    r.b = valid ? p[1] : zero;
+  } else {
+    r.a = valid ? *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + off) : zero;
+  }
+  return r;
+}
+template <int DT>
+__device__ inline void raw_to_float(const Raw8<DT>& r, float (&v)[8]) {
+  if constexpr (DT == ZC_F32) {
+    v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
+    v[4] = __uint_as_float(r.b.x); v[5] = __uint_as_float(r.b.y); v[6] = __uint_as_float(r.b.z); v[7] = __uint_as_float(r.b.w);
+  } else {
+    const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = half_bits_to_float<DT>(w[i] & 0xffffu);
+      v[2 * i + 1] = half_bits_to_float<DT>(w[i] >> 16);
+    }
+  }
+}
+
 template <int DT, int D, bool KTOK, bool VTOK>
 __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   constexpr int KS = D / 32;     // k-steps of the logit product
@@ -132,18 +165,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   // running state of this wave
   float m_run = -INFINITY, z_part = 0.f;
   float O[NR][4][2];
-  float Ot[MG][NR];
 #pragma unroll
   for (int r = 0; r < NR; ++r)
 #pragma unroll
     for (int j = 0; j < 4; ++j) { O[r][j][0] = 0.f; O[r][j][1] = 0.f; }
-#pragma unroll
-  for (int gg = 0; gg < MG; ++gg)
-#pragma unroll
-    for (int r = 0; r < NR; ++r) Ot[gg][r] = 0.f;
 
-  // this workgroup's share of the cost line (blocks + kSegCost per segment start)
-  const int u0 = (int)((int64_t)a.n_units * s / a.S), u1 = (int)((int64_t)a.n_units * (s + 1) / a.S);
+  // this workgroup's share of the cost line (half-blocks + kSegCost per segment start)
+  const int sp = max(a.S_packed, 1);
+  const int u0 = (int)((int64_t)a.n_units * s / sp), u1 = (int)((int64_t)a.n_units * (s + 1) / sp);
 
   // When the running maximum of a head grows, everything accumulated so far is
   // rescaled; rare after the first blocks, so it sits behind a wave-uniform branch.
@@ -161,16 +190,6 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
           if (acc) { acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1; }
         }
       if (acc1) { acc1->x *= f0; acc1->y *= f0; acc1->z *= f1; acc1->w *= f1; }
-#pragma unroll 1
-      for (int gg = 0; gg < G; ++gg) {
-        const float fg = __shfl(fac, 2 * gg);
-#pragma unroll
-        for (int g2 = 0; g2 < MG; ++g2)
-          if (g2 == gg) {
-#pragma unroll
-            for (int r = 0; r < NR; ++r) Ot[g2][r] *= fg;
-          }
-      }
     }
     m_run = fmaxf(m_run, m_new);
   };
@@ -263,6 +282,176 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     sumqq = grp_sum(sumqq);
     sumqqcz = grp_sum(sumqqcz);
   };
+
+  // Combines the (m, Z, o) the four waves left in LDS and writes the workgroup's
+  // result: the output itself when it is the only workgroup of its KV head.
+  auto write_result = [&]() {
+    const bool direct = a.S == 1;
+    for (int i = tid; i < G * D; i += 256) {
+      const int gg = i / D, c = i % D;
+      float M = fmaxf(fmaxf(mM[0][gg], mM[1][gg]), fmaxf(mM[2][gg], mM[3][gg]));
+      float o = 0.f, z = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        if (mM[w][gg] > -INFINITY) {
+          const float f = fast_exp2(mM[w][gg] - M);
+          o = fmaf(mO[w][gg][c], f, o);
+          z = fmaf(mZ[w][gg], f, z);
+        }
+      }
+      const int64_t hq = (int64_t)b * a.Hq + hk * G + gg;
+      if (direct) {
+        store1<DT>(a.out, hq * D + c, z > 0.f ? o / z : 0.f);
+        if (a.lse_out && c == 0) a.lse_out[hq] = (M + log2f(z)) * kLn2;
+      } else {
+        a.part_o[(hq * a.S + s) * D + c] = o;
+        if (c == 0) { a.part_m[hq * a.S + s] = M; a.part_z[hq * a.S + s] = z; }
+      }
+    }
+  };
+
+  // ---------------- full-precision tail: workgroups of its own ----------------------------
+  // One wave per unit of kTailUnit tokens.  All K and V rows of the unit are
+  // requested before the query operand is built, so the unit costs one trip to
+  // memory.  Logits on the matrix cores (K rows as the A operand); the weighted
+  // sum of V on the vector ALUs, lane = (token mod TPI, 8 channels).
+  if (s >= a.S_packed && a.tail_len > 0) {
+    constexpr int LPT = D / 8, TPI = 64 / LPT, NI = kTailUnit / TPI;
+    const int tw = s - a.S_packed, n_tw = a.S - a.S_packed;
+    const int n_tail = ceil_div(a.tail_len, kTailUnit);
+    const int tlo = (int)((int64_t)n_tail * tw / n_tw), thi = (int)((int64_t)n_tail * (tw + 1) / n_tw);
+    const int wlo = tlo + (thi - tlo) * wave / 4, whi = tlo + (thi - tlo) * (wave + 1) / 4;
+    const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
+    const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
+    const int vtok = lane / LPT, vch = 8 * (lane % LPT);
+    struct TBuf {
+      Raw8<DT> k[2][KS];
+      Raw8<DT> v[NI];
+    };
+    auto load_unit = [&](int tu, TBuf& bf) {
+      const int t0 = tu * kTailUnit;
+      const int ntok = min(kTailUnit, a.tail_len - t0);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          bf.k[j][ks] = raw_load8<DT>(a.tail_k, kb + (int64_t)(t0 + 16 * j + n) * a.tk_sL + 32 * ks + 8 * grp, 16 * j + n < ntok);
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        bf.v[i] = raw_load8<DT>(a.tail_v, vb + (int64_t)(t0 + i * TPI + vtok) * a.tv_sL + vch, i * TPI + vtok < ntok);
+    };
+    TBuf bf;
+    if (wlo < whi) load_unit(wlo, bf);
+    u4 qB[KS];
+    float dummy0, dummy1;
+    build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, qB, dummy0, dummy1);
+    float Ot[MG][8];
+#pragma unroll
+    for (int gg = 0; gg < MG; ++gg)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) Ot[gg][i] = 0.f;
+
+    for (int tu = wlo; tu < whi; ++tu) {
+      if (tu > wlo) load_unit(tu, bf);
+      const int ntok = min(kTailUnit, a.tail_len - tu * kTailUnit);
+      float U[2][4];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        // rows past the end of the tail are zeros; every lane takes part in the MFMAs
+        f4 s_hi = f4{0.f, 0.f, 0.f, 0.f}, s_lo = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          if constexpr (DT == ZC_F16) {
+            u4 ah; ah.x = bf.k[j][ks].a.x; ah.y = bf.k[j][ks].a.y; ah.z = bf.k[j][ks].a.z; ah.w = bf.k[j][ks].a.w;
+            s_hi = mfma16(ah, qB[ks], s_hi);
+          } else {
+            float kv[8];
+            raw_to_float<DT>(bf.k[j][ks], kv);
+            uint32_t rh[4], rl[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const _Float16 h0 = (_Float16)kv[2 * i], h1 = (_Float16)kv[2 * i + 1];
+              rh[i] = pack_h2(h0, h1);
+              if constexpr (DT == ZC_F32)
+                rl[i] = pack_h2((_Float16)((kv[2 * i] - (float)h0) * kLoScale), (_Float16)((kv[2 * i + 1] - (float)h1) * kLoScale));
+            }
+            u4 ah; ah.x = rh[0]; ah.y = rh[1]; ah.z = rh[2]; ah.w = rh[3];
+            s_hi = mfma16(ah, qB[ks], s_hi);
+            if constexpr (DT == ZC_F32) {
+              u4 al; al.x = rl[0]; al.y = rl[1]; al.z = rl[2]; al.w = rl[3];
+              s_lo = mfma16(al, qB[ks], s_lo);
+            }
+          }
+        }
+        const float own[4] = {s_hi.x + s_lo.x * kLoInv, s_hi.y + s_lo.y * kLoInv, s_hi.z + s_lo.z * kLoInv, s_hi.w + s_lo.w * kLoInv};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) U[j][v] = fmaf(xor1(own[v]), c_oth, own[v] * c_own);
+      }
+      float lmax = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          if (16 * j + 4 * grp + v >= ntok) U[j][v] = -INFINITY;
+          lmax = fmaxf(lmax, U[j][v]);
+        }
+      // a unit holds at least one token, so the new maximum is finite
+      const float m_new = fmaxf(m_run, grp_max(lmax));
+      if (__any(nvalid && m_new > m_run)) {
+        const float fac = (m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
+        z_part *= fac;
+#pragma unroll
+        for (int gg = 0; gg < MG; ++gg) {
+          if (gg < G) {
+            const float fg = __shfl(fac, 2 * gg);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) Ot[gg][i] *= fg;
+          }
+        }
+      }
+      m_run = m_new;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float p = nvalid ? fast_exp2(U[j][v] - m_run) : 0.f;     // 0 past the end of the tail
+          z_part += p;
+          if (nvalid && part == 0) ptile[wave][g][16 * j + 4 * grp + v] = p;
+        }
+      // weighted sum of the unit's V rows (ptile is written and read by this wave only)
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        float vv[8];
+        raw_to_float<DT>(bf.v[i], vv);
+#pragma unroll
+        for (int gg = 0; gg < MG; ++gg) {
+          if (gg < G) {
+            const float p = ptile[wave][gg][i * TPI + vtok];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Ot[gg][e] = fmaf(p, vv[e], Ot[gg][e]);
+          }
+        }
+      }
+    }
+    // merge: sum the token sub-rows, then the four waves through LDS
+    const float z_tot = grp_sum(z_part);
+    if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
+#pragma unroll
+    for (int gg = 0; gg < MG; ++gg) {
+      if (gg < G) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float x = Ot[gg][e];
+#pragma unroll
+          for (int o = LPT; o < 64; o <<= 1) x += __shfl_xor(x, o);
+          if (lane < LPT) mO[wave][gg][vch + e] = x;
+        }
+      }
+    }
+    __syncthreads();
+    write_result();
+    return;
+  }
 
   int cursor = 0;
   // ---------------- packed segments --------------------------------------------------
@@ -447,94 +636,6 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     }
   }
 
-  // ---------------- full-precision tail ------------------------------------------------
-  {
-    const int n_tail = ceil_div(a.tail_len, kTailUnit);
-    const int seg0 = cursor + kSegCost;
-    const int lo = max(u0 - seg0, 0), hi = min(u1 - seg0, n_tail);
-    if (lo < hi) {
-      const int wlo = lo + (hi - lo) * wave / 4, whi = lo + (hi - lo) * (wave + 1) / 4;
-      u4 qB[KS];
-      float dummy0, dummy1;
-      build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, qB, dummy0, dummy1);
-      const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
-      const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
-      for (int tu = wlo; tu < whi; ++tu) {
-        const int t0 = tu * kTailUnit;
-        const int ntok = min(kTailUnit, a.tail_len - t0);
-        float U[2][4];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int tok = 16 * j + n;          // row of the A operand
-          f4 s_hi = f4{0.f, 0.f, 0.f, 0.f}, s_lo = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) {
-            float kv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if (tok < ntok) load8<DT>(a.tail_k, kb + (int64_t)(t0 + tok) * a.tk_sL + 32 * ks + 8 * grp, kv);
-            uint32_t rh[4], rl[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const _Float16 h0 = (_Float16)kv[2 * i], h1 = (_Float16)kv[2 * i + 1];
-              rh[i] = pack_h2(h0, h1);
-              if constexpr (DT == ZC_F32)
-                rl[i] = pack_h2((_Float16)((kv[2 * i] - (float)h0) * kLoScale), (_Float16)((kv[2 * i + 1] - (float)h1) * kLoScale));
-            }
-            u4 ah; ah.x = rh[0]; ah.y = rh[1]; ah.z = rh[2]; ah.w = rh[3];
-            s_hi = mfma16(ah, qB[ks], s_hi);
-            if constexpr (DT == ZC_F32) {
-              u4 al; al.x = rl[0]; al.y = rl[1]; al.z = rl[2]; al.w = rl[3];
-              s_lo = mfma16(al, qB[ks], s_lo);
-            }
-          }
-          // rows past the end of the tail are zeros; every lane takes part in the MFMAs
-          const float own[4] = {s_hi.x + s_lo.x * kLoInv, s_hi.y + s_lo.y * kLoInv, s_hi.z + s_lo.z * kLoInv, s_hi.w + s_lo.w * kLoInv};
-#pragma unroll
-          for (int v = 0; v < 4; ++v) U[j][v] = fmaf(xor1(own[v]), c_oth, own[v] * c_own);
-        }
-        float lmax = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            if (16 * j + 4 * grp + v >= ntok) U[j][v] = -INFINITY;
-            lmax = fmaxf(lmax, U[j][v]);
-          }
-        float da1 = 0.f;
-        rescale_to(fmaxf(m_run, grp_max(lmax)), da1, nullptr, nullptr);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const float p = nvalid ? fast_exp2(U[j][v] - m_run) : 0.f;
-            z_part += p;
-            if (nvalid && part == 0) ptile[wave][g][16 * j + 4 * grp + v] = p;
-          }
-        // weighted sum of the tail values: every lane owns channels lane + 64 r
-#pragma unroll 1
-        for (int t8 = 0; t8 < kTailUnit; t8 += 8) {
-          float vv[NR][8];
-#pragma unroll
-          for (int t = 0; t < 8; ++t)
-#pragma unroll
-            for (int r = 0; r < NR; ++r)
-              vv[r][t] = (t8 + t < ntok) ? load1<DT>(a.tail_v, vb + (int64_t)(t0 + t8 + t) * a.tv_sL + lane + 64 * r) : 0.f;
-#pragma unroll
-          for (int gg = 0; gg < MG; ++gg) {
-            if (gg < G) {
-              const float4 pa = *reinterpret_cast<const float4*>(&ptile[wave][gg][t8]);
-              const float4 pb = *reinterpret_cast<const float4*>(&ptile[wave][gg][t8 + 4]);
-              const float pp[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
-#pragma unroll
-              for (int r = 0; r < NR; ++r)
-#pragma unroll
-                for (int t = 0; t < 8; ++t) Ot[gg][r] = fmaf(pp[t], vv[r][t], Ot[gg][r]);
-            }
-          }
-        }
-      }
-    }
-  }
-
   // ---------------- merge the four waves --------------------------------------------------
   const float z_tot = grp_sum(z_part);
   if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
@@ -547,37 +648,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
       if (g1 < G) mO[wave][g1][c] = O[r][j][1];
     }
   __syncthreads();
-#pragma unroll
-  for (int gg = 0; gg < MG; ++gg) {
-    if (gg < G) {
-#pragma unroll
-      for (int r = 0; r < NR; ++r) mO[wave][gg][lane + 64 * r] += Ot[gg][r];
-    }
-  }
-  __syncthreads();
-
-  const bool direct = a.S == 1;
-  for (int i = tid; i < G * D; i += 256) {
-    const int gg = i / D, c = i % D;
-    float M = fmaxf(fmaxf(mM[0][gg], mM[1][gg]), fmaxf(mM[2][gg], mM[3][gg]));
-    float o = 0.f, z = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      if (mM[w][gg] > -INFINITY) {
-        const float f = fast_exp2(mM[w][gg] - M);
-        o = fmaf(mO[w][gg][c], f, o);
-        z = fmaf(mZ[w][gg], f, z);
-      }
-    }
-    const int64_t hq = (int64_t)b * a.Hq + hk * G + gg;
-    if (direct) {
-      store1<DT>(a.out, hq * D + c, z > 0.f ? o / z : 0.f);
-      if (a.lse_out && c == 0) a.lse_out[hq] = (M + log2f(z)) * kLn2;
-    } else {
-      a.part_o[(hq * a.S + s) * D + c] = o;
-      if (c == 0) { a.part_m[hq * a.S + s] = M; a.part_z[hq * a.S + s] = z; }
-    }
-  }
+  write_result();
 }
 
 // Reduces the partial (m, Z, o) of the workgroups of one query head.
