@@ -19,12 +19,18 @@
 // Both products run on v_mfma_f32_16x16x32_f16 with the codes as one operand:
 //   logits  D[token][n]   = sum_c code[token][c] * q'[n][c]      (A = K codes, ROW layout)
 //   output  D[n][channel] = sum_t w[n][t] * code[t][channel]     (B = V codes, TGROUP layout)
+// A code enters as an fp16 subnormal: masking a packed word leaves the code's
+// bits somewhere in the low ten bits of each 16-bit half, which reads as
+// code * 2^pos * 2^-24 (the matrix cores keep subnormal inputs).  The bit
+// position pos differs from register to register; the other operand carries
+// 2^(P - pos) for the same k index, so every product is code * x * 2^(P - 24) and
+// one exact power of two restores the scale.  Unpacking is one AND per operand
+// register and one shift per packed word.
 // The 16 columns n hold the Hq/Hkv query heads of the KV head twice: the fp16
 // value of the operand (n even) and its rounding residual times 2^11 (n odd), so
-// the fp32 q and softmax weights keep about 21 bits.  A code c enters as the fp16
-// number 1 + c / SC (SC = 16 or 4) built by OR-ing its bits into the mantissa of
-// 1.0; the "1" terms are removed with the sum of the other operand (for the
-// output product that sum comes from one more MFMA against a vector of ones).
+// the fp32 q keeps about 21 bits; the softmax weights are split the same way for
+// fp32 tensors and are single fp16 numbers for 16-bit tensors.  The sum of the
+// weights comes from one more MFMA against the constants 2^(pos - P).
 // The packed layouts are chosen so that the 8 codes a lane feeds to one MFMA are
 // contiguous bits of one 32-bit word, and so that the lane that holds a logit is
 // the lane that must supply the corresponding softmax weight to the second MFMA.
@@ -49,28 +55,62 @@ __device__ inline f4 mfma16(u4 a, u4 b, f4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, b), c, 0, 0, 0);
 }
 
-// fp16 bit patterns of 1 + c/16 for the eight 4-bit codes of w: register i holds
-// code i (low half) and code i + 4 (high half).
+// Two encodings of a code as an fp16 operand element.
+//  * subnormal (16-bit tensors): the masked bits of the packed word, read as
+//    code * 2^pos * 2^-24; the other operand carries 2^(P - pos).  The matrix
+//    cores align the products of one instruction by their nominal exponents, so a
+//    code low in the mantissa loses up to 8 of the 24 accumulator bits; that is far
+//    below what 16-bit outputs resolve, but too coarse for fp32 tensors.
+//  * normalized (fp32 tensors): 1 + code / SC, the code OR-ed into the top mantissa
+//    bits of 1.0 (SC = 16 or 4); the other operand carries SC and the "1" terms are
+//    removed with the sum of the other operand.  Exact to the accumulator's 24 bits.
+// Register i of unpack4 holds code i (low half) and code i + 4 (high half);
+// register i of unpack2 holds codes (i, i + 8) for half 0, (4 + i, 12 + i) for half 1.
+template <bool SUBN>
 __device__ inline u4 unpack4(uint32_t w) {
-  const uint32_t M = 0x03C003C0u, E = 0x3C003C00u;
   u4 r;
-  r.x = ((w << 6) & M) | E;
-  r.y = ((w << 2) & M) | E;
-  r.z = ((w >> 2) & M) | E;
-  r.w = ((w >> 6) & M) | E;
+  if constexpr (SUBN) {
+    const uint32_t t = w >> 8;
+    r.x = w & 0x000F000Fu;
+    r.y = w & 0x00F000F0u;
+    r.z = t & 0x000F000Fu;
+    r.w = t & 0x00F000F0u;
+  } else {
+    const uint32_t M = 0x03C003C0u, E = 0x3C003C00u;
+    r.x = ((w << 6) & M) | E;
+    r.y = ((w << 2) & M) | E;
+    r.z = ((w >> 2) & M) | E;
+    r.w = ((w >> 6) & M) | E;
+  }
   return r;
 }
-// fp16 bit patterns of 1 + c/4 for eight of the sixteen 2-bit codes of w:
-// half 0: register i = codes (i, i + 8); half 1: register i = codes (4 + i, 12 + i).
+template <bool SUBN>
 __device__ inline u4 unpack2(uint32_t w, int half) {
-  const uint32_t M = 0x03000300u, E = 0x3C003C00u;
   if (half) w >>= 8;
   u4 r;
-  r.x = ((w << 8) & M) | E;
-  r.y = ((w << 6) & M) | E;
-  r.z = ((w << 4) & M) | E;
-  r.w = ((w << 2) & M) | E;
+  if constexpr (SUBN) {
+    r.x = w & 0x00030003u;
+    r.y = w & 0x000C000Cu;
+    r.z = w & 0x00300030u;
+    r.w = w & 0x00C000C0u;
+  } else {
+    const uint32_t M = 0x03000300u, E = 0x3C003C00u;
+    r.x = ((w << 8) & M) | E;
+    r.y = ((w << 6) & M) | E;
+    r.z = ((w << 4) & M) | E;
+    r.w = ((w << 2) & M) | E;
+  }
   return r;
+}
+// The factor the other operand carries for operand register i (both halves).
+template <int BITS, bool SUBN> __device__ inline float code_comp(int i) {
+  if constexpr (!SUBN) return BITS == 4 ? 16.f : 4.f;
+  else if constexpr (BITS == 4) return (i & 1) ? 1.f : 16.f;
+  else return (float)(64 >> (2 * i));
+}
+// product of a code and x, divided by what the matrix cores accumulate for it
+template <int BITS, bool SUBN> constexpr float code_unscale() {
+  return SUBN ? (float)(1 << (24 - (BITS == 4 ? 4 : 6))) : 1.f;
 }
 
 __device__ inline uint32_t pack_h2(_Float16 lo, _Float16 hi) {
@@ -78,6 +118,13 @@ __device__ inline uint32_t pack_h2(_Float16 lo, _Float16 hi) {
   __builtin_memcpy(&a, &lo, 2);
   __builtin_memcpy(&b, &hi, 2);
   return (uint32_t)a | ((uint32_t)b << 16);
+}
+
+// Two floats rounded to fp16 in one register (v_cvt_pk_f16_f32).
+__device__ inline uint32_t pack_f2(float lo, float hi) {
+  typedef float f2 __attribute__((ext_vector_type(2)));
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{lo, hi}, h2));
 }
 
 // Splits x into the fp16 nearest to it and the scaled residual; returns the one
@@ -147,12 +194,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   constexpr int MG = ZC_MAX_GROUP;
   __shared__ u4 sqB[KS][64];              // query operand of the current segment
   __shared__ float ssum[2][KS][64];
+  __shared__ float svc[2][D];             // channel scale and zero of V for the current segment
   __shared__ float mO[4][MG][D];
   __shared__ float mM[4][MG], mZ[4][MG];
   __shared__ float ptile[4][MG][kTailUnit];
 
   const int s = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int n = lane & 15, grp = lane >> 4;
   const int G = a.G;
   const int g = n >> 1, part = n & 1;
@@ -160,10 +209,11 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   const int g0 = 2 * grp, g1 = 2 * grp + 1;      // heads of this lane's rows in the output tiles
   // weights of (own, neighbour) column when a head's value and residual columns are added
   const float c_own = part ? kLoInv : 1.f, c_oth = part ? 1.f : kLoInv;
-  const u4 ones = u4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};   // fp16 1.0 x 8
+  constexpr bool WSPLIT = (DT == ZC_F32);    // softmax weights as value + residual
+  constexpr bool SUBN = (DT != ZC_F32);      // codes enter as fp16 subnormals
 
-  // running state of this wave
-  float m_run = -INFINITY, z_part = 0.f;
+  // running state of this wave; unused columns sit at +inf so that their weights are 0
+  float m_run = nvalid ? -INFINITY : INFINITY, z_part = 0.f;
   float O[NR][4][2];
 #pragma unroll
   for (int r = 0; r < NR; ++r)
@@ -174,12 +224,13 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   const int sp = max(a.S_packed, 1);
   const int u0 = (int)((int64_t)a.n_units * s / sp), u1 = (int)((int64_t)a.n_units * (s + 1) / sp);
 
-  // When the running maximum of a head grows, everything accumulated so far is
-  // rescaled; rare after the first blocks, so it sits behind a wave-uniform branch.
-  auto rescale_to = [&](float m_new, float& a1, f4 (*acc)[4], f4* acc1) {
-    const bool changed = nvalid && (m_new > m_run);
-    if (__any(changed)) {
-      const float fac = (m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
+  // The running maximum of a head is only touched when some slot of the
+  // half-block exceeds it (a ballot, no data movement otherwise); everything
+  // accumulated so far is then rescaled.  Rare after the first half-blocks.
+  auto update_max = [&](float lmax, float& a1, f4 (*acc)[4], f4& acc1) {
+    if (__any(nvalid && lmax > m_run)) {
+      const float m_new = fmaxf(m_run, grp_max(lmax));
+      const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
       z_part *= fac; a1 *= fac;
       const float f0 = __shfl(fac, 2 * g0), f1 = __shfl(fac, 2 * g1);
 #pragma unroll
@@ -187,20 +238,21 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           O[r][j][0] *= f0; O[r][j][1] *= f1;
-          if (acc) { acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1; }
+          acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1;
         }
-      if (acc1) { acc1->x *= f0; acc1->y *= f0; acc1->z *= f1; acc1->w *= f1; }
+      acc1.x *= f0; acc1.y *= f0; acc1.z *= f1; acc1.w *= f1;
+      m_run = m_new;
     }
-    m_run = fmaxf(m_run, m_new);
   };
 
   // The query operand of a segment, built once per workgroup: wave w computes
-  // k-step w.  MODE 4 / 2: codes of that width, q' = q cs SC in the channel order
-  // the unpacked K words have; MODE 0: the tail, q itself in natural order.
-  // Returns the operand registers and sum(q''), sum(q'' cz) over all channels.
-  auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, u4 (&qB)[KS], float& sumqq, float& sumqqcz) {
+  // k-step w.  MODE 4 / 2: codes of that width, q' = q cs sm_scale log2(e) times
+  // the factor of its operand register, in the channel order the unpacked K words
+  // have; MODE 0: the tail, q itself in natural order.
+  // Returns the operand registers and sum(q'), sum(q' cz) over all channels.
+  auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, const float* vcs, const float* vcz,
+                                 u4 (&qB)[KS], float& sumqq, float& sumqqcz) {
     constexpr int MODE = decltype(mode_c)::value;
-    constexpr float SC = MODE == 4 ? 16.f : (MODE == 2 ? 4.f : 1.f);
     // q and the channel parameters of this lane's k-step, straight from global
     // memory (issued together with the first block's loads by the caller)
     float q8[8], cs8[8], cz8[8];
@@ -249,20 +301,26 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
           }
       }
     }
-    __syncthreads();     // sqB / ssum of the previous segment are no longer read
+    // the V channel parameters wait in LDS until the segment is folded
+    float vparam = 0.f;
+    if (MODE != 0 && tid < 2 * D) vparam = (tid < D) ? vcs[tid] : vcz[tid - D];
+    __syncthreads();     // sqB / ssum / svc of the previous segment are no longer read
+    if (MODE != 0 && tid < 2 * D) svc[tid / D][tid % D] = vparam;
     if (ks0 < KS) {
       uint32_t regs[4];
       float sq = 0.f, sqz = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         _Float16 hv[2];
+        const float comp = (MODE == 0) ? 1.f : code_comp<MODE == 0 ? 4 : MODE, SUBN>(i);
+        const float inv_comp = 1.f / comp;      // powers of two
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-          const float qv = nvalid ? q8[2 * i + half] * a.scale_log2 * cs8[2 * i + half] * SC : 0.f;
+          const float qv = nvalid ? q8[2 * i + half] * a.scale_log2 * cs8[2 * i + half] * comp : 0.f;
           float rep;
           hv[half] = split_part(qv, part, rep);
-          sq += rep;
-          sqz += rep * cz8[2 * i + half];
+          sq = fmaf(rep, inv_comp, sq);
+          sqz = fmaf(rep * inv_comp, cz8[2 * i + half], sqz);
         }
         regs[i] = pack_h2(hv[0], hv[1]);
       }
@@ -344,7 +402,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     if (wlo < whi) load_unit(wlo, bf);
     u4 qB[KS];
     float dummy0, dummy1;
-    build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, qB, dummy0, dummy1);
+    build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, nullptr, nullptr, qB, dummy0, dummy1);
     float Ot[MG][8];
 #pragma unroll
     for (int gg = 0; gg < MG; ++gg)
@@ -457,149 +515,198 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   // ---------------- packed segments --------------------------------------------------
   auto segment = [&](auto bits_c, int ci, int sub, int begin, int len, int lo, int hi) {
     constexpr int BITS = decltype(bits_c)::value;
-    constexpr int E = 32 / BITS, TB = 4 * E, NT = TB / 16, NH = NT / 2;
-    constexpr float SC = (BITS == 4) ? 16.f : 4.f;
-    constexpr int KW = D * BITS / 128;       // 32-bit words of K codes per lane and token
+    constexpr int TB = 4 * (32 / BITS), NH = TB / 32;   // slots and half-blocks per block
+    constexpr int KW = D * BITS / 128;                  // 32-bit words of K codes per lane and token
+    constexpr int ROWB = D * BITS / 8;                  // bytes of one K row
+    constexpr float UNSCALE = code_unscale<BITS, SUBN>();
+    constexpr float SC = (BITS == 4) ? 16.f : 4.f;     // normalized encoding: 1 + code / SC
     const int64_t chan_off = ((int64_t)(ci * 2 + sub) * a.B + b) * (a.Hkv * D) + hk * D;
     // lo, hi: this workgroup's range of the segment in half-blocks; split over the waves
     const int hlo = lo + (hi - lo) * wave / 4, hhi = lo + (hi - lo) * (wave + 1) / 4;
 
+    // Buffer resources over this (batch, KV head)'s part of each array: the
+    // per-lane offset is fixed, the half-block adds a scalar offset, reads past
+    // the end return zeros.  (The host checks that each part is below 4 GiB.)
     const int64_t bh = (int64_t)b * a.Hkv + hk;
-    const int64_t nblk = a.cap[sub] / TB;
-    const uint8_t* kbase = a.kc[sub] + bh * a.cap[sub] * (D * BITS / 8) + grp * (KW * 4);
+    const uint32_t code_bytes = (uint32_t)(a.cap[sub] * ROWB);
+    const uint32_t tok_bytes = (uint32_t)(a.cap[sub] * 4);
+    constexpr int kRsrcFlags = 0x00020000;              // raw 32-bit data, no swizzle
+    const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.kc[sub] + bh * (int64_t)code_bytes), 0, code_bytes, kRsrcFlags);
+    const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(a.vc[sub]) + bh * (int64_t)code_bytes), 0, code_bytes, kRsrcFlags);
     const int64_t tokbase = (int64_t)b * a.cap[sub];
+    const auto rs_kts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? a.k_ts[sub] + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
+    const auto rs_ktz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? a.k_tz[sub] + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
+    const auto rs_vts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? a.v_ts[sub] + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
+    const auto rs_vtz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? a.v_tz[sub] + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
+    const int voff_k = n * ROWB + grp * (KW * 4);
+    const int voff_v = grp * (D * 4) + 16 * n;
+    const int voff_t = 16 * grp;
 
     // The loop runs over half-blocks of 32 slots (two 16-slot tiles): a 4-bit block
     // is one of them, a 2-bit block two that share the same V words.
     struct Buf {
       uint32_t kw[2][KW];
-      uint4 vw[NR];
-      float4 kts[2], ktz[2], vts[2], vtz[2];
+      u4 vw[NR];
+      u4 kts[2], ktz[2], vts[2], vtz[2];
     };
     auto load_half = [&](int hb, Buf& bf) {
-      const int blk = hb / NH, h = hb % NH;
-      const int slot0 = begin + blk * TB;
+      const int hslot = begin + 32 * hb;               // first slot of the half-block
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const int j = 2 * h + jj;
-        const uint32_t* kp = reinterpret_cast<const uint32_t*>(kbase + (int64_t)(slot0 + 16 * j + n) * (D * BITS / 8));
-        if constexpr (KW == 4) { const uint4 t = *reinterpret_cast<const uint4*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; bf.kw[jj][2] = t.z; bf.kw[jj][3] = t.w; }
-        else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; }
-        else { bf.kw[jj][0] = *kp; }
-        const int64_t to = tokbase + slot0 + 16 * j + 4 * grp;
+        const int so = (int)((uint32_t)(hslot + 16 * jj) * (uint32_t)ROWB);
+        if constexpr (KW == 4) {
+          const u4 t = __builtin_amdgcn_raw_buffer_load_b128(rs_k, voff_k, so, 0);
+          bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; bf.kw[jj][2] = t.z; bf.kw[jj][3] = t.w;
+        } else if constexpr (KW == 2) {
+          const auto t = __builtin_amdgcn_raw_buffer_load_b64(rs_k, voff_k, so, 0);
+          bf.kw[jj][0] = t[0]; bf.kw[jj][1] = t[1];
+        } else {
+          bf.kw[jj][0] = __builtin_amdgcn_raw_buffer_load_b32(rs_k, voff_k, so, 0);
+        }
+        const int to = (int)((uint32_t)(hslot + 16 * jj) * 4u);
         if constexpr (KTOK) {
-          bf.kts[jj] = *reinterpret_cast<const float4*>(a.k_ts[sub] + to);
-          bf.ktz[jj] = *reinterpret_cast<const float4*>(a.k_tz[sub] + to);
+          bf.kts[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_kts, voff_t, to, 0);
+          bf.ktz[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_ktz, voff_t, to, 0);
         }
         if constexpr (VTOK) {
-          bf.vts[jj] = *reinterpret_cast<const float4*>(a.v_ts[sub] + to);
-          bf.vtz[jj] = *reinterpret_cast<const float4*>(a.v_tz[sub] + to);
+          bf.vts[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_vts, voff_t, to, 0);
+          bf.vtz[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_vtz, voff_t, to, 0);
         }
       }
-      const uint32_t* vbase = a.vc[sub] + ((bh * nblk + slot0 / TB) * 4 + grp) * D;
+      const int vo = (int)((uint32_t)(begin / TB + hb / NH) * (uint32_t)(4 * D * 4));
 #pragma unroll
-      for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const uint4*>(vbase + 4 * (n + 16 * r));
+      for (int r = 0; r < NR; ++r) bf.vw[r] = __builtin_amdgcn_raw_buffer_load_b128(rs_v, voff_v + 256 * r, vo, 0);
     };
 
-    Buf cur;
-    if (hlo < hhi) load_half(hlo, cur);       // in flight while the operand is built
-    // channel parameters of the values, needed when the segment is folded
-    float4 vcs4[NR], vcz4[NR];
-#pragma unroll
-    for (int r = 0; r < NR; ++r) {
-      vcs4[r] = *reinterpret_cast<const float4*>(a.v_cs + chan_off + 4 * (n + 16 * r));
-      vcz4[r] = *reinterpret_cast<const float4*>(a.v_cz + chan_off + 4 * (n + 16 * r));
-    }
-
+    Buf b0, b1;
+    if (hlo < hhi) load_half(hlo, b0);       // in flight while the operand is built
     u4 qB[KS];
-    float sumqq, sumqqcz;
-    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, qB, sumqq, sumqqcz);
+    float Aq, sumqcz;
+    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz);
     if (hlo >= hhi) return;
-    const float Aq = sumqq / SC;
-    const float kconst = -(sumqq + sumqqcz / SC);     // removes the "1" terms and sum q' cz
+    const float kconst = SUBN ? -sumqcz : -(SC * Aq + sumqcz);   // normalized codes: the "1" terms add SC sum(q')
+    const float c_own_s = c_own * UNSCALE, c_oth_s = c_oth * UNSCALE;
+    // factor of operand register v of the weights; the residual rows are unused
+    // (zero) when the weights are not split
+    float wcomp[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) wcomp[v] = (!WSPLIT && part) ? 0.f : code_comp<BITS, SUBN>(v);
+    // B operand that sums the weights: 1 / factor of each operand register
+    // (normalized codes: plain ones, the sum then carries SC and is also the "1" term of the output product)
+    u4 ones;
+    if constexpr (!SUBN) ones = u4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
+    else if constexpr (BITS == 4) ones = u4{0x2C002C00u, 0x3C003C00u, 0x2C002C00u, 0x3C003C00u};   // 1/16, 1, 1/16, 1
+    else ones = u4{0x24002400u, 0x2C002C00u, 0x34003400u, 0x3C003C00u};                            // 1/64, 1/16, 1/4, 1
 
     f4 acc[NR][4];
-    f4 acc1 = f4{0.f, 0.f, 0.f, 0.f};     // sum of the weights operand (product with ones)
+    f4 acc1 = f4{0.f, 0.f, 0.f, 0.f};     // sum of the weights
 #pragma unroll
     for (int r = 0; r < NR; ++r)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[r][j] = f4{0.f, 0.f, 0.f, 0.f};
-    float a1 = 0.f;
+    float a1 = 0.f;                       // sum of w tz
 
-    // one half-block; MASKED only when it reaches past the end of the segment
-    auto half_block = [&](auto masked_c, const Buf& bf, int h, int ntok) {
-      constexpr bool MASKED = decltype(masked_c)::value;
-      float lg[2][4];
-      float lmax = -INFINITY;
+    auto half_block = [&](const Buf& bf, int hb) {
+      const int h = hb % NH;
+      const int ntok = len - 32 * hb;                  // slots of this half-block inside the segment, >= 1
+      const bool masked = ntok < 32;                   // only the last half-block of a segment
+      float lg[2][4], vts[2][4], vtz[2][4];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         f4 sacc = f4{0.f, 0.f, 0.f, 0.f};
         if constexpr (BITS == 4) {
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack4(bf.kw[jj][ks]), qB[ks], sacc);
+          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack4<SUBN>(bf.kw[jj][ks]), qB[ks], sacc);
         } else {
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack2(bf.kw[jj][ks >> 1], ks & 1), qB[ks], sacc);
+          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack2<SUBN>(bf.kw[jj][ks >> 1], ks & 1), qB[ks], sacc);
         }
         const float own[4] = {sacc.x, sacc.y, sacc.z, sacc.w};
-        const float kts[4] = {bf.kts[jj].x, bf.kts[jj].y, bf.kts[jj].z, bf.kts[jj].w};
-        const float ktz[4] = {bf.ktz[jj].x, bf.ktz[jj].y, bf.ktz[jj].z, bf.ktz[jj].w};
+        const float kts[4] = {__uint_as_float(bf.kts[jj].x), __uint_as_float(bf.kts[jj].y), __uint_as_float(bf.kts[jj].z), __uint_as_float(bf.kts[jj].w)};
+        const float ktz[4] = {__uint_as_float(bf.ktz[jj].x), __uint_as_float(bf.ktz[jj].y), __uint_as_float(bf.ktz[jj].z), __uint_as_float(bf.ktz[jj].w)};
+        vts[jj][0] = __uint_as_float(bf.vts[jj].x); vts[jj][1] = __uint_as_float(bf.vts[jj].y);
+        vts[jj][2] = __uint_as_float(bf.vts[jj].z); vts[jj][3] = __uint_as_float(bf.vts[jj].w);
+        vtz[jj][0] = __uint_as_float(bf.vtz[jj].x); vtz[jj][1] = __uint_as_float(bf.vtz[jj].y);
+        vtz[jj][2] = __uint_as_float(bf.vtz[jj].z); vtz[jj][3] = __uint_as_float(bf.vtz[jj].w);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          float x = fmaf(xor1(own[v]), c_oth, own[v] * c_own) + kconst;
+          float x = fmaf(xor1(own[v]), c_oth_s, fmaf(own[v], c_own_s, kconst));
           if constexpr (KTOK) x = kts[v] * fmaf(-ktz[v], Aq, x);
-          if constexpr (MASKED) x = (16 * jj + 4 * grp + v < ntok) ? x : -INFINITY;
           lg[jj][v] = x;
-          lmax = fmaxf(lmax, x);
         }
       }
-      rescale_to(fmaxf(m_run, grp_max(lmax)), a1, acc, &acc1);
-      // weights w = p ts and the A operand of the output product
-      _Float16 wh[2][4];
+      if (masked) {
+        // slots past the end of the segment: no weight, and their per-token
+        // parameters were never written
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const float vts[4] = {bf.vts[jj].x, bf.vts[jj].y, bf.vts[jj].z, bf.vts[jj].w};
-        const float vtz[4] = {bf.vtz[jj].x, bf.vtz[jj].y, bf.vtz[jj].z, bf.vtz[jj].w};
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const bool live = 16 * jj + 4 * grp + v < ntok;
+            lg[jj][v] = live ? lg[jj][v] : -INFINITY;
+            vts[jj][v] = live ? vts[jj][v] : 0.f;
+            vtz[jj][v] = live ? vtz[jj][v] : 0.f;
+          }
+      }
+      const float lmax = fmaxf(fmaxf(fmaxf(lg[0][0], lg[0][1]), fmaxf(lg[0][2], lg[0][3])),
+                               fmaxf(fmaxf(lg[1][0], lg[1][1]), fmaxf(lg[1][2], lg[1][3])));
+      update_max(lmax, a1, acc, acc1);
+      // weights w = p ts and the A operand of the output product
+      float w2[2][4];
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const float p = fast_exp2(lg[jj][v] - m_run);      // 0 for masked slots
+          const float p = fast_exp2(lg[jj][v] - m_run);      // 0 for masked slots and unused columns
           float w = p;
           if constexpr (VTOK) {
-            const bool live = !MASKED || (16 * jj + 4 * grp + v < ntok);   // parameters past the end are not written
-            w = live ? p * vts[v] : 0.f;
-            a1 = fmaf(w, live ? vtz[v] : 0.f, a1);
+            w = p * vts[jj][v];
+            a1 = fmaf(w, vtz[jj][v], a1);
           }
           z_part += p;
-          wh[jj][v] = split_part(w * SC, part);
+          w2[jj][v] = w * wcomp[v];
         }
-      }
       u4 pA;
-      pA.x = pack_h2(wh[0][0], wh[1][0]); pA.y = pack_h2(wh[0][1], wh[1][1]);
-      pA.z = pack_h2(wh[0][2], wh[1][2]); pA.w = pack_h2(wh[0][3], wh[1][3]);
+      if constexpr (WSPLIT) {
+        pA.x = pack_h2(split_part(w2[0][0], part), split_part(w2[1][0], part));
+        pA.y = pack_h2(split_part(w2[0][1], part), split_part(w2[1][1], part));
+        pA.z = pack_h2(split_part(w2[0][2], part), split_part(w2[1][2], part));
+        pA.w = pack_h2(split_part(w2[0][3], part), split_part(w2[1][3], part));
+      } else {
+        pA.x = pack_f2(w2[0][0], w2[1][0]); pA.y = pack_f2(w2[0][1], w2[1][1]);
+        pA.z = pack_f2(w2[0][2], w2[1][2]); pA.w = pack_f2(w2[0][3], w2[1][3]);
+      }
       acc1 = mfma16(pA, ones, acc1);
 #pragma unroll
       for (int r = 0; r < NR; ++r) {
         const uint32_t ww[4] = {bf.vw[r].x, bf.vw[r].y, bf.vw[r].z, bf.vw[r].w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          if constexpr (BITS == 4) acc[r][j] = mfma16(pA, unpack4(ww[j]), acc[r][j]);
-          else acc[r][j] = mfma16(pA, unpack2(ww[j], h), acc[r][j]);
+          if constexpr (BITS == 4) acc[r][j] = mfma16(pA, unpack4<SUBN>(ww[j]), acc[r][j]);
+          else acc[r][j] = mfma16(pA, unpack2<SUBN>(ww[j], h), acc[r][j]);
         }
       }
     };
 
-    for (int hb = hlo; hb < hhi; ++hb) {
-      Buf nxt;
-      if (hb + 1 < hhi) load_half(hb + 1, nxt);
-      const int h = hb % NH;
-      const int ntok = len - (hb / NH) * TB - 32 * h;      // slots of this half-block inside the segment
-      if (ntok >= 32) half_block(std::false_type{}, cur, h, 32);
-      else half_block(std::true_type{}, cur, h, ntok);
-      if (hb + 1 < hhi) cur = nxt;
+    // two buffers in turn: half-block i + 1 is requested before half-block i is computed
+    for (int hb = hlo; hb < hhi; hb += 2) {
+      const bool second = hb + 1 < hhi;
+      if (second) load_half(hb + 1, b1);
+      half_block(b0, hb);
+      if (second) {
+        if (hb + 2 < hhi) load_half(hb + 2, b0);
+        half_block(b1, hb + 1);
+      }
     }
     // ---- fold the segment into O ----
-    // sum_t w code = acc_value + acc_residual / 2^11 - sum_t w'';  sum_t w = sum_t w'' / SC
-    const float sw0 = acc1.x + acc1.y * kLoInv, sw1 = acc1.z + acc1.w * kLoInv;
+    //   subnormal codes:   sum_t w code = acc 2^(24 - P),  sum_t w = acc1
+    //   normalized codes:  sum_t w code = acc - acc1,         sum_t w = acc1 / SC
+    //   (value + residual / 2^11 when the weights are split)
+    const float r0 = WSPLIT ? acc1.x + acc1.y * kLoInv : acc1.x;
+    const float r1 = WSPLIT ? acc1.z + acc1.w * kLoInv : acc1.z;
+    const float sw0 = SUBN ? r0 : r0 * (1.f / SC), sw1 = SUBN ? r1 : r1 * (1.f / SC);
+    const float bias0 = SUBN ? 0.f : r0, bias1 = SUBN ? 0.f : r1;
     float a10 = 0.f, a11 = 0.f;
     if constexpr (VTOK) {
       a1 = grp_sum(a1);
@@ -607,13 +714,15 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-      const float cs[4] = {vcs4[r].x, vcs4[r].y, vcs4[r].z, vcs4[r].w}, cz[4] = {vcz4[r].x, vcz4[r].y, vcz4[r].z, vcz4[r].w};
+      const float4 vcs4 = *reinterpret_cast<const float4*>(&svc[0][4 * (n + 16 * r)]);
+      const float4 vcz4 = *reinterpret_cast<const float4*>(&svc[1][4 * (n + 16 * r)]);
+      const float cs[4] = {vcs4.x, vcs4.y, vcs4.z, vcs4.w}, cz[4] = {vcz4.x, vcz4.y, vcz4.z, vcz4.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float t0 = acc[r][j].x + acc[r][j].y * kLoInv - sw0;
-        const float t1 = acc[r][j].z + acc[r][j].w * kLoInv - sw1;
-        O[r][j][0] = fmaf(cs[j], t0 - a10 - cz[j] * (sw0 / SC), O[r][j][0]);
-        O[r][j][1] = fmaf(cs[j], t1 - a11 - cz[j] * (sw1 / SC), O[r][j][1]);
+        const float t0 = ((WSPLIT ? acc[r][j].x + acc[r][j].y * kLoInv : acc[r][j].x) - bias0) * UNSCALE;
+        const float t1 = ((WSPLIT ? acc[r][j].z + acc[r][j].w * kLoInv : acc[r][j].z) - bias1) * UNSCALE;
+        O[r][j][0] = fmaf(cs[j], t0 - a10 - cz[j] * sw0, O[r][j][0]);
+        O[r][j][1] = fmaf(cs[j], t1 - a11 - cz[j] * sw1, O[r][j][1]);
       }
     }
   };
@@ -623,6 +732,9 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
       int begin, len;
       if (a.chunks_inline) { begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1]; }
       else { begin = a.chunk_table[4 * ci + 2 * sub]; len = a.chunk_table[4 * ci + 2 * sub + 1]; }
+      // wave-uniform by construction; say so, so that offsets derived from them stay in scalar registers
+      begin = __builtin_amdgcn_readfirstlane(begin);
+      len = __builtin_amdgcn_readfirstlane(len);
       const int bits = a.bits[sub];
       const int TB = 4 * (32 / bits);
       const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
