@@ -9,13 +9,15 @@
 //   2. k_chan_finalize  reduces the partials and turns them once into the
 //                       parameters the quantizer needs (Eq. 5's R = max - min,
 //                       1/R and z per channel, or Eq. 6's c and 1/c).
-//   3. k_quant_pack     a team of waves owns one "unit" of up to 8 tokens that
-//                       share 32-bit words (or their 16-bit halves) in the TGROUP
-//                       layout: all rows of the unit's tokens are requested at
-//                       once, per-token min / max by DPP wave reduction for the
-//                       tokenwise schemes, tie-exact x (2^k-1) / R, round half to
-//                       even, + z, clamp, pack along channels (ROW layout) or along
-//                       tokens (TGROUP layout).
+//   3. k_quant_pack     a team of waves (one thread per 8 channels) owns one to
+//                       four word groups of a TGROUP block - the 32 / bits tokens
+//                       whose codes share 32-bit words - and walks them in
+//                       batches of 8 tokens, requesting batch i + 1 before it
+//                       reduces and quantizes batch i: per-token range by DPP wave
+//                       reduction (+ LDS across the team's waves) for the tokenwise
+//                       schemes, tie-exact x (2^k-1) / R for the zero points and the
+//                       channelwise codes, round half to even, + z, clamp, pack along
+//                       channels (ROW layout) or along tokens (TGROUP layout).
 // Every sweep reads 16 bytes per lane with consecutive lanes on consecutive
 // addresses of a (token, head) row; the second sweep of a tensor that fits the
 // 256 MB Infinity Cache does not reach HBM.
@@ -43,19 +45,24 @@ struct QPArgs {
   int32_t* chunk_row;          // device chunk_table row to fill
   int64_t pos_offset;
   int tiles[2], TT;            // stats sweep tiling
-  int units[2];                // quantize sweep: units per subset
+  int units[2];                // quantize sweep: word groups per subset (4 per TGROUP block)
+  int upw, wgs[2];             // word groups per workgroup (1, 2 or 4: divides a block), workgroups per subset
   int scheme;
 };
 
-constexpr int kStatMaxV = 4;   // channel vectors per thread in the statistics sweep (W <= 8192)
+constexpr int kStatThreads = 256;   // channel vectors (8 channels) per workgroup of the statistics sweep
+constexpr int kStatBatch = 8;       // token rows requested at once
 
 __host__ __device__ inline int stats_tile_tokens(int64_t total_tokens) {
   int64_t tt = ceil_div64(total_tokens, 1024);
   return tt < 16 ? 16 : (tt > 64 ? 64 : (int)tt);
 }
 
+// grid (tiles, B, ceil(NV / 256)): a workgroup reduces 256 channel vectors over a
+// tile of tokens of one subset; a thread owns one vector (8 channels).
 template <int DT>
-__global__ __launch_bounds__(256) void k_chan_stats(QPArgs a) {
+__global__ __launch_bounds__(kStatThreads) void k_chan_stats(QPArgs a) {
+  constexpr int RAW = (DT == ZC_F32) ? 2 : 1;        // 16-byte loads per channel vector
   const int b = blockIdx.y;
   int tile = blockIdx.x;
   const int sub = tile >= a.tiles[0] ? 1 : 0;
@@ -63,55 +70,54 @@ __global__ __launch_bounds__(256) void k_chan_stats(QPArgs a) {
   if (sub) tile -= a.tiles[0];
   const int t0 = tile * a.TT;
   const int t1 = min(t0 + a.TT, a.n[sub]);
-  const int TX = blockDim.x, x = threadIdx.x;
+  const int v = blockIdx.z * kStatThreads + threadIdx.x;
+  if (v >= a.NV) return;
   const int32_t* idx = a.idx[sub] + (int64_t)b * a.n[sub];
+  const int w = v * 8, h = w / a.D, c = w % a.D;
+  const char* base = reinterpret_cast<const char*>(a.x) + ((int64_t)b * a.sB + (int64_t)h * a.sH + c) * (DT == ZC_F32 ? 4 : 2);
+  const int64_t row_bytes = a.sL * (DT == ZC_F32 ? 4 : 2);
 
-  float mn[kStatMaxV][8], mx[kStatMaxV][8];
+  float mn[8], mx[8];
 #pragma unroll
-  for (int j = 0; j < kStatMaxV; ++j)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { mn[j][i] = INFINITY; mx[j][i] = -INFINITY; }
+  for (int i = 0; i < 8; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; }
 
-  for (int tb = t0; tb < t1; tb += 8) {
-    // all rows of the batch are requested before any is reduced
-    float vals[8][kStatMaxV][8];
-    bool live[8];
+  for (int tb = t0; tb < t1; tb += kStatBatch) {
+    // all rows of the batch are requested before any is reduced; rows past the
+    // end repeat the last one (min / max do not care)
+    uint4 raw[kStatBatch][RAW];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      live[t] = tb + t < t1;
-      const int64_t pos = live[t] ? idx[tb + t] : 0;
+    for (int t = 0; t < kStatBatch; ++t) {
+      const int64_t pos = idx[min(tb + t, t1 - 1)];
+      const uint4* src = reinterpret_cast<const uint4*>(base + pos * row_bytes);
 #pragma unroll
-      for (int j = 0; j < kStatMaxV; ++j) {
-        const int v = x + j * TX;
-        if (live[t] && v < a.NV) {
-          const int w = v * 8, h = w / a.D, c = w % a.D;
-          load8<DT>(a.x, (int64_t)b * a.sB + (int64_t)h * a.sH + pos * a.sL + c, vals[t][j]);
-        }
-      }
+      for (int r = 0; r < RAW; ++r) raw[t][r] = src[r];
     }
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int t = 0; t < kStatBatch; ++t) {
+      float x8[8];
+      if constexpr (DT == ZC_F32) {
+        x8[0] = __uint_as_float(raw[t][0].x); x8[1] = __uint_as_float(raw[t][0].y);
+        x8[2] = __uint_as_float(raw[t][0].z); x8[3] = __uint_as_float(raw[t][0].w);
+        x8[4] = __uint_as_float(raw[t][RAW - 1].x); x8[5] = __uint_as_float(raw[t][RAW - 1].y);
+        x8[6] = __uint_as_float(raw[t][RAW - 1].z); x8[7] = __uint_as_float(raw[t][RAW - 1].w);
+      } else {
+        const uint32_t w4[4] = {raw[t][0].x, raw[t][0].y, raw[t][0].z, raw[t][0].w};
 #pragma unroll
-      for (int j = 0; j < kStatMaxV; ++j) {
-        const int v = x + j * TX;
-        if (live[t] && v < a.NV) {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) { mn[j][i] = fminf(mn[j][i], vals[t][j][i]); mx[j][i] = fmaxf(mx[j][i], vals[t][j][i]); }
+        for (int i = 0; i < 4; ++i) {
+          x8[2 * i] = half_bits_to_float<DT>(w4[i] & 0xffffu);
+          x8[2 * i + 1] = half_bits_to_float<DT>(w4[i] >> 16);
         }
       }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { mn[i] = fminf(mn[i], x8[i]); mx[i] = fmaxf(mx[i], x8[i]); }
+    }
   }
   float* out = a.partial + ((int64_t)b * (a.tiles[0] + a.tiles[1]) + gtile) * a.W * 2;
-#pragma unroll
-  for (int j = 0; j < kStatMaxV; ++j) {
-    const int v = x + j * TX;
-    if (v < a.NV) {
-      float4* o4 = reinterpret_cast<float4*>(out + (int64_t)v * 16);
-      o4[0] = make_float4(mn[j][0], mx[j][0], mn[j][1], mx[j][1]);
-      o4[1] = make_float4(mn[j][2], mx[j][2], mn[j][3], mx[j][3]);
-      o4[2] = make_float4(mn[j][4], mx[j][4], mn[j][5], mx[j][5]);
-      o4[3] = make_float4(mn[j][6], mx[j][6], mn[j][7], mx[j][7]);
-    }
-  }
+  float4* o4 = reinterpret_cast<float4*>(out + (int64_t)v * 16);
+  o4[0] = make_float4(mn[0], mx[0], mn[1], mx[1]);
+  o4[1] = make_float4(mn[2], mx[2], mn[3], mx[3]);
+  o4[2] = make_float4(mn[4], mx[4], mn[5], mx[5]);
+  o4[3] = make_float4(mn[6], mx[6], mn[7], mx[7]);
 }
 
 // N / R from the correctly rounded reciprocal y = 1/R with one residual
@@ -205,224 +211,283 @@ __device__ inline int tile_of_field_group(int bits, int jf) {
 
 constexpr int kVPT = 1;  // channel vectors (8 channels each) per thread in the quantize sweep
 
-template <int DT, int BITS, int LAYOUT, bool TOKWISE>
-__device__ inline void quant_unit(const QPArgs& a, int sub, int u, int b, float (*red)[8][16]) {
-  constexpr int E = 32 / BITS;                       // code fields per 32-bit TGROUP word
-  constexpr int TU = E < 8 ? E : 8;                  // tokens per unit: a word, or half of a 2-bit word
-  constexpr int UW = E / TU;                         // units that share a word
-  constexpr int TBAT = (DT == ZC_F32) ? 4 : TU;      // tokens requested at once
-  constexpr int NBAT = TU / TBAT;
+// The quantize sweep of one workgroup: `ng` consecutive word groups of one TGROUP
+// block.  A word group is the 32 / bits tokens whose codes share 32-bit words in
+// the TGROUP layout (block blk, k-group kg); it is processed in batches of up to
+// 8 tokens, a thread owning 8 channels of every token.  The rows of batch i + 1
+// are requested before batch i is reduced and quantized.
+//   tokenwise schemes: x' = x / c is kept in registers between the range pass and
+//   the quantize pass; the per-token range goes through a DPP wave reduction,
+//   then (teams of several waves) through LDS; lanes 0..7 then compute the
+//   parameters of tokens 0..7 of the batch, once, and broadcast them.
+//   codes are assembled in float: sum of code * 2^(bits * position) over a 16-bit
+//   group is exact in fp32, so packing costs one FMA per code.
+template <int DT, int BITS, int LAYOUT, bool TOKWISE, bool PIPE>
+__device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int b, float (*red)[16][16], int32_t* sidx) {
+  constexpr int E = 32 / BITS;                       // tokens of a word group
+  constexpr int TBAT = E < 8 ? E : 8;                // tokens per batch
+  constexpr int NBAT = E / TBAT;                     // batches per word group
   constexpr int TB = 4 * E;                          // slots per TGROUP block
+  constexpr int FPG = 16 / BITS;                     // code fields per 16-bit group
   constexpr float QMAX = (float)((1 << BITS) - 1);
   constexpr int RAW = (DT == ZC_F32) ? 2 : 1;        // 16-byte loads per channel vector
+  constexpr int ESZ = (DT == ZC_F32) ? 4 : 2;
 
-  const int blk = u / (4 * UW), kg = (u / UW) & 3, hf = u % UW;     // unit = (block, k-group, part of the word)
   const int n = a.n[sub];
   const int TX = blockDim.x, x = threadIdx.x;
   const int lane = x & 63, wave = x >> 6, nwaves = TX >> 6;
   const int32_t* idx = a.idx[sub] + (int64_t)b * n;
+  const int blk = g0 >> 2;                           // every word group of this workgroup lies in this block
+
+  // source positions of the block's slots (-1 past the end of the subset)
+  if (x < TB) { const int rel = blk * TB + x; sidx[x] = rel < n ? idx[rel] : -1; }
 
   // parameters of the channels this thread owns
-  float p0[kVPT][8], p1[kVPT][8], p2[kVPT][8];
-  bool vvalid[kVPT];
-  int64_t xoff[kVPT];
-#pragma unroll
-  for (int j = 0; j < kVPT; ++j) {
-    const int v = x + j * TX;
-    vvalid[j] = v < a.NV;
-    const int w = (vvalid[j] ? v : 0) * 8, h = w / a.D, c = w % a.D;
-    xoff[j] = (int64_t)b * a.sB + (int64_t)h * a.sH + c;
+  const bool vvalid = x < a.NV;
+  const int w = (vvalid ? x : 0) * 8, h = w / a.D, c = w % a.D;
+  const char* xbase = reinterpret_cast<const char*>(a.x) + ((int64_t)b * a.sB + (int64_t)h * a.sH + c) * ESZ;
+  const int64_t row_bytes = a.sL * ESZ;
+  float p0[8], p1[8], p2[8];
+  {
     const float4* pp = a.params + (int64_t)(b * 2 + sub) * a.W + w;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float4 t = pp[i];
-      p0[j][i] = t.x; p1[j][i] = t.y; p2[j][i] = t.z;
+      p0[i] = t.x; p1[i] = t.y; p2[i] = t.z;
     }
   }
+  __syncthreads();
 
-  uint32_t words[kVPT][8];
-#pragma unroll
-  for (int j = 0; j < kVPT; ++j)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) words[j][i] = 0u;
-
-#pragma unroll
-  for (int bt = 0; bt < NBAT; ++bt) {
-    // slot (relative to the chunk) and source position of the batch's tokens
-    int rel[TBAT];
-    uint4 raw[TBAT][kVPT][RAW];
+  struct Batch { uint4 raw[TBAT][RAW]; };
+  // batch q of the workgroup: word group g0 + q / NBAT, tokens (q % NBAT) * TBAT + t of it
+  auto slot_of = [&](int q, int t) {                 // slot inside the block
+    const int kg = (g0 + q / NBAT) & 3;
+    const int e = (q % NBAT) * TBAT + t;
+    return 16 * tile_of_field_group(BITS, e >> 2) + 4 * kg + (e & 3);
+  };
+  auto issue = [&](int q, Batch& bt) {
 #pragma unroll
     for (int t = 0; t < TBAT; ++t) {
-      const int e = hf * TU + bt * TBAT + t;
-      rel[t] = blk * TB + 16 * tile_of_field_group(BITS, e >> 2) + 4 * kg + (e & 3);
-      const bool tv = rel[t] < n;
-      const int64_t pos = tv ? idx[rel[t]] : 0;
+      const int pos = sidx[slot_of(q, t)];
 #pragma unroll
-      for (int j = 0; j < kVPT; ++j)
-#pragma unroll
-        for (int r = 0; r < RAW; ++r) {
-          raw[t][j][r] = make_uint4(0u, 0u, 0u, 0u);
-          if (tv && vvalid[j]) {
-            const char* src = reinterpret_cast<const char*>(a.x) + (xoff[j] + pos * a.sL) * (DT == ZC_F32 ? 4 : 2) + 16 * r;
-            raw[t][j][r] = *reinterpret_cast<const uint4*>(src);
-          }
-        }
-    }
-    auto widen = [&](int t, int j, float (&v)[8]) {
-      if constexpr (DT == ZC_F32) {
-        v[0] = __uint_as_float(raw[t][j][0].x); v[1] = __uint_as_float(raw[t][j][0].y);
-        v[2] = __uint_as_float(raw[t][j][0].z); v[3] = __uint_as_float(raw[t][j][0].w);
-        v[4] = __uint_as_float(raw[t][j][RAW - 1].x); v[5] = __uint_as_float(raw[t][j][RAW - 1].y);
-        v[6] = __uint_as_float(raw[t][j][RAW - 1].z); v[7] = __uint_as_float(raw[t][j][RAW - 1].w);
-      } else {
-        const uint32_t w4[4] = {raw[t][j][0].x, raw[t][j][0].y, raw[t][j][0].z, raw[t][j][0].w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          v[2 * i] = half_bits_to_float<DT>(w4[i] & 0xffffu);
-          v[2 * i + 1] = half_bits_to_float<DT>(w4[i] >> 16);
-        }
+      for (int r = 0; r < RAW; ++r) {
+        bt.raw[t][r] = make_uint4(0u, 0u, 0u, 0u);
+        if (pos >= 0 && vvalid) bt.raw[t][r] = *reinterpret_cast<const uint4*>(xbase + (int64_t)pos * row_bytes + 16 * r);
       }
-    };
+    }
+  };
+  auto widen = [&](const Batch& bt, int t, float (&v)[8]) {
+    if constexpr (DT == ZC_F32) {
+      v[0] = __uint_as_float(bt.raw[t][0].x); v[1] = __uint_as_float(bt.raw[t][0].y);
+      v[2] = __uint_as_float(bt.raw[t][0].z); v[3] = __uint_as_float(bt.raw[t][0].w);
+      v[4] = __uint_as_float(bt.raw[t][RAW - 1].x); v[5] = __uint_as_float(bt.raw[t][RAW - 1].y);
+      v[6] = __uint_as_float(bt.raw[t][RAW - 1].z); v[7] = __uint_as_float(bt.raw[t][RAW - 1].w);
+    } else {
+      const uint32_t w4[4] = {bt.raw[t][0].x, bt.raw[t][0].y, bt.raw[t][0].z, bt.raw[t][0].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[2 * i] = half_bits_to_float<DT>(w4[i] & 0xffffu);
+        v[2 * i + 1] = half_bits_to_float<DT>(w4[i] >> 16);
+      }
+    }
+  };
 
-    float rng[TBAT], inv_r[TBAT], zt[TBAT];
+  uint32_t words[8];                                 // TGROUP: the word group's words of this thread's channels
+
+  auto process = [&](int q, const Batch& bt, int parity) {
+    const int kg = (g0 + q / NBAT) & 3, bi = q % NBAT;
+    bool tv[TBAT];
+#pragma unroll
+    for (int t = 0; t < TBAT; ++t) tv[t] = blk * TB + slot_of(q, t) < n;
+    if (LAYOUT == ZC_LAYOUT_TGROUP && bi == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) words[i] = 0u;
+    }
+    // bookkeeping of the batch's tokens by lanes 0 .. TBAT-1 of the first wave
+    const int my_t = lane < TBAT ? lane : 0;
+    const int my_rel = blk * TB + slot_of(q, my_t);
+    const bool my_live = x < TBAT && my_rel < n;
+    const int64_t my_o = (int64_t)b * a.cap[sub] + a.begin[sub] + my_rel;
+    if (my_live && a.pos[sub]) a.pos[sub][my_o] = (int32_t)(sidx[my_rel - blk * TB] + a.pos_offset);
+
+    float xs[TBAT][8];                               // tokenwise: x' = x / c; channelwise: x
+    float sinv[TBAT], zt[TBAT];
+#pragma unroll
+    for (int t = 0; t < TBAT; ++t) {
+      widen(bt, t, xs[t]);
+      if constexpr (TOKWISE) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xs[t][i] *= p0[i];
+      }
+    }
     if constexpr (TOKWISE) {
-      float tmin[TBAT], tmax[TBAT];
+      // (min, -max) of every token over the wave
+      float lo[TBAT], nhi[TBAT];
 #pragma unroll
       for (int t = 0; t < TBAT; ++t) {
-        float lo = INFINITY, hi = -INFINITY;
+        float l = xs[t][0], hneg = -xs[t][0];
 #pragma unroll
-        for (int j = 0; j < kVPT; ++j) {
-          if (vvalid[j]) {
-            float v[8];
-            widen(t, j, v);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) { const float y = v[i] * p0[j][i]; lo = fminf(lo, y); hi = fmaxf(hi, y); }
-          }
-        }
-        tmin[t] = wave_allreduce<false>(lo);
-        tmax[t] = wave_allreduce<true>(hi);
+        for (int i = 1; i < 8; ++i) { l = fminf(l, xs[t][i]); hneg = fminf(hneg, -xs[t][i]); }
+        if (!vvalid) { l = INFINITY; hneg = INFINITY; }
+        lo[t] = wave_allreduce<false>(l);
+        nhi[t] = wave_allreduce<false>(hneg);
       }
-      if (nwaves > 1) {
-        __syncthreads();
-        if (lane == 0) {
+      // through LDS: lane j < 16 ends up with value j (min of token j, or -max of token j - 8)
+      // over all waves.  One barrier per batch: the scratch alternates, and the barrier
+      // of the next batch separates these reads from the writes of the batch after it.
+      float* mine = &red[parity][wave][0];
+      if (lane == 0) {
 #pragma unroll
-          for (int t = 0; t < TBAT; ++t) { red[0][t][wave] = tmin[t]; red[1][t][wave] = tmax[t]; }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int t = 0; t < TBAT; ++t) {
-          float lo = red[0][t][0], hi = red[1][t][0];
-          for (int w = 1; w < nwaves; ++w) { lo = fminf(lo, red[0][t][w]); hi = fmaxf(hi, red[1][t][w]); }
-          tmin[t] = lo; tmax[t] = hi;
-        }
+        for (int t = 0; t < TBAT; ++t) { mine[t] = lo[t]; mine[8 + t] = nhi[t]; }
+      }
+      if (nwaves > 1) __syncthreads();
+      float r = red[parity][0][lane & 15];
+      for (int w2 = 1; w2 < nwaves; ++w2) r = fminf(r, red[parity][w2][lane & 15]);
+      const float tmin = r;
+      const float tmax = -__shfl(r, (lane & 7) + 8);
+      // parameters of token (lane & 7), computed once per lane group
+      float R = tmax - tmin;
+      if (R == 0.f) R = QMAX;                        // max == min: s := 1
+      const float y = __builtin_amdgcn_rcpf(R);
+      const float z = -rintf(refined_ratio(tmin, QMAX, R, y));   // tie-exact: a whole row depends on it
+      const float si = QMAX * y;
+      if (my_live) {
+        a.tok_scale[sub][my_o] = R * (1.f / QMAX);
+        a.tok_zero[sub][my_o] = z;
       }
 #pragma unroll
       for (int t = 0; t < TBAT; ++t) {
-        float R = tmax[t] - tmin[t];
-        if (R == 0.f) R = QMAX;                 // max == min: s := 1
-        const float y = 1.f / R;
-        const float z = -rintf(refined_ratio(tmin[t], QMAX, R, y));
-        rng[t] = R; inv_r[t] = y; zt[t] = z;
-        if (x == 0 && rel[t] < n) {
-          const int64_t o = (int64_t)b * a.cap[sub] + a.begin[sub] + rel[t];
-          a.tok_scale[sub][o] = R / QMAX;
-          a.tok_zero[sub][o] = z;
-        }
+        sinv[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(si), t));
+        zt[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z), t));
       }
     }
+
+    if (!vvalid) return;
 #pragma unroll
     for (int t = 0; t < TBAT; ++t) {
-      const bool tv = rel[t] < n;
-      if (x == 0 && tv && a.pos[sub])
-        a.pos[sub][(int64_t)b * a.cap[sub] + a.begin[sub] + rel[t]] = (int32_t)(idx[rel[t]] + a.pos_offset);
+      // Eq. 5: round(x / s) first, then + z, then clip
+      float code[8];
 #pragma unroll
-      for (int j = 0; j < kVPT; ++j) {
-        if (!vvalid[j]) continue;
-        float v[8];
-        widen(t, j, v);
-        uint32_t code[8];
+      for (int i = 0; i < 8; ++i) {
+        float qv;
+        if constexpr (TOKWISE) qv = rintf(xs[t][i] * sinv[t]) + zt[t];
+        else if constexpr (DT == ZC_F32) qv = rintf(refined_ratio(xs[t][i], QMAX, p2[i], p0[i])) + p1[i];
+        else qv = rintf(refined_div(xs[t][i] * QMAX, p2[i], p0[i])) + p1[i];   // x * qmax is exact
+        code[i] = __builtin_amdgcn_fmed3f(qv, 0.f, QMAX);
+      }
+      if constexpr (LAYOUT == ZC_LAYOUT_ROW) {
+        if (tv[t]) {
+          // the 8 codes of this token, 16 bits at a time
+          constexpr int NG = 8 / FPG;                // 16-bit groups of the 8 codes (>= 1: bits >= 2)
+          uint32_t half[NG];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          // Eq. 5: round(x / s) first, then + z, then clip
-          float q;
-          if constexpr (TOKWISE) q = rintf(refined_ratio(v[i] * p0[j][i], QMAX, rng[t], inv_r[t])) + zt[t];
-          else if constexpr (DT == ZC_F32) q = rintf(refined_ratio(v[i], QMAX, p2[j][i], p0[j][i])) + p1[j][i];
-          else q = rintf(refined_div(v[i] * QMAX, p2[j][i], p0[j][i])) + p1[j][i];   // x * qmax is exact
-          q = __builtin_amdgcn_fmed3f(q, 0.f, QMAX);
-          code[i] = tv ? (uint32_t)q : 0u;
-        }
-        if constexpr (LAYOUT == ZC_LAYOUT_TGROUP) {
-          const int e = bt * TBAT + t;             // field inside this unit's part of the word
+          for (int g = 0; g < NG; ++g) {
+            float acc = 0.f;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) words[j][i] |= code[i] << (BITS * e);
-        } else if (tv) {
-          const int w = (x + j * TX) * 8, h = w / a.D, c = w % a.D;
-          const int64_t slot = a.begin[sub] + rel[t];
+            for (int f = 0; f < FPG; ++f) acc = fmaf(code[g * FPG + f], (float)(1 << (BITS * f)), acc);
+            half[g] = (uint32_t)acc;
+          }
+          const int64_t slot = a.begin[sub] + blk * TB + slot_of(q, t);
           uint8_t* row = a.codes[sub] + (((int64_t)b * a.H + h) * a.cap[sub] + slot) * (a.D * BITS / 8) + c * BITS / 8;
           if constexpr (BITS == 8) {
-            uint2 o;
-            o.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
-            o.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
-            *reinterpret_cast<uint2*>(row) = o;
+            *reinterpret_cast<uint2*>(row) = make_uint2(half[0] | (half[1] << 16), half[2] | (half[3] << 16));
           } else if constexpr (BITS == 4) {
-            uint32_t o = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) o |= code[i] << (4 * i);
-            *reinterpret_cast<uint32_t*>(row) = o;
+            *reinterpret_cast<uint32_t*>(row) = half[0] | (half[1] << 16);
           } else {
-            uint32_t o = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) o |= code[i] << (2 * i);
-            *reinterpret_cast<uint16_t*>(row) = (uint16_t)o;
+            *reinterpret_cast<uint16_t*>(row) = (uint16_t)half[0];
           }
         }
       }
     }
-  }
-  if constexpr (LAYOUT == ZC_LAYOUT_TGROUP) {
+    if constexpr (LAYOUT == ZC_LAYOUT_TGROUP) {
+      // channel i: the batch's tokens, 16 bits (FPG tokens) at a time; dead tokens add nothing
+      constexpr int NG = TBAT / FPG > 0 ? TBAT / FPG : 1;
+      constexpr int TPG = TBAT < FPG ? TBAT : FPG;   // tokens per 16-bit group
+      float mult[TBAT];
 #pragma unroll
-    for (int j = 0; j < kVPT; ++j) {
-      if (!vvalid[j]) continue;
-      const int w = (x + j * TX) * 8, h = w / a.D, c = w % a.D;
-      const int64_t nblk = a.cap[sub] / TB;
-      const int64_t gblk = a.begin[sub] / TB + blk;
-      uint32_t* dst = reinterpret_cast<uint32_t*>(a.codes[sub]) +
-                      ((((int64_t)b * a.H + h) * nblk + gblk) * 4 + kg) * a.D + c;
-      if constexpr (UW == 1) {
-        reinterpret_cast<uint4*>(dst)[0] = make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]);
-        reinterpret_cast<uint4*>(dst)[1] = make_uint4(words[j][4], words[j][5], words[j][6], words[j][7]);
-      } else {
-        // this unit fills 16 bits of each word; the other half belongs to a neighbouring workgroup
-        uint16_t* d16 = reinterpret_cast<uint16_t*>(dst) + hf;
+      for (int t = 0; t < TBAT; ++t) mult[t] = tv[t] ? (float)(1 << (BITS * (t % TPG))) : 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) d16[2 * i] = (uint16_t)words[j][i];
+      for (int i = 0; i < 8; ++i) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          float acc = 0.f;
+#pragma unroll
+          for (int f = 0; f < TPG; ++f) {
+            const int t = g * TPG + f;
+            float qv;
+            if constexpr (TOKWISE) qv = rintf(xs[t][i] * sinv[t]) + zt[t];
+            else if constexpr (DT == ZC_F32) qv = rintf(refined_ratio(xs[t][i], QMAX, p2[i], p0[i])) + p1[i];
+            else qv = rintf(refined_div(xs[t][i] * QMAX, p2[i], p0[i])) + p1[i];
+            acc = fmaf(__builtin_amdgcn_fmed3f(qv, 0.f, QMAX), mult[t], acc);
+          }
+          words[i] |= (uint32_t)acc << (BITS * (bi * TBAT + g * TPG));
+        }
       }
+      if (bi == NBAT - 1) {
+        const int64_t nblk = a.cap[sub] / TB;
+        const int64_t gblk = a.begin[sub] / TB + blk;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(a.codes[sub]) + ((((int64_t)b * a.H + h) * nblk + gblk) * 4 + kg) * a.D + c;
+        reinterpret_cast<uint4*>(dst)[0] = make_uint4(words[0], words[1], words[2], words[3]);
+        reinterpret_cast<uint4*>(dst)[1] = make_uint4(words[4], words[5], words[6], words[7]);
+      }
+    }
+  };
+
+  const int nq = ng * NBAT;
+  if constexpr (PIPE) {
+    Batch b0, b1;
+    issue(0, b0);
+    for (int i = 0; i < nq; i += 2) {
+      const bool second = i + 1 < nq;
+      if (second) issue(i + 1, b1);
+      process(i, b0, 0);
+      if (second) {
+        if (i + 2 < nq) issue(i + 2, b0);
+        process(i + 1, b1, 1);
+      }
+    }
+  } else {
+    Batch b0;
+    for (int i = 0; i < nq; ++i) {
+      issue(i, b0);
+      process(i, b0, i & 1);
     }
   }
 }
 
-template <int DT, int LAYOUT, bool TOKWISE>
-__global__ __launch_bounds__(1024) void k_quant_pack(QPArgs a) {
-  __shared__ float red[2][8][16];    // cross-wave min / max of a batch of tokens (<= 16 waves)
+// MAXT: most threads of a workgroup (W / 8 rounded up to a wave); it bounds the
+// registers of a thread, and with them whether two batches of rows fit.
+template <int DT, int LAYOUT, bool TOKWISE, int MAXT>
+__global__ __launch_bounds__(MAXT) void k_quant_pack(QPArgs a) {
+  constexpr bool PIPE = (DT != ZC_F32) && MAXT <= 768;
+  __shared__ float red[2][16][16];   // [turn][wave][min of token 0..7, -max of token 0..7]
+  __shared__ int32_t sidx[64];
   const int b = blockIdx.y;
-  int u = blockIdx.x;
-  const int sub = u >= a.units[0] ? 1 : 0;
-  if (sub) u -= a.units[0];
+  int wg = blockIdx.x;
+  const int sub = wg >= a.wgs[0] ? 1 : 0;
+  if (sub) wg -= a.wgs[0];
+  const int g0 = wg * a.upw, ng = a.upw;
   const int bits = a.bits[sub];
-  if (bits == 4) quant_unit<DT, 4, LAYOUT, TOKWISE>(a, sub, u, b, red);
-  else if (bits == 2) quant_unit<DT, 2, LAYOUT, TOKWISE>(a, sub, u, b, red);
-  else quant_unit<DT, 8, LAYOUT, TOKWISE>(a, sub, u, b, red);
+  if (bits == 4) quant_units<DT, 4, LAYOUT, TOKWISE, PIPE>(a, sub, g0, ng, b, red, sidx);
+  else if (bits == 2) quant_units<DT, 2, LAYOUT, TOKWISE, PIPE>(a, sub, g0, ng, b, red, sidx);
+  else quant_units<DT, 8, LAYOUT, TOKWISE, PIPE>(a, sub, g0, ng, b, red, sidx);
 }
 
+template <int DT, int MAXT>
+static void launch_qp_t(const QPArgs& a, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
+  if (layout == ZC_LAYOUT_ROW) {
+    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, true, MAXT>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, false, MAXT>), grid, block, 0, st, a);
+  } else {
+    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, true, MAXT>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, false, MAXT>), grid, block, 0, st, a);
+  }
+}
 template <int DT>
 static void launch_qp(const QPArgs& a, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
-  if (layout == ZC_LAYOUT_ROW) {
-    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, false>), grid, block, 0, st, a);
-  } else {
-    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, false>), grid, block, 0, st, a);
-  }
+  if (block.x <= 256) launch_qp_t<DT, 256>(a, layout, tokwise, grid, block, st);
+  else if (block.x <= 768) launch_qp_t<DT, 768>(a, layout, tokwise, grid, block, st);
+  else launch_qp_t<DT, 1024>(a, layout, tokwise, grid, block, st);
 }
 
 static int64_t stats_tiles(int64_t B, int64_t n_tokens, int* TT_out) {
@@ -454,7 +519,7 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   if ((k > 0 && !salient_idx) || (n_reg > 0 && !regular_idx)) return ZC_ERR_INVALID_ARG;
   if (x->B != out->B || x->H != out->H || x->D != out->D) return ZC_ERR_INVALID_ARG;
   const int64_t W = x->H * x->D;
-  if (W / 8 > kStatMaxV * 256 || W / 8 > kVPT * 1024) return ZC_ERR_UNSUPPORTED;
+  if (W / 8 > kVPT * 1024) return ZC_ERR_UNSUPPORTED;
   if (x->B > 65535) return ZC_ERR_UNSUPPORTED;
   if (out->n_chunks >= out->max_chunks) return ZC_ERR_CAPACITY;
   const int64_t end_hi = align_up64(out->n_hi + k, ZC_SLOT_ALIGN);
@@ -489,14 +554,14 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   a.TT = TT;
   a.tiles[0] = (int)ceil_div64(k, TT);
   a.tiles[1] = (int)ceil_div64(n_reg, TT);
-  // units of min(32 / bits, 8) tokens; a TGROUP block holds 4 * (32 / bits) slots
-  a.units[0] = (int)ceil_div64(k, 4 * (32 / out->bits_hi)) * (out->bits_hi == 2 ? 8 : 4);
-  a.units[1] = (int)ceil_div64(n_reg, 4 * (32 / out->bits_lo)) * (out->bits_lo == 2 ? 8 : 4);
+  // word groups of 32 / bits tokens; a TGROUP block holds 4 of them
+  a.units[0] = (int)ceil_div64(k, 4 * (32 / out->bits_hi)) * 4;
+  a.units[1] = (int)ceil_div64(n_reg, 4 * (32 / out->bits_lo)) * 4;
 
   // ---- sweep 1: channel statistics (partials) -----------------------------------
   if (out->scheme != ZC_SCHEME_TOKEN && a.tiles[0] + a.tiles[1] > 0) {
-    const int TX = a.NV >= 256 ? 256 : (int)align_up64(a.NV, 64);
-    dim3 grid((unsigned)(a.tiles[0] + a.tiles[1]), (unsigned)x->B), block(TX);
+    const int TX = a.NV >= kStatThreads ? kStatThreads : (int)align_up64(a.NV, 64);
+    dim3 grid((unsigned)(a.tiles[0] + a.tiles[1]), (unsigned)x->B, (unsigned)ceil_div64(a.NV, kStatThreads)), block(TX);
     if (x->dtype == ZC_F32) hipLaunchKernelGGL(k_chan_stats<ZC_F32>, grid, block, 0, st, a);
     else if (x->dtype == ZC_F16) hipLaunchKernelGGL(k_chan_stats<ZC_F16>, grid, block, 0, st, a);
     else hipLaunchKernelGGL(k_chan_stats<ZC_BF16>, grid, block, 0, st, a);
@@ -506,10 +571,20 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   hipLaunchKernelGGL(k_chan_finalize, dim3((unsigned)ceil_div64(W, 64), 2, (unsigned)x->B), dim3(64, 4), 0, st, a);
   ZC_LAUNCH_CHECK();
   // ---- sweep 2: quantize + pack ---------------------------------------------------
+  // word groups per workgroup: one while the launch is small (latency), up to a whole
+  // block of consecutive slots when there is enough work to fill the chip anyway
+  {
+    const int64_t total = (int64_t)(a.units[0] + a.units[1]) * x->B;
+    int upw = 1;
+    while (upw < 4 && total / (2 * upw) >= 1024) upw *= 2;
+    a.upw = upw;
+    a.wgs[0] = a.units[0] / upw;
+    a.wgs[1] = a.units[1] / upw;
+  }
   if (a.units[0] + a.units[1] > 0) {
     const bool tokwise = out->scheme != ZC_SCHEME_CHANNEL;
     const int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
-    dim3 grid((unsigned)(a.units[0] + a.units[1]), (unsigned)x->B), block(TXq);
+    dim3 grid((unsigned)(a.wgs[0] + a.wgs[1]), (unsigned)x->B), block(TXq);
     if (x->dtype == ZC_F32) launch_qp<ZC_F32>(a, out->layout, tokwise, grid, block, st);
     else if (x->dtype == ZC_F16) launch_qp<ZC_F16>(a, out->layout, tokwise, grid, block, st);
     else launch_qp<ZC_BF16>(a, out->layout, tokwise, grid, block, st);
