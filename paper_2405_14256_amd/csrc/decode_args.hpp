@@ -5,7 +5,7 @@
 
 namespace zc {
 
-constexpr int kTailUnit = 32;    // tail tokens per work unit of the MFMA decode kernel
+constexpr int kTailUnit = 16;    // tail tokens per work unit of the MFMA decode kernel (a multiple of 16)
 constexpr int kMaxSplits = 128;
 constexpr int kTailSplits = 8;    // most workgroups per (batch, KV head) that share the tail
 constexpr int kSegCost = 3;        // cost, in blocks, charged for starting a segment (query operand)

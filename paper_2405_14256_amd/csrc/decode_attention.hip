@@ -427,8 +427,8 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   int S = split_cap(q->B, q->H);
   a.S_packed = 0;
   if (mfma_path) {
-    // tail: one wave per unit of kTailUnit tokens, four waves per workgroup
-    int TW = (int)ceil_div64(ceil_div64(tail_len, kTailUnit), 4);
+    // tail: one wave per unit of kTailUnit tokens
+    int TW = (int)ceil_div64(ceil_div64(tail_len, kTailUnit), 2);   // two busy waves per workgroup measured faster than four
     if (TW > kTailSplits) TW = kTailSplits;
     // packed cache: give every wave about two units before splitting further;
     // the reduce kernel reads at most 32 partials per head

@@ -369,12 +369,12 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
   };
 
   // ---------------- full-precision tail: workgroups of its own ----------------------------
-  // One wave per unit of kTailUnit tokens.  All K and V rows of the unit are
+  // One wave per unit of kTailUnit tokens (one 16-row MFMA tile).  All K and V rows of the unit are
   // requested before the query operand is built, so the unit costs one trip to
   // memory.  Logits on the matrix cores (K rows as the A operand); the weighted
   // sum of V on the vector ALUs, lane = (token mod TPI, 8 channels).
   if (s >= a.S_packed && a.tail_len > 0) {
-    constexpr int LPT = D / 8, TPI = 64 / LPT, NI = kTailUnit / TPI;
+    constexpr int LPT = D / 8, TPI = 64 / LPT, NI = kTailUnit / TPI, NJ = kTailUnit / 16;
     const int tw = s - a.S_packed, n_tw = a.S - a.S_packed;
     const int n_tail = ceil_div(a.tail_len, kTailUnit);
     const int tlo = (int)((int64_t)n_tail * tw / n_tw), thi = (int)((int64_t)n_tail * (tw + 1) / n_tw);
@@ -383,14 +383,14 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
     const int vtok = lane / LPT, vch = 8 * (lane % LPT);
     struct TBuf {
-      Raw8<DT> k[2][KS];
+      Raw8<DT> k[NJ][KS];
       Raw8<DT> v[NI];
     };
     auto load_unit = [&](int tu, TBuf& bf) {
       const int t0 = tu * kTailUnit;
       const int ntok = min(kTailUnit, a.tail_len - t0);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           bf.k[j][ks] = raw_load8<DT>(a.tail_k, kb + (int64_t)(t0 + 16 * j + n) * a.tk_sL + 32 * ks + 8 * grp, 16 * j + n < ntok);
@@ -412,9 +412,9 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
     for (int tu = wlo; tu < whi; ++tu) {
       if (tu > wlo) load_unit(tu, bf);
       const int ntok = min(kTailUnit, a.tail_len - tu * kTailUnit);
-      float U[2][4];
+      float U[NJ][4];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         // rows past the end of the tail are zeros; every lane takes part in the MFMAs
         f4 s_hi = f4{0.f, 0.f, 0.f, 0.f}, s_lo = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -428,10 +428,13 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
             uint32_t rh[4], rl[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const _Float16 h0 = (_Float16)kv[2 * i], h1 = (_Float16)kv[2 * i + 1];
-              rh[i] = pack_h2(h0, h1);
-              if constexpr (DT == ZC_F32)
+              if constexpr (DT == ZC_F32) {
+                const _Float16 h0 = (_Float16)kv[2 * i], h1 = (_Float16)kv[2 * i + 1];
+                rh[i] = pack_h2(h0, h1);
                 rl[i] = pack_h2((_Float16)((kv[2 * i] - (float)h0) * kLoScale), (_Float16)((kv[2 * i + 1] - (float)h1) * kLoScale));
+              } else {
+                rh[i] = pack_f2(kv[2 * i], kv[2 * i + 1]);
+              }
             }
             u4 ah; ah.x = rh[0]; ah.y = rh[1]; ah.z = rh[2]; ah.w = rh[3];
             s_hi = mfma16(ah, qB[ks], s_hi);
@@ -447,7 +450,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
       }
       float lmax = -INFINITY;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           if (16 * j + 4 * grp + v >= ntok) U[j][v] = -INFINITY;
@@ -469,7 +472,7 @@ __global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
       }
       m_run = m_new;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const float p = nvalid ? fast_exp2(U[j][v] - m_run) : 0.f;     // 0 past the end of the tail
