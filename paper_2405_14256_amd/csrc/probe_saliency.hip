@@ -3,12 +3,16 @@
 //
 // The probe rows of A = Softmax(Q_probe K^T / sqrt(d)) are never stored.  Two
 // matrix-core sweeps recompute the logits instead:
-//   k_probe_lse     one workgroup per 64 probe rows: streams 128-column K tiles
-//                   through LDS, logits come out of the MFMA as D[column][row]
-//                   so that every lane owns one probe row and keeps its running
-//                   (max, sum) in two registers; writes log-sum-exp per row.
+//   k_probe_lse     one workgroup per 64 probe rows and column range (the columns a
+//                   row block can see are split over up to 8 workgroups when the
+//                   launch would not fill the chip): streams 128-column K tiles
+//                   through LDS (the next tile's loads in flight), logits come
+//                   out of the MFMA as D[column][row] so that every lane owns one
+//                   probe row and keeps its running (max, sum) in two registers;
+//                   writes the (max, sum) pair per row and column range.
 //   k_probe_colsum  one workgroup per 128 key columns: K fragments stay in
-//                   registers, 64-row probe tiles stream through LDS, logits
+//                   registers, 64-row probe tiles stream through LDS (merging the
+//                   (max, sum) pairs of a row into its log-sum-exp on the way), logits
 //                   come out as D[row][column] so that every lane owns one
 //                   column and sums exp(logit - lse) over the rows in registers;
 //                   divides by the number of probes that can see the column.
@@ -34,8 +38,9 @@ struct ProbeArgs {
   const int32_t* probe_rows;
   const int32_t* probe_pos;
   float scale_log2;
-  const float* lse_in;   // natural log, [B, Hq, P]
-  float* lse_out;
+  const float* lse_in;   // natural log, [B, Hq, P]; null: use the partials
+  float2* lse_part;      // [B, Hq, P, nsplit] (running maximum in log2 units, sum): sweep 1's result
+  int nsplit;            // column ranges a row block's sweep 1 is split into
   float* per_head;       // [B, Hq, Lk]
 };
 
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
   __shared__ int spos[64];
   __shared__ float sm[4][64], sz[4][64];
 
-  const int rb0 = blockIdx.x * 64, hq = blockIdx.y, b = blockIdx.z, hk = hq / a.G;
+  const int rb0 = blockIdx.x * 64, hq = blockIdx.y, b = blockIdx.z / a.nsplit, split = blockIdx.z % a.nsplit, hk = hq / a.G;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
   const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
   const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
@@ -99,6 +104,9 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
   const int nvalid = min(64, a.P - rb0);
   const int pmax = min(spos[nvalid - 1], a.Lk - 1);
   const int ntiles = pmax / 128 + 1;
+  // this workgroup's share of the column tiles
+  const int per = ceil_div(ntiles, a.nsplit);
+  const int t_begin = split * per, t_end = min(t_begin + per, ntiles);
 
   u32x4 qf[2][T::NKC];
 #pragma unroll
@@ -109,16 +117,31 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
   const int myp[2] = {spos[r], spos[32 + r]};
   float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
 
-  for (int t = 0; t < ntiles; ++t) {
-    __syncthreads();
-    for (int i = tid; i < 128 * T::CPR; i += 256) {
+  // a K tile travels global -> registers -> LDS; the next tile's loads are in
+  // flight while the current one is multiplied
+  constexpr int KCH = 128 * T::CPR / 256;      // 16-byte chunks per thread and tile
+  u32x4 kreg[KCH];
+  auto fetch = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+      const int i = tid + j * 256;
       const int row = i / T::CPR, cc = i % T::CPR;
       const int col = t * 128 + row;
-      u32x4 v = {0, 0, 0, 0};
-      if (col < a.Lk) v = *reinterpret_cast<const u32x4*>(kb + (int64_t)col * a.k_sL * T::EB + cc * 16);
-      *reinterpret_cast<u32x4*>(Ks + row * T::STRIDE + cc * 16) = v;
+      kreg[j] = u32x4{0, 0, 0, 0};
+      if (col < a.Lk) kreg[j] = *reinterpret_cast<const u32x4*>(kb + (int64_t)col * a.k_sL * T::EB + cc * 16);
+    }
+  };
+  if (t_begin < t_end) fetch(t_begin);
+
+  for (int t = t_begin; t < t_end; ++t) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+      const int i = tid + j * 256;
+      *reinterpret_cast<u32x4*>(Ks + (i / T::CPR) * T::STRIDE + (i % T::CPR) * 16) = kreg[j];
     }
     __syncthreads();
+    if (t + 1 < t_end) fetch(t + 1);
     v16f acc[2];
 #pragma unroll
     for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
@@ -167,7 +190,7 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) Z += sz[i][tid] * exp2f(sm[i][tid] - M);
     }
-    a.lse_out[((int64_t)b * a.Hq + hq) * a.P + rb0 + tid] = (M + log2f(Z)) * kLn2;
+    a.lse_part[(((int64_t)b * a.Hq + hq) * a.P + rb0 + tid) * a.nsplit + split] = make_float2(M, Z);
   }
 }
 
@@ -194,7 +217,7 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
   const int rbw = w >> 1, cbp = w & 1;
   const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
   const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
-  const float* lse = a.lse_in + ((int64_t)b * a.Hq + hq) * a.P;
+  const int64_t lrow = ((int64_t)b * a.Hq + hq) * a.P;
 
   for (int i = tid; i < 128 * T::CPR; i += 256) {
     const int row = i / T::CPR, cc = i % T::CPR;
@@ -214,24 +237,59 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
   const int pstart = lower_bound_pos(a.probe_pos, a.P, col0);
   float colsum[2] = {0.f, 0.f};
 
-  for (int pr = pstart; pr < a.P; pr += 64) {
-    __syncthreads();
-    for (int i = tid; i < 64 * T::CPR; i += 256) {
+  // a tile of 64 probe rows travels global -> registers -> LDS, the next one in
+  // flight while the current one is multiplied; threads 0..63 also carry the
+  // row's position and its log-sum-exp (log2 units)
+  constexpr int QCH = 64 * T::CPR / 256;
+  u32x4 qreg[QCH];
+  int pos_reg = -1;
+  float lse_reg = 0.f;
+  auto fetch = [&](int pr) {
+#pragma unroll
+    for (int j = 0; j < QCH; ++j) {
+      const int i = tid + j * 256;
       const int row = i / T::CPR, cc = i % T::CPR;
       const int p = pr + row;
-      u32x4 v = {0, 0, 0, 0};
+      qreg[j] = u32x4{0, 0, 0, 0};
       if (p < a.P) {
         const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
-        v = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
+        qreg[j] = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
       }
-      *reinterpret_cast<u32x4*>(Qs + row * T::STRIDE + cc * 16) = v;
     }
     if (tid < 64) {
       const int p = pr + tid;
-      spos[tid] = p < a.P ? a.probe_pos[p] : -1;
-      slse[tid] = p < a.P ? lse[p] * kLog2e : 0.f;
+      pos_reg = p < a.P ? a.probe_pos[p] : -1;
+      lse_reg = 0.f;
+      if (p < a.P) {
+        if (a.lse_in) {
+          lse_reg = a.lse_in[lrow + p] * kLog2e;
+        } else {
+          // merge sweep 1's partial (maximum, sum) pairs of this row
+          const float2* part = a.lse_part + (lrow + p) * a.nsplit;
+          float M = -INFINITY;
+          for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, part[sp].x);
+          float Z = 0.f;
+          for (int sp = 0; sp < a.nsplit; ++sp) {
+            const float2 v = part[sp];
+            if (v.x > -INFINITY) Z += v.y * exp2f(v.x - M);
+          }
+          lse_reg = M + log2f(Z);
+        }
+      }
     }
+  };
+  if (pstart < a.P) fetch(pstart);
+
+  for (int pr = pstart; pr < a.P; pr += 64) {
     __syncthreads();
+#pragma unroll
+    for (int j = 0; j < QCH; ++j) {
+      const int i = tid + j * 256;
+      *reinterpret_cast<u32x4*>(Qs + (i / T::CPR) * T::STRIDE + (i % T::CPR) * 16) = qreg[j];
+    }
+    if (tid < 64) { spos[tid] = pos_reg; slse[tid] = lse_reg; }
+    __syncthreads();
+    if (pr + 64 < a.P) fetch(pr + 64);
     int rp[16];
     float rl[16];
 #pragma unroll
@@ -272,24 +330,33 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
   }
 }
 
-__global__ void k_probe_mean(const float* __restrict__ per_head, float* __restrict__ scores, int Hq, int Lk) {
+// Mean over the query heads: block (64 columns, 4 head groups); every group
+// sums its heads in order, the four partial sums are then added in order.
+__global__ __launch_bounds__(256) void k_probe_mean(const float* __restrict__ per_head, float* __restrict__ scores, int Hq, int Lk) {
+  __shared__ float part[4][64];
   const int b = blockIdx.y;
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= Lk) return;
+  const int cx = threadIdx.x, gy = threadIdx.y;
+  const int i = blockIdx.x * 64 + cx;
+  const int per = (Hq + 3) / 4;
   float s = 0.f;
-  for (int h = 0; h < Hq; ++h) s += per_head[((int64_t)b * Hq + h) * Lk + i];
-  scores[(int64_t)b * Lk + i] = s / (float)Hq;
+  if (i < Lk) {
+    const int h1 = min(Hq, (gy + 1) * per);
+    for (int h = gy * per; h < h1; ++h) s += per_head[((int64_t)b * Hq + h) * Lk + i];
+  }
+  part[gy][cx] = s;
+  __syncthreads();
+  if (gy == 0 && i < Lk) scores[(int64_t)b * Lk + i] = (((part[0][cx] + part[1][cx]) + part[2][cx]) + part[3][cx]) / (float)Hq;
 }
 
 template <int DT, int D>
 static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStream_t st) {
   if (need_lse) {
-    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3(ceil_div(a.P, 64), a.Hq, a.B), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3(ceil_div(a.P, 64), a.Hq, a.B * a.nsplit), dim3(256), 0, st, a);
     ZC_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL((k_probe_colsum<DT, D>), dim3(ceil_div(a.Lk, 128), a.Hq, a.B), dim3(256), 0, st, a);
   ZC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_probe_mean, dim3(ceil_div(a.Lk, 256), a.B), dim3(256), 0, st, a.per_head, scores, a.Hq, a.Lk);
+  hipLaunchKernelGGL(k_probe_mean, dim3(ceil_div(a.Lk, 64), a.B), dim3(64, 4), 0, st, a.per_head, scores, a.Hq, a.Lk);
   ZC_LAUNCH_CHECK();
   return ZC_OK;
 }
@@ -298,7 +365,14 @@ static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStr
 
 using namespace zc;
 
-static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * 4, 256); }
+constexpr int kMaxProbeSplit = 8;
+// column ranges per row block of sweep 1: enough workgroups to fill the chip
+static int probe_splits(int64_t B, int64_t Hq, int64_t P) {
+  const int64_t wgs = B * Hq * ceil_div64(P, 64);
+  int64_t ns = ceil_div64(1024, wgs);
+  return (int)(ns < 1 ? 1 : (ns > kMaxProbeSplit ? kMaxProbeSplit : ns));
+}
+static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * kMaxProbeSplit * (int64_t)sizeof(float2), 256); }
 
 extern "C" size_t zc_probe_saliency_workspace(int64_t B, int64_t Hq, int64_t Lk, int64_t P) {
   if (B <= 0 || Hq <= 0 || Lk <= 0 || P <= 0) return 0;
@@ -329,10 +403,11 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   a.B = (int)q->B; a.Hq = (int)q->H; a.Hkv = (int)k->H; a.G = a.Hq / a.Hkv; a.Lk = (int)k->L; a.P = P;
   a.probe_rows = probe_rows; a.probe_pos = probe_pos;
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)q->D) : sm_scale) * kLog2e;
-  float* ws_lse = reinterpret_cast<float*>(ws);
   float* ws_ph = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + lse_bytes(q->B, q->H, P));
-  a.lse_in = lse_ext ? lse_ext : ws_lse;
-  a.lse_out = ws_lse;
+  a.lse_in = lse_ext;
+  a.lse_part = reinterpret_cast<float2*>(ws);
+  a.nsplit = probe_splits(q->B, q->H, P);
+  if ((int64_t)q->B * a.nsplit > 65535) return ZC_ERR_UNSUPPORTED;
   a.per_head = scores_per_head ? scores_per_head : ws_ph;
 
   hipStream_t st = (hipStream_t)stream;
