@@ -30,6 +30,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
+constexpr int kMaxProbeSplit = 8;
+
 struct ProbeArgs {
   const void* q;
   const void* k;
@@ -38,8 +40,9 @@ struct ProbeArgs {
   const int32_t* probe_rows;
   const int32_t* probe_pos;
   float scale_log2;
-  const float* lse_in;   // natural log, [B, Hq, P]; null: use the partials
-  float2* lse_part;      // [B, Hq, P, nsplit] (running maximum in log2 units, sum): sweep 1's result
+  const float* lse_in;   // natural log, [B, Hq, P]; null: use lse2
+  float* lse2;           // [B, Hq, P] log-sum-exp in log2 units: sweep 1's result
+  float2* lse_part;      // [B, Hq, P, nsplit] (running maximum in log2 units, sum) when nsplit > 1
   int nsplit;            // column ranges a row block's sweep 1 is split into
   float* per_head;       // [B, Hq, Lk]
 };
@@ -71,6 +74,15 @@ struct Tile {
   static constexpr int NKC = ROWB / 32;        // operand chunks per lane and row
 };
 
+// Workgroups are handed to the 8 XCDs round-robin by their linear index, and
+// every XCD has its own L2.  This maps the hardware index to a logical index such
+// that each XCD gets one contiguous range of logical indices: workgroups that
+// read the same K head (or the same probe rows) then share an L2.
+__device__ inline int xcd_contiguous(int id, int n) {
+  const int xcd = id & 7, slot = id >> 3;
+  return xcd * (n >> 3) + min(xcd, n & 7) + slot;
+}
+
 // Row index inside a 32x32 MFMA result held by accumulator register v of a lane
 // in half-wave kh.
 __device__ inline int acc_row(int v, int kh) { return 8 * (v >> 2) + 4 * kh + (v & 3); }
@@ -78,44 +90,31 @@ __device__ inline int acc_row(int v, int kh) { return 8 * (v >> 2) + 4 * kh + (v
 template <int DT, int D>
 __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
   using T = Tile<DT, D>;
-  __shared__ __align__(16) uint8_t Qs[64 * T::STRIDE];
+  // the probe rows go through the same LDS space as the K tiles: they are in
+  // registers before the first tile arrives (four workgroups fit a CU this way)
   __shared__ __align__(16) uint8_t Ks[128 * T::STRIDE];
+  uint8_t* Qs = Ks;
   __shared__ int spos[64];
   __shared__ float sm[4][64], sz[4][64];
 
-  const int rb0 = blockIdx.x * 64, hq = blockIdx.y, b = blockIdx.z / a.nsplit, split = blockIdx.z % a.nsplit, hk = hq / a.G;
+  // logical order: probe-row block fastest, then column range, then query head, then batch
+  const int nrb = ceil_div(a.P, 64);
+  int j = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int rb0 = (j % nrb) * 64; j /= nrb;
+  const int split = j % a.nsplit; j /= a.nsplit;
+  const int hq = j % a.Hq, b = j / a.Hq, hk = hq / a.G;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
   const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
   const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
 
-  for (int i = tid; i < 64 * T::CPR; i += 256) {
-    const int row = i / T::CPR, cc = i % T::CPR;
-    const int p = rb0 + row;
-    u32x4 v = {0, 0, 0, 0};
-    if (p < a.P) {
-      const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
-      v = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
-    }
-    *reinterpret_cast<u32x4*>(Qs + row * T::STRIDE + cc * 16) = v;
-  }
-  if (tid < 64) spos[tid] = (rb0 + tid < a.P) ? a.probe_pos[rb0 + tid] : -1;
-  __syncthreads();
-
+  // the block's last row decides how many column tiles it sees; read it first so
+  // that the first K tile is requested together with the probe rows
   const int nvalid = min(64, a.P - rb0);
-  const int pmax = min(spos[nvalid - 1], a.Lk - 1);
+  const int pmax = min(a.probe_pos[rb0 + nvalid - 1], a.Lk - 1);
   const int ntiles = pmax / 128 + 1;
   // this workgroup's share of the column tiles
   const int per = ceil_div(ntiles, a.nsplit);
   const int t_begin = split * per, t_end = min(t_begin + per, ntiles);
-
-  u32x4 qf[2][T::NKC];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int kc = 0; kc < T::NKC; ++kc)
-      qf[rb][kc] = *reinterpret_cast<const u32x4*>(Qs + (rb * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
-  const int myp[2] = {spos[r], spos[32 + r]};
-  float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
 
   // a K tile travels global -> registers -> LDS; the next tile's loads are in
   // flight while the current one is multiplied
@@ -132,6 +131,28 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
     }
   };
   if (t_begin < t_end) fetch(t_begin);
+
+  for (int i = tid; i < 64 * T::CPR; i += 256) {
+    const int row = i / T::CPR, cc = i % T::CPR;
+    const int p = rb0 + row;
+    u32x4 v = {0, 0, 0, 0};
+    if (p < a.P) {
+      const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
+      v = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
+    }
+    *reinterpret_cast<u32x4*>(Qs + row * T::STRIDE + cc * 16) = v;
+  }
+  if (tid < 64) spos[tid] = (rb0 + tid < a.P) ? a.probe_pos[rb0 + tid] : -1;
+  __syncthreads();
+
+  u32x4 qf[2][T::NKC];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int kc = 0; kc < T::NKC; ++kc)
+      qf[rb][kc] = *reinterpret_cast<const u32x4*>(Qs + (rb * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+  const int myp[2] = {spos[r], spos[32 + r]};
+  float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
 
   for (int t = t_begin; t < t_end; ++t) {
     __syncthreads();
@@ -152,24 +173,39 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
       mma_chunk<DT>(acc[1], af, qf[1][kc]);
     }
     const int colb = t * 128 + w * 32;
+    // rows are sorted by position: when the tile's last column is visible to the
+    // block's first row, nothing in the tile is masked
+    const bool tile_full = t * 128 + 127 <= spos[0];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-      float sv[16];
-      float tmax = -INFINITY;
+      if (tile_full) {
+        float tmax = acc[rb][0];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int col = colb + acc_row(v, kh);
-        const float s = (col <= myp[rb]) ? acc[rb][v] * a.scale_log2 : -INFINITY;
-        sv[v] = s;
-        tmax = fmaxf(tmax, s);
-      }
-      const float m_new = fmaxf(m[rb], tmax);
-      if (m_new > -INFINITY) {
+        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[rb][v]);
+        const float m_new = fmaxf(m[rb], tmax * a.scale_log2);
         float sum = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sum += exp2f(sv[v] - m_new);
-        z[rb] = z[rb] * exp2f(m[rb] - m_new) + sum;
+        for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][v], a.scale_log2, -m_new));
+        z[rb] = z[rb] * __builtin_amdgcn_exp2f(m[rb] - m_new) + sum;
         m[rb] = m_new;
+      } else {
+        float sv[16];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int col = colb + acc_row(v, kh);
+          const float sc = (col <= myp[rb]) ? acc[rb][v] * a.scale_log2 : -INFINITY;
+          sv[v] = sc;
+          tmax = fmaxf(tmax, sc);
+        }
+        const float m_new = fmaxf(m[rb], tmax);
+        if (m_new > -INFINITY) {
+          float sum = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(sv[v] - m_new);
+          z[rb] = z[rb] * __builtin_amdgcn_exp2f(m[rb] - m_new) + sum;
+          m[rb] = m_new;
+        }
       }
     }
   }
@@ -190,8 +226,27 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) Z += sz[i][tid] * exp2f(sm[i][tid] - M);
     }
-    a.lse_part[(((int64_t)b * a.Hq + hq) * a.P + rb0 + tid) * a.nsplit + split] = make_float2(M, Z);
+    const int64_t row = ((int64_t)b * a.Hq + hq) * a.P + rb0 + tid;
+    if (a.nsplit == 1) a.lse2[row] = M + log2f(Z);
+    else a.lse_part[row * a.nsplit + split] = make_float2(M, Z);
   }
+}
+
+// Merges the (maximum, sum) pairs of a probe row's column ranges.
+__global__ void k_probe_lse_merge(const float2* __restrict__ part, float* __restrict__ lse2, int64_t rows, int nsplit) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows) return;
+  float2 v[kMaxProbeSplit];
+#pragma unroll
+  for (int sp = 0; sp < kMaxProbeSplit; ++sp) v[sp] = sp < nsplit ? part[i * nsplit + sp] : make_float2(-INFINITY, 0.f);
+  float M = -INFINITY;
+#pragma unroll
+  for (int sp = 0; sp < kMaxProbeSplit; ++sp) M = fmaxf(M, v[sp].x);
+  float Z = 0.f;
+#pragma unroll
+  for (int sp = 0; sp < kMaxProbeSplit; ++sp)
+    if (v[sp].x > -INFINITY) Z += v[sp].y * exp2f(v[sp].x - M);
+  lse2[i] = M + log2f(Z);
 }
 
 __device__ inline int lower_bound_pos(const int32_t* pos, int n, int key) {
@@ -206,13 +261,18 @@ __device__ inline int lower_bound_pos(const int32_t* pos, int n, int key) {
 template <int DT, int D>
 __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
   using T = Tile<DT, D>;
+  // one LDS space: first the K tile (until its fragments are in registers), then
+  // the probe positions followed by the current tile of probe rows
   __shared__ __align__(16) uint8_t Ks[128 * T::STRIDE];
-  __shared__ __align__(16) uint8_t Qs[64 * T::STRIDE];
   __shared__ int spos[64];
   __shared__ float slse[64];
   __shared__ float scol[2][128];
 
-  const int col0 = blockIdx.x * 128, hq = blockIdx.y, b = blockIdx.z, hk = hq / a.G;
+  // logical order: column tile fastest, then query head, then batch
+  const int nct = ceil_div(a.Lk, 128);
+  int j = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int col0 = (j % nct) * 128; j /= nct;
+  const int hq = j % a.Hq, b = j / a.Hq, hk = hq / a.G;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
   const int rbw = w >> 1, cbp = w & 1;
   const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
@@ -234,7 +294,19 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
     for (int kc = 0; kc < T::NKC; ++kc)
       kf[cb][kc] = *reinterpret_cast<const u32x4*>(Ks + ((cbp * 2 + cb) * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
 
-  const int pstart = lower_bound_pos(a.probe_pos, a.P, col0);
+  // the K tile is in registers now: its LDS space takes the probe positions, so
+  // that the two binary searches of this workgroup do not go to memory
+  __syncthreads();
+  constexpr int kPosCap = (128 - 64) * T::STRIDE / 4;     // what the tile of probe rows leaves free
+  const int32_t* ppos = a.probe_pos;
+  uint8_t* Qs = Ks + 64 * T::STRIDE;
+  if (a.P <= kPosCap) {
+    int32_t* lp = reinterpret_cast<int32_t*>(Ks);
+    for (int i = tid; i < a.P; i += 256) lp[i] = a.probe_pos[i];
+    __syncthreads();
+    ppos = lp;
+  }
+  const int pstart = lower_bound_pos(ppos, a.P, col0);
   float colsum[2] = {0.f, 0.f};
 
   // a tile of 64 probe rows travels global -> registers -> LDS, the next one in
@@ -261,20 +333,7 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
       pos_reg = p < a.P ? a.probe_pos[p] : -1;
       lse_reg = 0.f;
       if (p < a.P) {
-        if (a.lse_in) {
-          lse_reg = a.lse_in[lrow + p] * kLog2e;
-        } else {
-          // merge sweep 1's partial (maximum, sum) pairs of this row
-          const float2* part = a.lse_part + (lrow + p) * a.nsplit;
-          float M = -INFINITY;
-          for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, part[sp].x);
-          float Z = 0.f;
-          for (int sp = 0; sp < a.nsplit; ++sp) {
-            const float2 v = part[sp];
-            if (v.x > -INFINITY) Z += v.y * exp2f(v.x - M);
-          }
-          lse_reg = M + log2f(Z);
-        }
+        lse_reg = a.lse_in ? a.lse_in[lrow + p] * kLog2e : a.lse2[lrow + p];
       }
     }
   };
@@ -306,13 +365,21 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
       mma_chunk<DT>(acc[0], af, kf[0][kc]);
       mma_chunk<DT>(acc[1], af, kf[1][kc]);
     }
+    // a tile of 64 real rows whose first position is past this workgroup's last
+    // column needs no mask
+    const bool tile_full = pr + 64 <= a.P && col0 + 127 <= spos[0];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
       const int col = col0 + (cbp * 2 + cb) * 32 + r;
+      if (tile_full) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float e = exp2f(acc[cb][v] * a.scale_log2 - rl[v]);
-        colsum[cb] += (col <= rp[v]) ? e : 0.f;
+        for (int v = 0; v < 16; ++v) colsum[cb] += __builtin_amdgcn_exp2f(fmaf(acc[cb][v], a.scale_log2, -rl[v]));
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(acc[cb][v], a.scale_log2, -rl[v]));
+          colsum[cb] += (col <= rp[v]) ? e : 0.f;
+        }
       }
     }
   }
@@ -325,7 +392,7 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
   if (tid < 128 && col0 + tid < a.Lk) {
     const int col = col0 + tid;
     const float total = scol[0][tid] + scol[1][tid];
-    const int cnt = a.P - lower_bound_pos(a.probe_pos, a.P, col);
+    const int cnt = a.P - lower_bound_pos(ppos, a.P, col);
     a.per_head[((int64_t)b * a.Hq + hq) * a.Lk + col] = cnt > 0 ? total / (float)cnt : 0.f;
   }
 }
@@ -351,10 +418,15 @@ __global__ __launch_bounds__(256) void k_probe_mean(const float* __restrict__ pe
 template <int DT, int D>
 static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStream_t st) {
   if (need_lse) {
-    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3(ceil_div(a.P, 64), a.Hq, a.B * a.nsplit), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3((unsigned)((int64_t)ceil_div(a.P, 64) * a.Hq * a.B * a.nsplit)), dim3(256), 0, st, a);
     ZC_LAUNCH_CHECK();
+    if (a.nsplit > 1) {
+      const int64_t rows = (int64_t)a.B * a.Hq * a.P;
+      hipLaunchKernelGGL(k_probe_lse_merge, dim3((unsigned)ceil_div64(rows, 256)), dim3(256), 0, st, a.lse_part, a.lse2, rows, a.nsplit);
+      ZC_LAUNCH_CHECK();
+    }
   }
-  hipLaunchKernelGGL((k_probe_colsum<DT, D>), dim3(ceil_div(a.Lk, 128), a.Hq, a.B), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((k_probe_colsum<DT, D>), dim3((unsigned)((int64_t)ceil_div(a.Lk, 128) * a.Hq * a.B)), dim3(256), 0, st, a);
   ZC_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_probe_mean, dim3(ceil_div(a.Lk, 64), a.B), dim3(64, 4), 0, st, a.per_head, scores, a.Hq, a.Lk);
   ZC_LAUNCH_CHECK();
@@ -365,14 +437,13 @@ static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStr
 
 using namespace zc;
 
-constexpr int kMaxProbeSplit = 8;
 // column ranges per row block of sweep 1: enough workgroups to fill the chip
 static int probe_splits(int64_t B, int64_t Hq, int64_t P) {
   const int64_t wgs = B * Hq * ceil_div64(P, 64);
-  int64_t ns = ceil_div64(1024, wgs);
+  int64_t ns = 1024 / wgs;      // four workgroups fit a CU
   return (int)(ns < 1 ? 1 : (ns > kMaxProbeSplit ? kMaxProbeSplit : ns));
 }
-static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * kMaxProbeSplit * (int64_t)sizeof(float2), 256); }
+static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * (kMaxProbeSplit * (int64_t)sizeof(float2) + 4), 256); }
 
 extern "C" size_t zc_probe_saliency_workspace(int64_t B, int64_t Hq, int64_t Lk, int64_t P) {
   if (B <= 0 || Hq <= 0 || Lk <= 0 || P <= 0) return 0;
@@ -406,8 +477,10 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   float* ws_ph = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + lse_bytes(q->B, q->H, P));
   a.lse_in = lse_ext;
   a.lse_part = reinterpret_cast<float2*>(ws);
+  a.lse2 = reinterpret_cast<float*>(a.lse_part + (int64_t)q->B * q->H * P * kMaxProbeSplit);
   a.nsplit = probe_splits(q->B, q->H, P);
-  if ((int64_t)q->B * a.nsplit > 65535) return ZC_ERR_UNSUPPORTED;
+  if ((int64_t)ceil_div64(P, 64) * q->H * q->B * a.nsplit > 0x7fffffff || (int64_t)ceil_div64(k->L, 128) * q->H * q->B > 0x7fffffff)
+    return ZC_ERR_UNSUPPORTED;
   a.per_head = scores_per_head ? scores_per_head : ws_ph;
 
   hipStream_t st = (hipStream_t)stream;
