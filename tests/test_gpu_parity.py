@@ -60,6 +60,23 @@ def test_needles_are_selected():
     assert rep["salient_overlap"] > 0.99
 
 
+# ---- the other configurations at their full sizes -------------------------------------
+# The GPU runs the whole batch in the launch configuration the benchmark times; the
+# oracle checks one batch element (every stage, element by element) and a few decode steps.
+
+def test_full_size_mistral_7b_8k_b8():
+    run_pipeline_check(WORKLOADS["mistral_7b_8k_b8"], decode_steps=3, bsel=[5], verbose=True)
+
+
+def test_full_size_llama2_13b_4k_b16():
+    run_pipeline_check(WORKLOADS["llama2_13b_4k_b16"], decode_steps=3, bsel=[11], verbose=True)
+
+
+def test_full_size_llama3_8b_32k():
+    rep = run_pipeline_check(WORKLOADS["llama3_8b_32k"], decode_steps=3, verbose=True)
+    assert rep["salient_overlap"] > 0.99
+
+
 # ---- edge cases ---------------------------------------------------------------------
 
 def _rand_scores(B, L, seed):
