@@ -185,7 +185,8 @@ def cpu_baseline(hp: HotPath, decode_sample: int = 4):
     except Exception:
         cores = os.cpu_count() or 1
     w = hp.w
-    Q, K, V = (to_f64(hp.cpu_inputs[n]) for n in ("Q", "K", "V"))
+    nb = 1 if w.B > 1 else w.B          # batch elements are independent: time one, scale by B
+    Q, K, V = (to_f64(hp.cpu_inputs[n][:nb]) for n in ("Q", "K", "V"))
     t0 = time.perf_counter()
     scores, _ = zo.saliency_scores(Q, K, hp.pos_np)
     ck, cv, sal, reg = zo.compress_prefill(K, V, scores, hp.k, w.bits_hi, w.bits_lo)
@@ -194,13 +195,13 @@ def cpu_baseline(hp: HotPath, decode_sample: int = 4):
     n = min(decode_sample, hp.S)
     for j in range(n):
         d = hp.cpu_decode[j]
-        cache.step(to_f64(d["q"]), to_f64(d["k_new"]), to_f64(d["v_new"]), False)
+        cache.step(to_f64(d["q"][:nb]), to_f64(d["k_new"][:nb]), to_f64(d["v_new"][:nb]), False)
     t2 = time.perf_counter()
-    t_step = (t1 - t0) + (t2 - t1) / n * hp.S
+    t_step = ((t1 - t0) + (t2 - t1) / n * hp.S) * (w.B / nb)
     return {"value": w.B * hp.S / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"float64 numpy oracle: probe scores + split + quantize of the full {w.name} prefill "
-                      f"({t1 - t0:.2f} s) and {n} of {hp.S} decode steps ({(t2 - t1) / n:.3f} s each), "
-                      f"extrapolated to one whole step"}, sal
+            "sample": f"float64 numpy oracle on {nb} of {w.B} batch elements: probe scores + split + quantize of the "
+                      f"{w.name} prefill ({t1 - t0:.2f} s) and {n} of {hp.S} decode steps ({(t2 - t1) / n:.3f} s each), "
+                      f"extrapolated to one whole step of the whole batch"}, sal
 
 
 def main():
@@ -211,6 +212,9 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_4k")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run three plain copies of 256 MiB (a kernel of known traffic, "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -292,10 +296,18 @@ def main():
             "probe_saliency_TFLOPs": probe_tflops, "probe_saliency_ms": stage_ms["probe"],
             "select_ms": stage_ms["select"], "flush_ms": stage_ms.get("flush", 0.0),
             "timing": "HIP events between the stage graphs inside the timed region"},
-        "roofline": {"bound": "hbm", "kernel": "k_decode_mfma (zc_decode_attention)",
+        "roofline": {"bound": "hbm", "kernel": "zc_decode_attention (k_decode_mfma + k_decode_reduce)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "bytes_per_launch": dec_avg_bytes, "avg_launch_us": dec_avg_ms * 1e3, "traffic": None},
     }
+    if w.name != "llama3_8b_4k":
+        result["metric"] += f" (supplementary workload {w.name})"
+    if args.calibrate_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"], _ = cpu_baseline(hp)
     print(json.dumps(result))

@@ -40,6 +40,7 @@ struct DecArgs {
   float scale_log2;
   int S, n_units;  // workgroups per (batch, KV head); length of the packed cache's cost line
   int S_packed;    // the first S_packed workgroups split the packed cache, the others the tail
+  int n_cu;        // compute units of the device
   float* part_m;   // [B, Hq, S]
   float* part_z;   // [B, Hq, S]
   float* part_o;   // [B, Hq, S, D]

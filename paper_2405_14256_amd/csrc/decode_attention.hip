@@ -442,6 +442,18 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     S = (int)(units > 0 ? units : 1);
   }
   a.S = S;
+  {
+    // compute units of the current device (asked once per process and device id)
+    static int cu_of_device[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ZC_ERR_HIP;
+    int ncu = (dev >= 0 && dev < 64) ? cu_of_device[dev] : 0;
+    if (ncu == 0) {
+      if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0) ncu = 256;
+      if (dev >= 0 && dev < 64) cu_of_device[dev] = ncu;
+    }
+    a.n_cu = ncu;
+  }
   const int64_t nq = q->B * q->H;
   float* wsf = reinterpret_cast<float*>(ws);
   a.part_m = wsf;

@@ -187,8 +187,11 @@ __device__ inline void raw_to_float(const Raw8<DT>& r, float (&v)[8]) {
   }
 }
 
-template <int DT, int D, bool KTOK, bool VTOK>
-__global__ __launch_bounds__(256, 2) void k_decode_mfma(DecArgs a) {
+// MINB: workgroups per CU the register budget is sized for.  2 for launches that
+// fill the chip; 1 (the whole register file, nothing spilled to scratch) for
+// launches of at most one workgroup per CU, where only latency counts.
+template <int DT, int D, bool KTOK, bool VTOK, int MINB>
+__global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   constexpr int KS = D / 32;     // k-steps of the logit product
   constexpr int NR = D / 64;     // 16-byte V loads per lane and block
   constexpr int MG = ZC_MAX_GROUP;
@@ -799,10 +802,16 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
 template <int DT>
 static int launch_decode_mfma_dt(const DecArgs& a, hipStream_t st) {
   dim3 grid(a.S, a.Hkv, a.B), block(256);
-#define ZC_L(KT, VT)                                                                              \
-  do {                                                                                            \
-    if (a.D == 128) hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT>), grid, block, 0, st, a);  \
-    else hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT>), grid, block, 0, st, a);              \
+  const bool small = (int64_t)a.S * a.Hkv * a.B <= a.n_cu;
+#define ZC_L(KT, VT)                                                                                          \
+  do {                                                                                                        \
+    if (a.D == 128) {                                                                                         \
+      if (small) hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 1>), grid, block, 0, st, a);              \
+      else hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 2>), grid, block, 0, st, a);                    \
+    } else {                                                                                                  \
+      if (small) hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 1>), grid, block, 0, st, a);               \
+      else hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 2>), grid, block, 0, st, a);                     \
+    }                                                                                                         \
   } while (0)
   if (a.k_tok && a.v_tok) ZC_L(true, true);
   else if (a.k_tok) ZC_L(true, false);
