@@ -428,11 +428,11 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   a.S_packed = 0;
   if (mfma_path) {
     // tail: one wave per unit of kTailUnit tokens
-    int TW = (int)ceil_div64(ceil_div64(tail_len, kTailUnit), 2);   // two busy waves per workgroup measured faster than four
+    int TW = (int)ceil_div64(tail_len, kTailUnit);   // one busy wave per workgroup measured fastest
     if (TW > kTailSplits) TW = kTailSplits;
     // packed cache: give every wave about two units before splitting further;
     // the reduce kernel reads at most 32 partials per head
-    const int64_t want = ceil_div64(units, 6);
+    const int64_t want = ceil_div64(units, 8);
     if (S > want) S = (int)want;
     if (S > 32 - TW) S = 32 - TW;
     if (S + TW == 0) S = 1;          // empty cache: one workgroup writes the zeros
