@@ -187,6 +187,26 @@ __device__ inline void raw_to_float(const Raw8<DT>& r, float (&v)[8]) {
   }
 }
 
+// ---- global -> LDS without passing through registers -----------------------------------
+// One instruction moves 64 x 16 (or 64 x 4) bytes: lane l's bytes go to
+// lds_addr + OFF + l * 16 (or * 4); OFF is added to the memory address too.  Lanes
+// whose address is outside the buffer write zeros.  The compiler does not know
+// about these transfers: the reader waits with wait_vmem<N>() for all but the N
+// newest loads of the wave, and must have its own reads of a staging buffer
+// complete (dma_reuse_fence) before loads into the same buffer are issued.
+template <int OFF>
+__device__ inline void dma16(uint32_t lds_addr, __amdgpu_buffer_rsrc_t rs, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen offset:%4 lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff), "n"(OFF) : "memory");
+}
+__device__ inline void dma4(uint32_t lds_addr, __amdgpu_buffer_rsrc_t rs, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff) : "memory");
+}
+template <int N>
+__device__ inline void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+__device__ inline void dma_reuse_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 // MINB: workgroups per CU the register budget is sized for.  2 for launches that
 // fill the chip; 1 (the whole register file, nothing spilled to scratch) for
 // launches of at most one workgroup per CU, where only latency counts.
@@ -198,7 +218,17 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   __shared__ u4 sqB[KS][64];              // query operand of the current segment
   __shared__ float ssum[2][KS][64];
   __shared__ float svc[2][D];             // channel scale and zero of V for the current segment
-  __shared__ float mO[4][MG][D];
+  // Per wave a ring of kStages staging buffers for one block of the packed cache
+  // each: K codes (D * 16 bytes), V codes (D * 16 bytes), then 256 bytes each of
+  // V token scale, V token zero, K token scale, K token zero.  After its last block a
+  // wave's ring holds its partial output for the merge (mO).
+  constexpr int kStages = 3;
+  constexpr int kCodeBytes = D * 16;
+  constexpr int kStageBytes = 2 * kCodeBytes + 1024;
+  constexpr int kRingBytes = kStages * kStageBytes;
+  static_assert(kRingBytes >= MG * D * 4, "a wave's ring must hold its partial output");
+  __shared__ __align__(16) uint8_t ring[4][kRingBytes];
+  auto mO = [&](int w, int gg, int c) -> float& { return reinterpret_cast<float*>(&ring[w][0])[gg * D + c]; };
   __shared__ float mM[4][MG], mZ[4][MG];
   __shared__ float ptile[4][MG][kTailUnit];
 
@@ -276,10 +306,17 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         const float4 zb = *reinterpret_cast<const float4*>(kcz + base + 8 + 4 * (ks0 & 1));
         const float csa[4] = {ca.x, ca.y, ca.z, ca.w}, csb[4] = {cb.x, cb.y, cb.z, cb.w};
         const float cza[4] = {za.x, za.y, za.z, za.w}, czb[4] = {zb.x, zb.y, zb.z, zb.w};
+        // (a wave-uniform branch with constant indices: a select between array
+        // elements would put the arrays in scratch memory)
+        if (ks0 & 1) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { q8[2 * i] = qa[4 + i]; q8[2 * i + 1] = qb[4 + i]; }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { q8[2 * i] = qa[i]; q8[2 * i + 1] = qb[i]; }
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          q8[2 * i] = (ks0 & 1) ? qa[4 + i] : qa[i];
-          q8[2 * i + 1] = (ks0 & 1) ? qb[4 + i] : qb[i];
           cs8[2 * i] = csa[i]; cs8[2 * i + 1] = csb[i];
           cz8[2 * i] = cza[i]; cz8[2 * i + 1] = czb[i];
         }
@@ -356,7 +393,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       for (int w = 0; w < 4; ++w) {
         if (mM[w][gg] > -INFINITY) {
           const float f = fast_exp2(mM[w][gg] - M);
-          o = fmaf(mO[w][gg][c], f, o);
+          o = fmaf(mO(w, gg, c), f, o);
           z = fmaf(mZ[w][gg], f, z);
         }
       }
@@ -508,7 +545,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
           float x = Ot[gg][e];
 #pragma unroll
           for (int o = LPT; o < 64; o <<= 1) x += __shfl_xor(x, o);
-          if (lane < LPT) mO[wave][gg][vch + e] = x;
+          if (lane < LPT) mO(wave, gg, vch + e) = x;
         }
       }
     }
@@ -545,48 +582,36 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const auto rs_ktz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? a.k_tz[sub] + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
     const auto rs_vts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? a.v_ts[sub] + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
     const auto rs_vtz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? a.v_tz[sub] + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
-    const int voff_k = n * ROWB + grp * (KW * 4);
-    const int voff_v = grp * (D * 4) + 16 * n;
-    const int voff_t = 16 * grp;
-
-    // The loop runs over half-blocks of 32 slots (two 16-slot tiles): a 4-bit block
-    // is one of them, a 2-bit block two that share the same V words.
-    struct Buf {
-      uint32_t kw[2][KW];
-      u4 vw[NR];
-      u4 kts[2], ktz[2], vts[2], vtz[2];
-    };
-    auto load_half = [&](int hb, Buf& bf) {
-      const int hslot = begin + 32 * hb;               // first slot of the half-block
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const int so = (int)((uint32_t)(hslot + 16 * jj) * (uint32_t)ROWB);
-        if constexpr (KW == 4) {
-          const u4 t = __builtin_amdgcn_raw_buffer_load_b128(rs_k, voff_k, so, 0);
-          bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; bf.kw[jj][2] = t.z; bf.kw[jj][3] = t.w;
-        } else if constexpr (KW == 2) {
-          const auto t = __builtin_amdgcn_raw_buffer_load_b64(rs_k, voff_k, so, 0);
-          bf.kw[jj][0] = t[0]; bf.kw[jj][1] = t[1];
-        } else {
-          bf.kw[jj][0] = __builtin_amdgcn_raw_buffer_load_b32(rs_k, voff_k, so, 0);
-        }
-        const int to = (int)((uint32_t)(hslot + 16 * jj) * 4u);
-        if constexpr (KTOK) {
-          bf.kts[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_kts, voff_t, to, 0);
-          bf.ktz[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_ktz, voff_t, to, 0);
-        }
-        if constexpr (VTOK) {
-          bf.vts[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_vts, voff_t, to, 0);
-          bf.vtz[jj] = __builtin_amdgcn_raw_buffer_load_b128(rs_vtz, voff_t, to, 0);
-        }
+    // Staging: block bi of the segment is D * 16 contiguous bytes of K codes and as
+    // many of V codes; each goes to LDS with KCH 1 KB transfers.  (Token parameters:
+    // 64 floats per array, of which a 4-bit block uses the first 32.)
+    constexpr int KCH = D / 64;                           // 1 KB transfers per code array and block
+    constexpr int L_STAGE = 2 * KCH + (VTOK ? 2 : 0) + (KTOK ? 2 : 0);   // transfers per block
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&ring[wave][0];
+    const uint8_t* ring_gen = &ring[wave][0];
+    const int bl_lo = hlo / NH, bl_hi = hlo < hhi ? (hhi - 1) / NH + 1 : hlo / NH;    // this wave's blocks
+    auto issue = [&](int st, int bi) {
+      const uint32_t dst = ring_lds + st * kStageBytes;
+      const int ko = (int)((uint32_t)(begin + bi * TB) * (uint32_t)ROWB);          // = block index * D * 16
+      const int to = (int)((uint32_t)(begin + bi * TB) * 4u);
+      dma16<0>(dst, rs_k, 16 * lane, ko);
+      if constexpr (KCH == 2) dma16<1024>(dst, rs_k, 16 * lane, ko);
+      dma16<0>(dst + kCodeBytes, rs_v, 16 * lane, ko);
+      if constexpr (KCH == 2) dma16<1024>(dst + kCodeBytes, rs_v, 16 * lane, ko);
+      if constexpr (VTOK) {
+        dma4(dst + 2 * kCodeBytes, rs_vts, 4 * lane, to);
+        dma4(dst + 2 * kCodeBytes + 256, rs_vtz, 4 * lane, to);
       }
-      const int vo = (int)((uint32_t)(begin / TB + hb / NH) * (uint32_t)(4 * D * 4));
-#pragma unroll
-      for (int r = 0; r < NR; ++r) bf.vw[r] = __builtin_amdgcn_raw_buffer_load_b128(rs_v, voff_v + 256 * r, vo, 0);
+      if constexpr (KTOK) {
+        dma4(dst + 2 * kCodeBytes + 512, rs_kts, 4 * lane, to);
+        dma4(dst + 2 * kCodeBytes + 768, rs_ktz, 4 * lane, to);
+      }
     };
+    // the first blocks are in flight while the operand is built
+#pragma unroll
+    for (int i = 0; i < kStages - 1; ++i)
+      if (bl_lo + i < bl_hi) issue(i, bl_lo + i);
 
-    Buf b0, b1;
-    if (hlo < hhi) load_half(hlo, b0);       // in flight while the operand is built
     u4 qB[KS];
     float Aq, sumqcz;
     build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz);
@@ -613,8 +638,24 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       for (int j = 0; j < 4; ++j) acc[r][j] = f4{0.f, 0.f, 0.f, 0.f};
     float a1 = 0.f;                       // sum of w tz
 
-    auto half_block = [&](const Buf& bf, int hb) {
+    auto half_block = [&](int st, int hb) {
       const int h = hb % NH;
+      // operands of this half-block from the staging buffer
+      const uint8_t* sb = ring_gen + st * kStageBytes;
+      struct { uint32_t kw[2][KW]; u4 vw[NR]; u4 kts[2], ktz[2], vts[2], vtz[2]; } bf;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const int row = 16 * (2 * h + jj) + n;
+        const uint8_t* kp = sb + row * ROWB + grp * (KW * 4);
+        if constexpr (KW == 4) { const u4 t = *reinterpret_cast<const u4*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; bf.kw[jj][2] = t.z; bf.kw[jj][3] = t.w; }
+        else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; }
+        else { bf.kw[jj][0] = *reinterpret_cast<const uint32_t*>(kp); }
+        const uint8_t* tp = sb + 2 * kCodeBytes + (16 * (2 * h + jj) + 4 * grp) * 4;
+        if constexpr (VTOK) { bf.vts[jj] = *reinterpret_cast<const u4*>(tp); bf.vtz[jj] = *reinterpret_cast<const u4*>(tp + 256); }
+        if constexpr (KTOK) { bf.kts[jj] = *reinterpret_cast<const u4*>(tp + 512); bf.ktz[jj] = *reinterpret_cast<const u4*>(tp + 768); }
+      }
+#pragma unroll
+      for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const u4*>(sb + kCodeBytes + grp * (D * 4) + 16 * (n + 16 * r));
       const int ntok = len - 32 * hb;                  // slots of this half-block inside the segment, >= 1
       const bool masked = ntok < 32;                   // only the last half-block of a segment
       float lg[2][4], vts[2][4], vtz[2][4];
@@ -695,16 +736,26 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       }
     };
 
-    // two buffers in turn: half-block i + 1 is requested before half-block i is computed
-    for (int hb = hlo; hb < hhi; hb += 2) {
-      const bool second = hb + 1 < hhi;
-      if (second) load_half(hb + 1, b1);
-      half_block(b0, hb);
-      if (second) {
-        if (hb + 2 < hhi) load_half(hb + 2, b0);
-        half_block(b1, hb + 1);
+    // Blocks in turn through the ring: the block kStages - 1 ahead is requested, then
+    // the wave waits for all but the loads issued after the current block's.
+    for (int bi = bl_lo; bi < bl_hi; ++bi) {
+      const int st = (bi - bl_lo) % kStages;
+      const int ahead = bi + kStages - 1;
+      if (ahead < bl_hi) {
+        dma_reuse_fence();                       // last iteration's reads of that buffer are complete
+        issue((st + kStages - 1) % kStages, ahead);
+      }
+      const int later = min(kStages - 1, bl_hi - 1 - bi);     // blocks requested after this one
+      if (later >= 2) wait_vmem<2 * L_STAGE>();
+      else if (later == 1) wait_vmem<L_STAGE>();
+      else wait_vmem<0>();
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        const int hb = bi * NH + h;
+        if (hb >= hlo && hb < hhi) half_block(st, hb);
       }
     }
+    dma_reuse_fence();                           // the ring is reused (next segment, merge)
     // ---- fold the segment into O ----
     //   subnormal codes:   sum_t w code = acc 2^(24 - P),  sum_t w = acc1
     //   normalized codes:  sum_t w code = acc - acc1,         sum_t w = acc1 / SC
@@ -735,12 +786,19 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 
   for (int ci = 0; ci < a.n_chunks; ++ci) {
     for (int sub = 0; sub < 2; ++sub) {
+      // The row of the chunk table: from the kernel arguments (a scalar load) when the
+      // table travels there, else from memory.  The empty asm statements pin each
+      // source's values in scalar registers, so that the two loads are not merged
+      // into one load through a selected (then generic) pointer.
       int begin, len;
-      if (a.chunks_inline) { begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1]; }
-      else { begin = a.chunk_table[4 * ci + 2 * sub]; len = a.chunk_table[4 * ci + 2 * sub + 1]; }
-      // wave-uniform by construction; say so, so that offsets derived from them stay in scalar registers
-      begin = __builtin_amdgcn_readfirstlane(begin);
-      len = __builtin_amdgcn_readfirstlane(len);
+      if (a.chunks_inline) {
+        begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1];
+        asm volatile("" : "+s"(begin), "+s"(len));
+      } else {
+        begin = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub]);
+        len = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub + 1]);
+        asm volatile("" : "+s"(begin), "+s"(len));
+      }
       const int bits = a.bits[sub];
       const int TB = 4 * (32 / bits);
       const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
@@ -762,8 +820,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = 4 * (n + 16 * r) + j;
-      if (g0 < G) mO[wave][g0][c] = O[r][j][0];
-      if (g1 < G) mO[wave][g1][c] = O[r][j][1];
+      if (g0 < G) mO(wave, g0, c) = O[r][j][0];
+      if (g1 < G) mO(wave, g1, c) = O[r][j][1];
     }
   __syncthreads();
   write_result();
