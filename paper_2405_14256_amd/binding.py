@@ -118,10 +118,10 @@ _ws_cache = {}
 
 
 def _workspace(nbytes: int, device, tag: str = "scratch") -> torch.Tensor:
-    """A per-device, per-operation scratch tensor, zero-filled when allocated,
-    grown on demand and reused across calls (the decode workspace must start
-    zeroed and is left zeroed by every call)."""
-    key = (str(device), tag)
+    """A scratch tensor per device, operation and stream (calls issued on different
+    streams may run concurrently, so they must not share scratch memory), grown
+    on demand and reused across calls."""
+    key = (str(device), tag, _stream())
     cur = _ws_cache.get(key)
     if cur is None or cur.numel() < nbytes:
         cur = torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
