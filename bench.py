@@ -34,6 +34,10 @@ from paper_2405_14256_amd import probes                 # noqa: E402
 from paper_2405_14256_amd.workloads import WORKLOADS, make_decode_step, make_prefill, to_f64  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per decode call from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by
+# what the same counter reads for a plain 256 MiB copy); the summary of those runs and their
+# commands are in profiles/decode_traffic_llama3_8b_4k.txt.  Not measurable from inside this script.
+MEASURED_DECODE_TRAFFIC = {"llama3_8b_4k": 5265027.0}
 FLUSH_INTERVAL = 100
 
 
@@ -298,7 +302,8 @@ def main():
             "timing": "HIP events between the stage graphs inside the timed region"},
         "roofline": {"bound": "hbm", "kernel": "zc_decode_attention (k_decode_mfma + k_decode_reduce)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "bytes_per_launch": dec_avg_bytes, "avg_launch_us": dec_avg_ms * 1e3, "traffic": None},
+                     "bytes_per_launch": dec_avg_bytes, "avg_launch_us": dec_avg_ms * 1e3,
+                     "traffic": MEASURED_DECODE_TRAFFIC.get(w.name)},
     }
     if w.name != "llama3_8b_4k":
         result["metric"] += f" (supplementary workload {w.name})"
