@@ -424,24 +424,6 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   a.tail_len = (int)tail_len;
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)q->D) : sm_scale) * kLog2e;
   a.n_units = (int)units;
-  int S = split_cap(q->B, q->H);
-  a.S_packed = 0;
-  if (mfma_path) {
-    // tail: one wave per unit of kTailUnit tokens
-    int TW = (int)ceil_div64(tail_len, kTailUnit);   // one busy wave per workgroup measured fastest
-    if (TW > kTailSplits) TW = kTailSplits;
-    // packed cache: give every wave about two units before splitting further;
-    // the reduce kernel reads at most 32 partials per head
-    const int64_t want = ceil_div64(units, 8);
-    if (S > want) S = (int)want;
-    if (S > 32 - TW) S = 32 - TW;
-    if (S + TW == 0) S = 1;          // empty cache: one workgroup writes the zeros
-    a.S_packed = S;
-    S += TW;
-  } else if (S > units) {
-    S = (int)(units > 0 ? units : 1);
-  }
-  a.S = S;
   {
     // compute units of the current device (asked once per process and device id)
     static int cu_of_device[64] = {0};
@@ -454,6 +436,40 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     }
     a.n_cu = ncu;
   }
+  int S = split_cap(q->B, q->H);
+  a.S_packed = 0;
+  if (mfma_path) {
+    const int64_t heads = q->B * Kp->H;
+    const int64_t tail_units = ceil_div64(tail_len, kTailUnit);
+    // Packed cache.  About eight cost units per workgroup is the finest useful split;
+    // the reduce kernel reads at most 32 partials per head.
+    int64_t want = ceil_div64(units, 8);
+    if (want > 32) want = 32;
+    if (want > S) want = S;
+    if (heads * want <= a.n_cu) {
+      S = (int)want;                 // one workgroup per CU at most: only latency counts
+    } else {
+      // The launch runs in rounds of two workgroups per CU; a workgroup costs a fixed
+      // part (start-up, operand, merge: about 48 units' worth, measured) plus its units.
+      int64_t best = 0, best_cost = 0;
+      for (int64_t c = 1; c <= want; ++c) {
+        const int64_t cost = ceil_div64(heads * c, 2 * (int64_t)a.n_cu) * (48 + ceil_div64(units, c));
+        if (best == 0 || cost < best_cost) { best = c; best_cost = cost; }
+      }
+      S = (int)best;
+    }
+    // Tail: one unit (a wave's work) per workgroup while the launch stays below one
+    // workgroup per CU, else eight units per workgroup.
+    int64_t TW = (heads * (S + tail_units) <= a.n_cu) ? tail_units : ceil_div64(tail_units, 8);
+    if (TW > kTailSplits) TW = kTailSplits;
+    if (S > 32 - TW) S = 32 - (int)TW;
+    if (S + TW == 0) S = 1;          // empty cache: one workgroup writes the zeros
+    a.S_packed = S;
+    S += (int)TW;
+  } else if (S > units) {
+    S = (int)(units > 0 ? units : 1);
+  }
+  a.S = S;
   const int64_t nq = q->B * q->H;
   float* wsf = reinterpret_cast<float*>(ws);
   a.part_m = wsf;
