@@ -31,6 +31,14 @@ def test_tiny_other_schemes(k_scheme, v_scheme):
     run_pipeline_check(WORKLOADS["tiny"], decode_steps=3, k_scheme=k_scheme, v_scheme=v_scheme, verbose=True)
 
 
+@pytest.mark.parametrize("bits_hi,bits_lo", [(8, 4), (8, 8), (4, 4), (2, 2), (8, 2)])
+def test_other_bit_widths(bits_hi, bits_lo):
+    # 8-bit subsets take the generic decode kernel, equal widths the matrix-core one
+    run_pipeline_check(scaled(WORKLOADS["tiny"], bits_hi=bits_hi, bits_lo=bits_lo), decode_steps=3, verbose=True)
+    w = scaled(WORKLOADS["llama3_8b_4k"], L=700, decode_steps=2, bits_hi=bits_hi, bits_lo=bits_lo)
+    run_pipeline_check(w, verbose=True)
+
+
 def test_llama3_shape_ragged():
     # several 128-column tiles, 64-row probe tiles and 32/64-slot blocks, all with ragged tails
     w = scaled(WORKLOADS["llama3_8b_4k"], L=1237, decode_steps=5)
