@@ -230,6 +230,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   __shared__ __align__(16) uint8_t ring[4][kRingBytes];
   auto mO = [&](int w, int gg, int c) -> float& { return reinterpret_cast<float*>(&ring[w][0])[gg * D + c]; };
   __shared__ float mM[4][MG], mZ[4][MG];
+  __shared__ __align__(16) float lds_ones[4];   // what the sum-of-p rows read in place of the V token scales
   __shared__ float ptile[4][MG][kTailUnit];
 
   const int s = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
@@ -244,9 +245,15 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   const float c_own = part ? kLoInv : 1.f, c_oth = part ? 1.f : kLoInv;
   constexpr bool WSPLIT = (DT == ZC_F32);    // softmax weights as value + residual
   constexpr bool SUBN = (DT != ZC_F32);      // codes enter as fp16 subnormals
+  // q' always enters as value + residual (two columns per head).  A single fp16 q'
+  // was tried for 16-bit tensors: it saves two instructions per logit but moves the
+  // log-sum-exp by up to 3e-3, which the streaming saliency scores inherit.
+  constexpr bool QSPLIT = true;
 
   // running state of this wave; unused columns sit at +inf so that their weights are 0
   float m_run = nvalid ? -INFINITY : INFINITY, z_part = 0.f;
+  float Zrun0 = 0.f, Zrun1 = 0.f;            // unsplit weights: sum of p of heads g0, g1 (from the matrix cores)
+  if (tid < 4) lds_ones[tid] = 1.f;          // (published by the barriers of the first operand build)
   float O[NR][4][2];
 #pragma unroll
   for (int r = 0; r < NR; ++r)
@@ -266,6 +273,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
       z_part *= fac; a1 *= fac;
       const float f0 = __shfl(fac, 2 * g0), f1 = __shfl(fac, 2 * g1);
+      Zrun0 *= f0; Zrun1 *= f1;
 #pragma unroll
       for (int r = 0; r < NR; ++r)
 #pragma unroll
@@ -358,7 +366,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         for (int half = 0; half < 2; ++half) {
           const float qv = nvalid ? q8[2 * i + half] * a.scale_log2 * cs8[2 * i + half] * comp : 0.f;
           float rep;
-          hv[half] = split_part(qv, part, rep);
+          if constexpr (QSPLIT) {
+            hv[half] = split_part(qv, part, rep);
+          } else {
+            hv[half] = (_Float16)qv;
+            rep = (float)hv[half];
+          }
           sq = fmaf(rep, inv_comp, sq);
           sqz = fmaf(rep * inv_comp, cz8[2 * i + half], sqz);
         }
@@ -486,7 +499,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         }
         const float own[4] = {s_hi.x + s_lo.x * kLoInv, s_hi.y + s_lo.y * kLoInv, s_hi.z + s_lo.z * kLoInv, s_hi.w + s_lo.w * kLoInv};
 #pragma unroll
-        for (int v = 0; v < 4; ++v) U[j][v] = fmaf(xor1(own[v]), c_oth, own[v] * c_own);
+        for (int v = 0; v < 4; ++v) U[j][v] = QSPLIT ? fmaf(xor1(own[v]), c_oth, own[v] * c_own) : own[v];
       }
       float lmax = -INFINITY;
 #pragma unroll
@@ -618,11 +631,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     if (hlo >= hhi) return;
     const float kconst = SUBN ? -sumqcz : -(SC * Aq + sumqcz);   // normalized codes: the "1" terms add SC sum(q')
     const float c_own_s = c_own * UNSCALE, c_oth_s = c_oth * UNSCALE;
-    // factor of operand register v of the weights; the residual rows are unused
-    // (zero) when the weights are not split
+    // factor of operand register v of the weights.  When the weights are not split,
+    // the second row of a head carries p instead of w = p ts: its product with the
+    // constants below is the sum of p (the softmax denominator), at no VALU cost
     float wcomp[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) wcomp[v] = (!WSPLIT && part) ? 0.f : code_comp<BITS, SUBN>(v);
+    for (int v = 0; v < 4; ++v) wcomp[v] = code_comp<BITS, SUBN>(v);
     // B operand that sums the weights: 1 / factor of each operand register
     // (normalized codes: plain ones, the sum then carries SC and is also the "1" term of the output product)
     u4 ones;
@@ -651,7 +665,11 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; }
         else { bf.kw[jj][0] = *reinterpret_cast<const uint32_t*>(kp); }
         const uint8_t* tp = sb + 2 * kCodeBytes + (16 * (2 * h + jj) + 4 * grp) * 4;
-        if constexpr (VTOK) { bf.vts[jj] = *reinterpret_cast<const u4*>(tp); bf.vtz[jj] = *reinterpret_cast<const u4*>(tp + 256); }
+        if constexpr (VTOK) {
+          const uint8_t* tps = (!WSPLIT && part) ? reinterpret_cast<const uint8_t*>(lds_ones) : tp;
+          bf.vts[jj] = *reinterpret_cast<const u4*>(tps);
+          bf.vtz[jj] = *reinterpret_cast<const u4*>(tp + 256);
+        }
         if constexpr (KTOK) { bf.kts[jj] = *reinterpret_cast<const u4*>(tp + 512); bf.ktz[jj] = *reinterpret_cast<const u4*>(tp + 768); }
       }
 #pragma unroll
@@ -678,7 +696,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         vtz[jj][2] = __uint_as_float(bf.vtz[jj].z); vtz[jj][3] = __uint_as_float(bf.vtz[jj].w);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          float x = fmaf(xor1(own[v]), c_oth_s, fmaf(own[v], c_own_s, kconst));
+          float x;
+          if constexpr (QSPLIT) x = fmaf(xor1(own[v]), c_oth_s, fmaf(own[v], c_own_s, kconst));
+          else x = fmaf(own[v], UNSCALE, kconst);
           if constexpr (KTOK) x = kts[v] * fmaf(-ktz[v], Aq, x);
           lg[jj][v] = x;
         }
@@ -711,7 +731,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
             w = p * vts[jj][v];
             a1 = fmaf(w, vtz[jj][v], a1);
           }
-          z_part += p;
+          if constexpr (WSPLIT) z_part += p;
           w2[jj][v] = w * wcomp[v];
         }
       u4 pA;
@@ -764,6 +784,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const float r1 = WSPLIT ? acc1.z + acc1.w * kLoInv : acc1.z;
     const float sw0 = SUBN ? r0 : r0 * (1.f / SC), sw1 = SUBN ? r1 : r1 * (1.f / SC);
     const float bias0 = SUBN ? 0.f : r0, bias1 = SUBN ? 0.f : r1;
+    if constexpr (!WSPLIT) { Zrun0 += acc1.y; Zrun1 += acc1.w; }
     float a10 = 0.f, a11 = 0.f;
     if constexpr (VTOK) {
       a1 = grp_sum(a1);
@@ -813,8 +834,16 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   }
 
   // ---------------- merge the four waves --------------------------------------------------
-  const float z_tot = grp_sum(z_part);
-  if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
+  if constexpr (WSPLIT) {
+    const float z_tot = grp_sum(z_part);
+    if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
+  } else {
+    if (nvalid && part == 0 && grp == 0) mM[wave][g] = m_run;
+    if (n == 0) {
+      if (g0 < G) mZ[wave][g0] = Zrun0;
+      if (g1 < G) mZ[wave][g1] = Zrun1;
+    }
+  }
 #pragma unroll
   for (int r = 0; r < NR; ++r)
 #pragma unroll
