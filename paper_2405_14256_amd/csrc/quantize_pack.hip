@@ -243,8 +243,11 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
   if (x < TB) { const int rel = blk * TB + x; sidx[x] = rel < n ? idx[rel] : -1; }
 
   // parameters of the channels this thread owns
-  const bool vvalid = x < a.NV;
-  const int w = (vvalid ? x : 0) * 8, h = w / a.D, c = w % a.D;
+  // (the channelwise scheme needs no reduction over a token row, so its launches cut
+  // the row into chunks of blockDim.x vectors along grid.z)
+  const int vec = (int)blockIdx.z * TX + x;
+  const bool vvalid = vec < a.NV;
+  const int w = (vvalid ? vec : 0) * 8, h = w / a.D, c = w % a.D;
   const char* xbase = reinterpret_cast<const char*>(a.x) + ((int64_t)b * a.sB + (int64_t)h * a.sH + c) * ESZ;
   const int64_t row_bytes = a.sL * ESZ;
   float p0[8], p1[8], p2[8];
@@ -306,7 +309,7 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
     // bookkeeping of the batch's tokens by lanes 0 .. TBAT-1 of the first wave
     const int my_t = lane < TBAT ? lane : 0;
     const int my_rel = blk * TB + slot_of(q, my_t);
-    const bool my_live = x < TBAT && my_rel < n;
+    const bool my_live = x < TBAT && blockIdx.z == 0 && my_rel < n;
     const int64_t my_o = (int64_t)b * a.cap[sub] + a.begin[sub] + my_rel;
     if (my_live && a.pos[sub]) a.pos[sub][my_o] = (int32_t)(sidx[my_rel - blk * TB] + a.pos_offset);
 
@@ -583,8 +586,10 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   }
   if (a.units[0] + a.units[1] > 0) {
     const bool tokwise = out->scheme != ZC_SCHEME_CHANNEL;
-    const int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
-    dim3 grid((unsigned)(a.wgs[0] + a.wgs[1]), (unsigned)x->B), block(TXq);
+    int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
+    int zchunks = 1;
+    if (!tokwise && TXq > 256) { zchunks = (int)ceil_div64(a.NV, 256); TXq = 256; }
+    dim3 grid((unsigned)(a.wgs[0] + a.wgs[1]), (unsigned)x->B, (unsigned)zchunks), block(TXq);
     if (x->dtype == ZC_F32) launch_qp<ZC_F32>(a, out->layout, tokwise, grid, block, st);
     else if (x->dtype == ZC_F16) launch_qp<ZC_F16>(a, out->layout, tokwise, grid, block, st);
     else launch_qp<ZC_BF16>(a, out->layout, tokwise, grid, block, st);
