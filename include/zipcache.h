@@ -192,6 +192,18 @@ int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packe
 size_t zc_arena_bytes(int64_t B, int64_t H, int64_t D, int64_t cap, int32_t bits);
 /* Smallest legal capacity that holds `n_chunks` chunks totalling n tokens. */
 int64_t zc_arena_slots(int64_t n_tokens, int64_t n_chunks);
+/* ---- inverse of the packing (Eq. 5's de-quantization; the bit layouts above) ----
+ * Unpacks subset `which` (0: hi / salient, 1: lo / regular) of chunk `chunk` of
+ * a packed tensor into canonical token-major arrays: element [b, r, w] belongs
+ * to slot r of that chunk's subset (ascending original position) and channel
+ * w = h*D + c.  codes_out (device uint8 [B, len, W], one byte per code) and
+ * dequant_out (device float [B, len, W], x_hat of the formula at zc_scheme) may
+ * each be NULL.  len is the subset's length in the chunk table (host mirror).
+ * Nothing is allocated; the work is enqueued on `stream`.
+ * Errors: ZC_ERR_INVALID_ARG for a bad descriptor, chunk or subset index. */
+int zc_unpack(const zc_packed* p, int32_t which, int32_t chunk, uint8_t* codes_out, float* dequant_out,
+              void* stream);
+
 const char* zc_status_string(int status);
 int zc_version(void);
 

@@ -82,6 +82,8 @@ def load() -> C.CDLL:
     lib.zc_decode_attention_workspace.argtypes = [I64, I64, I64]
     lib.zc_decode_attention.restype = C.c_int
     lib.zc_decode_attention.argtypes = [T4, PK, PK, T4, T4, I64, F, P, P, P, SZ, P]
+    lib.zc_unpack.restype = C.c_int
+    lib.zc_unpack.argtypes = [PK, I32, I32, P, P, P]
     lib.zc_arena_bytes.restype = SZ
     lib.zc_arena_bytes.argtypes = [I64, I64, I64, I64, I32]
     lib.zc_arena_slots.restype = I64
@@ -221,6 +223,20 @@ def zc_quantize_pack(x: torch.Tensor, salient_idx: torch.Tensor, regular_idx: to
            lib.zc_quantize_pack(C.byref(tx), _ptr(salient_idx) if k else None, k,
                                 _ptr(regular_idx) if n_reg else None, n_reg, pos_offset,
                                 C.byref(out.c), ws.data_ptr(), ws.numel(), _stream()))
+
+
+def zc_unpack(p: PackedTensor, which: int, chunk: int, codes: bool = True, dequant: bool = True):
+    """(codes uint8 [B, len, W] or None, x_hat float32 [B, len, W] or None) of subset
+    `which` (0 hi, 1 lo) of chunk `chunk`, token-major in slot order."""
+    lib = load()
+    row = p.chunks[chunk]
+    n = int(row[2 * which + 1])
+    W = p.H * p.D
+    dev = p.chan_scale.device
+    co = torch.empty(p.B, n, W, dtype=torch.uint8, device=dev) if codes else None
+    dq = torch.empty(p.B, n, W, dtype=torch.float32, device=dev) if dequant else None
+    _check("zc_unpack", lib.zc_unpack(C.byref(p.c), which, chunk, _ptr(co) if n else None, _ptr(dq) if n else None, _stream()))
+    return co, dq
 
 
 def zc_decode_attention(q: torch.Tensor, Kp: PackedTensor, Vp: PackedTensor,

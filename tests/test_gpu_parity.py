@@ -137,6 +137,36 @@ def test_quantize_empty_subsets_and_degenerate_rows():
             assert P.chunks == [(0, k, 0, L - k)]
 
 
+@pytest.mark.parametrize("bits_hi,bits_lo", [(4, 2), (8, 4), (2, 2)])
+def test_unpack_inverts_the_packing(bits_hi, bits_lo):
+    # zc_unpack against the reference decoder written from the header (tests/packfmt.py)
+    # and the oracle's de-quantization; two chunks, ragged lengths, both layouts, all schemes
+    from tests.pipeline_check import packed_to_chunks
+    B, H, L, D = 2, 4, 150, 64
+    g = torch.Generator().manual_seed(11)
+    X = torch.randn(B, H, L, D, generator=g).to(torch.bfloat16)
+    X2 = torch.randn(B, H, 70, D, generator=g).to(torch.bfloat16)
+    perm = torch.stack([torch.randperm(L, generator=g) for _ in range(B)])
+    sal = perm[:, :61].sort(dim=1).values.to(torch.int32)
+    reg = perm[:, 61:].sort(dim=1).values.to(torch.int32)
+    sal2 = torch.arange(0, 70, 3, dtype=torch.int32)[None].repeat(B, 1)
+    reg2 = torch.tensor([i for i in range(70) if i % 3], dtype=torch.int32)[None].repeat(B, 1)
+    for scheme, layout in (("cst", zb.ZC_LAYOUT_TGROUP), ("channel", zb.ZC_LAYOUT_ROW), ("token", zb.ZC_LAYOUT_TGROUP), ("channel", zb.ZC_LAYOUT_TGROUP)):
+        P = zb.PackedTensor(B, H, D, 256, 256, bits_hi, bits_lo, scheme, layout, max_chunks=2, device=DEV)
+        zb.zc_quantize_pack(X.to(DEV), sal.to(DEV), reg.to(DEV), P)
+        zb.zc_quantize_pack(X2.to(DEV), sal2.to(DEV), reg2.to(DEV), P, pos_offset=L)
+        torch.cuda.synchronize()
+        ref = packed_to_chunks(P, list(range(B)))
+        for ci in range(2):
+            for which, sub in ((0, ref[ci].hi), (1, ref[ci].lo)):
+                codes, xhat = zb.zc_unpack(P, which, ci)
+                torch.cuda.synchronize()
+                assert np.array_equal(codes.cpu().numpy().astype(np.float64), sub.codes), (scheme, layout, ci, which)
+                want = sub.dequant()
+                got = xhat.cpu().numpy().astype(np.float64)
+                assert np.allclose(got, want, rtol=2e-6, atol=1e-6 * np.abs(want).max()), (scheme, layout, ci, which)
+
+
 def test_decode_tail_only_and_no_tail():
     w = scaled(WORKLOADS["tiny"], L=64)
     B, Hq, Hkv, d = 1, 8, 8, 64
