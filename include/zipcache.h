@@ -18,7 +18,8 @@
  * General rules
  *   - Every pointer marked "device" is GPU memory owned by the caller; every
  *     other pointer is host memory.  The library allocates nothing, keeps no
- *     pointer after a call returns and has no global mutable state.
+ *     pointer after a call returns and has no global mutable state (apart from
+ *     a cached copy of the device's compute-unit count).
  *   - All work is enqueued on the given HIP stream (`stream` is a hipStream_t
  *     passed as void*; NULL is the default stream).  Calls never synchronise
  *     with the host and never read results back.

@@ -324,13 +324,14 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
       const int p = pr + row;
       qreg[j] = u32x4{0, 0, 0, 0};
       if (p < a.P) {
-        const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
+        // (the positions are in LDS by now: no second trip to memory for the row address)
+        const int64_t qrow = a.probe_rows ? a.probe_rows[p] : ppos[p];
         qreg[j] = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
       }
     }
     if (tid < 64) {
       const int p = pr + tid;
-      pos_reg = p < a.P ? a.probe_pos[p] : -1;
+      pos_reg = p < a.P ? ppos[p] : -1;
       lse_reg = 0.f;
       if (p < a.P) {
         lse_reg = a.lse_in ? a.lse_in[lrow + p] * kLog2e : a.lse2[lrow + p];
