@@ -3,6 +3,8 @@
 // on the order-preserving uint32 image of the scores finds the k-th largest
 // key and how many tokens equal to it are taken (lowest indices first); one
 // ordered compaction pass then writes both index lists in ascending order.
+// The keys of a row are read from memory once and kept in LDS (up to 36864 tokens
+// per row; longer rows are re-read from memory by every pass).
 #include "zc_common.hpp"
 
 namespace zc {
@@ -10,14 +12,17 @@ namespace zc {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 
+constexpr int kSelMaxCached = 36864;     // keys of one row that fit the LDS of a CU next to the small arrays
+
+template <bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void k_select_salient(
     const float* __restrict__ scores, int L, int k, int32_t* __restrict__ salient,
     int32_t* __restrict__ regular, uint8_t* __restrict__ mask) {
+  extern __shared__ uint32_t skeys[];     // CACHED: the row's keys
   __shared__ int hist[256];
   __shared__ uint32_t s_prefix;
   __shared__ int s_need;
   __shared__ int s_wave_gt[kSelWaves], s_wave_eq[kSelWaves];
-  __shared__ int s_base_gt, s_base_eq;
 
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
@@ -25,6 +30,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select_salient(
   int32_t* sal = salient + (int64_t)b * k;
   int32_t* reg = regular + (int64_t)b * (L - k);
   uint8_t* mk = mask ? mask + (int64_t)b * L : nullptr;
+  if constexpr (CACHED) {
+    for (int i = tid; i < L; i += kSelThreads) skeys[i] = float_key(sc[i]);
+    __syncthreads();
+  }
+  auto key_at = [&](int i) -> uint32_t {
+    if constexpr (CACHED) return skeys[i];
+    else return float_key(sc[i]);
+  };
 
   // ---- radix select of the k-th largest key ---------------------------------
   uint32_t prefix = 0;   // key bits decided so far (high bits)
@@ -36,7 +49,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_salient(
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       for (int i = tid; i < L; i += kSelThreads) {
-        uint32_t key = float_key(sc[i]);
+        uint32_t key = key_at(i);
         if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
       }
       __syncthreads();
@@ -78,44 +91,52 @@ __global__ __launch_bounds__(kSelThreads) void k_select_salient(
   const bool take_all = (k >= L);
   const bool take_none = (k <= 0);
 
-  if (tid == 0) { s_base_gt = 0; s_base_eq = 0; }
-  __syncthreads();
-
+  // Ordered compaction without a barrier per step: wave w owns the contiguous run
+  // [w * seg, (w + 1) * seg) of the row; it first counts its salient candidates
+  // (> and == the k-th key), the waves exchange the counts once, then every wave
+  // writes its run in order from its own base offsets.
   const int lane = tid & 63, wave = tid >> 6;
-  for (int base = 0; base < L; base += kSelThreads) {
-    const int i = base + tid;
-    bool gt = false, eq = false;
-    if (i < L) {
+  const int seg = ((L + kSelWaves - 1) / kSelWaves + 63) & ~63;
+  const int i0 = min(wave * seg, L), i1 = min(i0 + seg, L);
+  auto classify = [&](int i, bool& gt, bool& eq) {
+    gt = false; eq = false;
+    if (i < i1) {
       if (take_all) gt = true;
       else if (!take_none) {
-        uint32_t key = float_key(sc[i]);
+        const uint32_t key = key_at(i);
         gt = key > prefix;
         eq = key == prefix;
       }
     }
+  };
+  int cnt_gt = 0, cnt_eq = 0;
+  for (int base = i0; base < i1; base += 64) {
+    bool gt, eq;
+    classify(base + lane, gt, eq);
+    cnt_gt += __popcll(__ballot(gt));
+    cnt_eq += __popcll(__ballot(eq));
+  }
+  if (lane == 0) { s_wave_gt[wave] = cnt_gt; s_wave_eq[wave] = cnt_eq; }
+  __syncthreads();
+  int run_gt = 0, run_eq = 0;
+  for (int w = 0; w < wave; ++w) { run_gt += s_wave_gt[w]; run_eq += s_wave_eq[w]; }
+  const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int base = i0; base < i1; base += 64) {
+    const int i = base + lane;
+    bool gt, eq;
+    classify(i, gt, eq);
     const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
-    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    int pre_gt = __popcll(bgt & below), pre_eq = __popcll(beq & below);
-    if (lane == 0) { s_wave_gt[wave] = __popcll(bgt); s_wave_eq[wave] = __popcll(beq); }
-    __syncthreads();
-    int tot_gt = 0, tot_eq = 0;
-    for (int w = 0; w < kSelWaves; ++w) {
-      int g = s_wave_gt[w], e = s_wave_eq[w];
-      if (w < wave) { pre_gt += g; pre_eq += e; }
-      tot_gt += g; tot_eq += e;
-    }
-    const int gt_before = s_base_gt + pre_gt;
-    const int eq_before = s_base_eq + pre_eq;
-    if (i < L) {
+    const int gt_before = run_gt + __popcll(bgt & below);
+    const int eq_before = run_eq + __popcll(beq & below);
+    if (i < i1) {
       const bool is_sal = gt || (eq && eq_before < need);
       const int sal_before = gt_before + min(eq_before, need);
       if (is_sal) sal[sal_before] = i;
       else reg[i - sal_before] = i;
       if (mk) mk[i] = is_sal ? 1 : 0;
     }
-    __syncthreads();
-    if (tid == 0) { s_base_gt += tot_gt; s_base_eq += tot_eq; }
-    __syncthreads();
+    run_gt += __popcll(bgt);
+    run_eq += __popcll(beq);
   }
 }
 
@@ -133,8 +154,20 @@ extern "C" int zc_select_salient(const float* scores, int64_t B, int64_t L, int6
   if ((reinterpret_cast<uintptr_t>(scores) & 3) || (reinterpret_cast<uintptr_t>(salient_idx) & 3) ||
       (reinterpret_cast<uintptr_t>(regular_idx) & 3))
     return ZC_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(zc::k_select_salient, dim3((unsigned)B), dim3(zc::kSelThreads), 0,
-                     (hipStream_t)stream, scores, (int)L, (int)k, salient_idx, regular_idx, mask);
+  if (L <= zc::kSelMaxCached) {
+    const size_t lds = (size_t)L * sizeof(uint32_t);
+    if (lds > 48 * 1024) {
+      // a launch above the default dynamic-LDS limit needs the attribute raised (idempotent)
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&zc::k_select_salient<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)(zc::kSelMaxCached * sizeof(uint32_t))) != hipSuccess)
+        return ZC_ERR_HIP;
+    }
+    hipLaunchKernelGGL(zc::k_select_salient<true>, dim3((unsigned)B), dim3(zc::kSelThreads), lds,
+                       (hipStream_t)stream, scores, (int)L, (int)k, salient_idx, regular_idx, mask);
+  } else {
+    hipLaunchKernelGGL(zc::k_select_salient<false>, dim3((unsigned)B), dim3(zc::kSelThreads), 0,
+                       (hipStream_t)stream, scores, (int)L, (int)k, salient_idx, regular_idx, mask);
+  }
   ZC_LAUNCH_CHECK();
   return ZC_OK;
 }
