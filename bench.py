@@ -208,6 +208,75 @@ def cpu_baseline(hp: HotPath, decode_sample: int = 4):
                       f"extrapolated to one whole step of the whole batch"}, sal
 
 
+def decode_sweep(args):
+    """Decode entry point alone at the metric's layer shape, batch 1 -> 64: each size is
+    timed "warm" (the same packed cache every call: it stays in the last-level cache) and
+    "cold" (calls rotate through copies of the cache that together exceed 512 MiB, so no
+    call finds its lines cached).  A least-squares line t = t0 + bytes / BW over the cold
+    points gives the fixed cost of a call and the asymptotic bandwidth."""
+    import dataclasses
+    w0 = WORKLOADS[args.workload]
+    lib = zb.load()
+    dev = torch.device("cuda")
+    rows = []
+    for B in (1, 2, 4, 8, 16, 32, 64):
+        w = dataclasses.replace(w0, B=B)
+        g = torch.Generator(device=dev).manual_seed(w.seed)
+        K = torch.randn(B, w.Hkv, w.L, w.d, device=dev, generator=g).to(w.torch_dtype)
+        V = torch.randn(B, w.Hkv, w.L, w.d, device=dev, generator=g).to(w.torch_dtype)
+        q = torch.randn(B, w.Hq, 1, w.d, device=dev, generator=g).to(w.torch_dtype)
+        scores = torch.rand(B, w.L, device=dev, generator=g)
+        k = w.k_salient
+        sal, reg = zb.zc_select_salient(scores, k)
+        eb = 4 if w.dtype == "fp32" else 2
+        nbytes = (2 * B * w.W * (w.bits_hi * k + w.bits_lo * (w.L - k)) / 8 + 8 * B * w.L
+                  + 2 * B * w.W * 12 + 2 * B * w.Hq * w.d * eb)
+        copies = int(min(max(4, -(-(512 << 20) // int(nbytes))), 192))
+        caches = []
+        for _ in range(copies):
+            mk = lambda scheme, layout: zb.PackedTensor(B, w.Hkv, w.d, lib.zc_arena_slots(k, 1),
+                                                        lib.zc_arena_slots(w.L - k, 1), w.bits_hi, w.bits_lo,
+                                                        scheme, layout, max_chunks=1, device="cuda", store_pos=False)
+            Kp, Vp = mk("channel", zb.ZC_LAYOUT_ROW), mk("cst", zb.ZC_LAYOUT_TGROUP)
+            zb.zc_quantize_pack(K, sal, reg, Kp)
+            zb.zc_quantize_pack(V, sal, reg, Vp)
+            caches.append((Kp, Vp))
+        del K, V
+        out = torch.empty(B, w.Hq, w.d, dtype=w.torch_dtype, device=dev)
+        torch.cuda.synchronize()
+
+        def timed(seq, reps):
+            for Kp, Vp in seq[:2]:
+                zb.zc_decode_attention(q, Kp, Vp, out=out)
+            torch.cuda.synchronize()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                for Kp, Vp in seq:
+                    zb.zc_decode_attention(q, Kp, Vp, out=out)
+            gr.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                gr.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / (reps * len(seq))
+
+        reps = max(2, 400 // copies)
+        cold_us = timed(caches, reps)
+        warm_us = timed([caches[0]] * min(copies, 32), max(2, 400 // min(copies, 32)))
+        rows.append({"batch": B, "bytes_per_call": nbytes, "copies": copies, "cold_us": cold_us, "warm_us": warm_us,
+                     "cold_GBps": nbytes / cold_us * 1e-3, "warm_GBps": nbytes / warm_us * 1e-3,
+                     "cold_frac_of_peak": nbytes / cold_us * 1e-3 / HBM_PEAK_GBPS})
+        del caches
+        torch.cuda.empty_cache()
+    x = np.array([r["bytes_per_call"] for r in rows]); y = np.array([r["cold_us"] for r in rows])
+    slope, t0 = np.polyfit(x, y, 1)
+    print(json.dumps({"sweep": "zc_decode_attention alone, batch 1..64 at the layer shape of " + w0.name,
+                      "fit_cold": {"t0_us": float(t0), "asymptotic_GBps": float(1e-3 / slope)}, "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +288,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain copies of 256 MiB (a kernel of known traffic, "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--decode-sweep", action="store_true",
+                    help="instead of the step: time the decode entry point alone at batch 1..64 of the "
+                         "workload's layer shape, cold and warm caches, and print that table as one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -227,6 +299,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     zb.load()
+    if args.decode_sweep:
+        decode_sweep(args)
+        return
     w = WORKLOADS[args.workload]
     hp = HotPath(w)
 
