@@ -108,6 +108,11 @@ template <int BITS, bool SUBN> __device__ inline float code_comp(int i) {
   else if constexpr (BITS == 4) return (i & 1) ? 1.f : 16.f;
   else return (float)(64 >> (2 * i));
 }
+template <int BITS, bool SUBN> __device__ inline int code_comp_log2(int i) {
+  if constexpr (!SUBN) return BITS == 4 ? 4 : 2;
+  else if constexpr (BITS == 4) return (i & 1) ? 0 : 4;
+  else return 6 - 2 * i;
+}
 // product of a code and x, divided by what the matrix cores accumulate for it
 template <int BITS, bool SUBN> constexpr float code_unscale() {
   return SUBN ? (float)(1 << (24 - (BITS == 4 ? 4 : 6))) : 1.f;
@@ -134,11 +139,15 @@ __device__ inline _Float16 split_part(float x, int part) {
   const _Float16 lo = (_Float16)((x - (float)hi) * kLoScale);
   return part ? lo : hi;
 }
-__device__ inline _Float16 split_part(float x, int part, float& represented) {
+// The same for the query operand, whose residual is NOT scaled: its column then comes out
+// of the matrix cores in the unit of the value column and the two are simply added.
+// A residual below 2^-14 is an fp16 subnormal (absolute step 2^-24), which bounds
+// the error of a logit by 2^-25 per channel and code unit: far below the fp32 sum's own.
+__device__ inline _Float16 split_q(float x, int part, float& represented) {
   const _Float16 hi = (_Float16)x;
   const float hif = (float)hi;
-  const _Float16 lo = (_Float16)((x - hif) * kLoScale);
-  represented = hif + (float)lo * kLoInv;
+  const _Float16 lo = (_Float16)(x - hif);
+  represented = hif + (float)lo;
   return part ? lo : hi;
 }
 
@@ -241,8 +250,6 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   const int g = n >> 1, part = n & 1;
   const bool nvalid = n < 2 * G;
   const int g0 = 2 * grp, g1 = 2 * grp + 1;      // heads of this lane's rows in the output tiles
-  // weights of (own, neighbour) column when a head's value and residual columns are added
-  const float c_own = part ? kLoInv : 1.f, c_oth = part ? 1.f : kLoInv;
   constexpr bool WSPLIT = (DT == ZC_F32);    // softmax weights as value + residual
   constexpr bool SUBN = (DT != ZC_F32);      // codes enter as fp16 subnormals
   // q' always enters as value + residual (two columns per head).  A single fp16 q'
@@ -267,11 +274,13 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // The running maximum of a head is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
   // accumulated so far is then rescaled.  Rare after the first half-blocks.
-  auto update_max = [&](float lmax, float& a1, f4 (*acc)[4], f4& acc1) {
+  auto update_max = [&](float lmax, float (&a1)[4], f4 (*acc)[4], f4& acc1) {
     if (__any(nvalid && lmax > m_run)) {
       const float m_new = fmaxf(m_run, grp_max(lmax));
       const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
-      z_part *= fac; a1 *= fac;
+      z_part *= fac;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) a1[v] *= fac;
       const float f0 = __shfl(fac, 2 * g0), f1 = __shfl(fac, 2 * g1);
       Zrun0 *= f0; Zrun1 *= f1;
 #pragma unroll
@@ -367,7 +376,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
           const float qv = nvalid ? q8[2 * i + half] * a.scale_log2 * cs8[2 * i + half] * comp : 0.f;
           float rep;
           if constexpr (QSPLIT) {
-            hv[half] = split_part(qv, part, rep);
+            hv[half] = split_q(qv, part, rep);
           } else {
             hv[half] = (_Float16)qv;
             rep = (float)hv[half];
@@ -499,7 +508,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         }
         const float own[4] = {s_hi.x + s_lo.x * kLoInv, s_hi.y + s_lo.y * kLoInv, s_hi.z + s_lo.z * kLoInv, s_hi.w + s_lo.w * kLoInv};
 #pragma unroll
-        for (int v = 0; v < 4; ++v) U[j][v] = QSPLIT ? fmaf(xor1(own[v]), c_oth, own[v] * c_own) : own[v];
+        for (int v = 0; v < 4; ++v) U[j][v] = QSPLIT ? own[v] + xor1(own[v]) : own[v];
       }
       float lmax = -INFINITY;
 #pragma unroll
@@ -630,13 +639,21 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz);
     if (hlo >= hhi) return;
     const float kconst = SUBN ? -sumqcz : -(SC * Aq + sumqcz);   // normalized codes: the "1" terms add SC sum(q')
-    const float c_own_s = c_own * UNSCALE, c_oth_s = c_oth * UNSCALE;
     // factor of operand register v of the weights.  When the weights are not split,
     // the second row of a head carries p instead of w = p ts: its product with the
     // constants below is the sum of p (the softmax denominator), at no VALU cost
     float wcomp[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) wcomp[v] = code_comp<BITS, SUBN>(v);
+    // Unsplit weights: that factor (a power of two) is folded into the logit, so exp2
+    // delivers p times the factor; the running maximum is then the maximum of the
+    // shifted logits, which is as good a reference point as the true one.
+    float lshift[4], kshift[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      lshift[v] = WSPLIT ? 0.f : (float)code_comp_log2<BITS, SUBN>(v);
+      kshift[v] = kconst + lshift[v];
+    }
     // B operand that sums the weights: 1 / factor of each operand register
     // (normalized codes: plain ones, the sum then carries SC and is also the "1" term of the output product)
     u4 ones;
@@ -650,7 +667,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     for (int r = 0; r < NR; ++r)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[r][j] = f4{0.f, 0.f, 0.f, 0.f};
-    float a1 = 0.f;                       // sum of w tz
+    float a1[4] = {0.f, 0.f, 0.f, 0.f};   // sum of w tz, one per operand register of the weights
 
     auto half_block = [&](int st, int hb) {
       const int h = hb % NH;
@@ -697,9 +714,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           float x;
-          if constexpr (QSPLIT) x = fmaf(xor1(own[v]), c_oth_s, fmaf(own[v], c_own_s, kconst));
-          else x = fmaf(own[v], UNSCALE, kconst);
-          if constexpr (KTOK) x = kts[v] * fmaf(-ktz[v], Aq, x);
+          const float dot = QSPLIT ? own[v] + xor1(own[v]) : own[v];     // value + residual column
+          if constexpr (KTOK) x = fmaf(kts[v], fmaf(-ktz[v], Aq, fmaf(dot, UNSCALE, kconst)), lshift[v]);
+          else x = fmaf(dot, UNSCALE, kshift[v]);
           lg[jj][v] = x;
         }
       }
@@ -729,10 +746,10 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
           float w = p;
           if constexpr (VTOK) {
             w = p * vts[jj][v];
-            a1 = fmaf(w, vtz[jj][v], a1);
+            a1[v] = fmaf(w, vtz[jj][v], a1[v]);
           }
-          if constexpr (WSPLIT) z_part += p;
-          w2[jj][v] = w * wcomp[v];
+          if constexpr (WSPLIT) { z_part += p; w2[jj][v] = w * wcomp[v]; }
+          else w2[jj][v] = w;
         }
       u4 pA;
       if constexpr (WSPLIT) {
@@ -787,8 +804,11 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     if constexpr (!WSPLIT) { Zrun0 += acc1.y; Zrun1 += acc1.w; }
     float a10 = 0.f, a11 = 0.f;
     if constexpr (VTOK) {
-      a1 = grp_sum(a1);
-      a10 = __shfl(a1, 2 * g0); a11 = __shfl(a1, 2 * g1);
+      float a1s = 0.f;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) a1s = fmaf(a1[v], WSPLIT ? 1.f : 1.f / wcomp[v], a1s);
+      a1s = grp_sum(a1s);
+      a10 = __shfl(a1s, 2 * g0); a11 = __shfl(a1s, 2 * g1);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
