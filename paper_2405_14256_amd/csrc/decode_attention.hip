@@ -377,9 +377,11 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
       return ZC_ERR_INVALID_ARG;
   }
   if (q->B > 65535 || Kp->H > 65535) return ZC_ERR_UNSUPPORTED;
-  // the matrix-core kernel addresses one (batch, KV head) part of an arena with 32-bit offsets
-  if (Kp->cap_hi * (q->D * Kp->bits_hi / 8) >= (int64_t)1 << 32 || Kp->cap_lo * (q->D * Kp->bits_lo / 8) >= (int64_t)1 << 32 ||
-      Kp->cap_hi >= (int64_t)1 << 30 || Kp->cap_lo >= (int64_t)1 << 30)
+  // the matrix-core kernel addresses one (batch, KV head) part of an arena with 32-bit offsets,
+  // and requests "nothing" by pointing every lane at offset 0xFFFFF000, which must lie past the end
+  constexpr int64_t kPartLimit = 0xFFFFF000ll;
+  if (Kp->cap_hi * (q->D * Kp->bits_hi / 8) >= kPartLimit || Kp->cap_lo * (q->D * Kp->bits_lo / 8) >= kPartLimit ||
+      Kp->cap_hi * 4 >= kPartLimit || Kp->cap_lo * 4 >= kPartLimit)
     return ZC_ERR_UNSUPPORTED;
   const size_t need = zc_decode_attention_workspace(q->B, q->H, q->D);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;

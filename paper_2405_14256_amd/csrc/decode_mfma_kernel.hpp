@@ -233,13 +233,13 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // wave's ring holds its partial output for the merge (mO).
   constexpr int kStages = 3;
   constexpr int kCodeBytes = D * 16;
-  constexpr int kStageBytes = 2 * kCodeBytes + 1024;
+  constexpr int kOnesOff = 2 * kCodeBytes + 1024;     // 256 bytes of 1.0f: what the sum-of-p rows read as "token scale"
+  constexpr int kStageBytes = kOnesOff + 256;
   constexpr int kRingBytes = kStages * kStageBytes;
   static_assert(kRingBytes >= MG * D * 4, "a wave's ring must hold its partial output");
   __shared__ __align__(16) uint8_t ring[4][kRingBytes];
   auto mO = [&](int w, int gg, int c) -> float& { return reinterpret_cast<float*>(&ring[w][0])[gg * D + c]; };
   __shared__ float mM[4][MG], mZ[4][MG];
-  __shared__ __align__(16) float lds_ones[4];   // what the sum-of-p rows read in place of the V token scales
   __shared__ float ptile[4][MG][kTailUnit];
 
   const int s = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
@@ -260,7 +260,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // running state of this wave; unused columns sit at +inf so that their weights are 0
   float m_run = nvalid ? -INFINITY : INFINITY, z_part = 0.f;
   float Zrun0 = 0.f, Zrun1 = 0.f;            // unsplit weights: sum of p of heads g0, g1 (from the matrix cores)
-  if (tid < 4) lds_ones[tid] = 1.f;          // (published by the barriers of the first operand build)
+#pragma unroll
+  for (int st = 0; st < kStages; ++st)       // each wave fills (and later reads) its own ring
+    reinterpret_cast<float*>(&ring[wave][st * kStageBytes + kOnesOff])[lane] = 1.f;
   float O[NR][4][2];
 #pragma unroll
   for (int r = 0; r < NR; ++r)
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // half-block exceeds it (a ballot, no data movement otherwise); everything
   // accumulated so far is then rescaled.  Rare after the first half-blocks.
   auto update_max = [&](float lmax, float (&a1)[4], f4 (*acc)[4], f4& acc1) {
-    if (__any(nvalid && lmax > m_run)) {
+    if (__builtin_amdgcn_ballot_w64(lmax > m_run)) {     // (unused columns sit at +inf)
       const float m_new = fmaxf(m_run, grp_max(lmax));
       const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
       z_part *= fac;
@@ -612,27 +614,29 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&ring[wave][0];
     const uint8_t* ring_gen = &ring[wave][0];
     const int bl_lo = hlo / NH, bl_hi = hlo < hhi ? (hhi - 1) / NH + 1 : hlo / NH;    // this wave's blocks
-    auto issue = [&](int st, int bi) {
-      const uint32_t dst = ring_lds + st * kStageBytes;
+    // (live == false: the same number of transfers, all out of range -- they move
+    // zeros and touch no memory -- so that the wait counts below are constants)
+    auto issue = [&](uint32_t dst, int bi, bool live) {
       const int ko = (int)((uint32_t)(begin + bi * TB) * (uint32_t)ROWB);          // = block index * D * 16
       const int to = (int)((uint32_t)(begin + bi * TB) * 4u);
-      dma16<0>(dst, rs_k, 16 * lane, ko);
-      if constexpr (KCH == 2) dma16<1024>(dst, rs_k, 16 * lane, ko);
-      dma16<0>(dst + kCodeBytes, rs_v, 16 * lane, ko);
-      if constexpr (KCH == 2) dma16<1024>(dst + kCodeBytes, rs_v, 16 * lane, ko);
+      const int oob = live ? 0 : (int)0xFFFFF000u;     // per-lane offsets beyond any buffer the host admits
+      const int v16 = (16 * lane) | oob, v4 = (4 * lane) | oob;
+      dma16<0>(dst, rs_k, v16, ko);
+      if constexpr (KCH == 2) dma16<1024>(dst, rs_k, v16, ko);
+      dma16<0>(dst + kCodeBytes, rs_v, v16, ko);
+      if constexpr (KCH == 2) dma16<1024>(dst + kCodeBytes, rs_v, v16, ko);
       if constexpr (VTOK) {
-        dma4(dst + 2 * kCodeBytes, rs_vts, 4 * lane, to);
-        dma4(dst + 2 * kCodeBytes + 256, rs_vtz, 4 * lane, to);
+        dma4(dst + 2 * kCodeBytes, rs_vts, v4, to);
+        dma4(dst + 2 * kCodeBytes + 256, rs_vtz, v4, to);
       }
       if constexpr (KTOK) {
-        dma4(dst + 2 * kCodeBytes + 512, rs_kts, 4 * lane, to);
-        dma4(dst + 2 * kCodeBytes + 768, rs_ktz, 4 * lane, to);
+        dma4(dst + 2 * kCodeBytes + 512, rs_kts, v4, to);
+        dma4(dst + 2 * kCodeBytes + 768, rs_ktz, v4, to);
       }
     };
     // the first blocks are in flight while the operand is built
-#pragma unroll
-    for (int i = 0; i < kStages - 1; ++i)
-      if (bl_lo + i < bl_hi) issue(i, bl_lo + i);
+    issue(ring_lds, bl_lo, bl_lo < bl_hi);
+    issue(ring_lds + kStageBytes, bl_lo + 1, bl_lo + 1 < bl_hi);
 
     u4 qB[KS];
     float Aq, sumqcz;
@@ -669,28 +673,32 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       for (int j = 0; j < 4; ++j) acc[r][j] = f4{0.f, 0.f, 0.f, 0.f};
     float a1[4] = {0.f, 0.f, 0.f, 0.f};   // sum of w tz, one per operand register of the weights
 
-    auto half_block = [&](int st, int hb) {
-      const int h = hb % NH;
+    // this lane's addresses in the current stage (they move with the ring, once per
+    // block); the half-block adds constants
+    const uint8_t* kbase = ring_gen + n * ROWB + grp * (KW * 4);
+    const uint8_t* vbase = ring_gen + kCodeBytes + grp * (D * 4) + 16 * n;
+    const uint8_t* tbase = ring_gen + 2 * kCodeBytes + 16 * grp;
+    const uint8_t* tsbase = (!WSPLIT && part) ? ring_gen + kOnesOff : tbase;
+    auto half_block = [&](auto h_c, int hb) {
+      constexpr int SB = 0;
+      constexpr int h = decltype(h_c)::value;
       // operands of this half-block from the staging buffer
-      const uint8_t* sb = ring_gen + st * kStageBytes;
       struct { uint32_t kw[2][KW]; u4 vw[NR]; u4 kts[2], ktz[2], vts[2], vtz[2]; } bf;
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const int row = 16 * (2 * h + jj) + n;
-        const uint8_t* kp = sb + row * ROWB + grp * (KW * 4);
+        const uint8_t* kp = kbase + SB + 16 * (2 * h + jj) * ROWB;
         if constexpr (KW == 4) { const u4 t = *reinterpret_cast<const u4*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; bf.kw[jj][2] = t.z; bf.kw[jj][3] = t.w; }
         else if constexpr (KW == 2) { const uint2 t = *reinterpret_cast<const uint2*>(kp); bf.kw[jj][0] = t.x; bf.kw[jj][1] = t.y; }
         else { bf.kw[jj][0] = *reinterpret_cast<const uint32_t*>(kp); }
-        const uint8_t* tp = sb + 2 * kCodeBytes + (16 * (2 * h + jj) + 4 * grp) * 4;
+        const uint8_t* tp = tbase + SB + 64 * (2 * h + jj);
         if constexpr (VTOK) {
-          const uint8_t* tps = (!WSPLIT && part) ? reinterpret_cast<const uint8_t*>(lds_ones) : tp;
-          bf.vts[jj] = *reinterpret_cast<const u4*>(tps);
+          bf.vts[jj] = *reinterpret_cast<const u4*>(tsbase + SB + 64 * (2 * h + jj));
           bf.vtz[jj] = *reinterpret_cast<const u4*>(tp + 256);
         }
         if constexpr (KTOK) { bf.kts[jj] = *reinterpret_cast<const u4*>(tp + 512); bf.ktz[jj] = *reinterpret_cast<const u4*>(tp + 768); }
       }
 #pragma unroll
-      for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const u4*>(sb + kCodeBytes + grp * (D * 4) + 16 * (n + 16 * r));
+      for (int r = 0; r < NR; ++r) bf.vw[r] = *reinterpret_cast<const u4*>(vbase + SB + 256 * r);
       const int ntok = len - 32 * hb;                  // slots of this half-block inside the segment, >= 1
       const bool masked = ntok < 32;                   // only the last half-block of a segment
       float lg[2][4], vts[2][4], vtz[2][4];
@@ -773,25 +781,29 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       }
     };
 
-    // Blocks in turn through the ring: the block kStages - 1 ahead is requested, then
-    // the wave waits for all but the loads issued after the current block's.
+    // Blocks in turn through the ring: the block kStages - 1 ahead is requested (out of
+    // range past the wave's last block), then the wave waits for all but the two blocks'
+    // loads issued after the current one's.
+    int st = 0, st_ahead = kStages - 1;
+    uint32_t dst_ahead = ring_lds + (kStages - 1) * kStageBytes;
     for (int bi = bl_lo; bi < bl_hi; ++bi) {
-      const int st = (bi - bl_lo) % kStages;
-      const int ahead = bi + kStages - 1;
-      if (ahead < bl_hi) {
-        dma_reuse_fence();                       // last iteration's reads of that buffer are complete
-        issue((st + kStages - 1) % kStages, ahead);
+      dma_reuse_fence();                         // the reads of the buffer about to be refilled are complete
+      issue(dst_ahead, bi + kStages - 1, bi + kStages - 1 < bl_hi);
+      wait_vmem<2 * L_STAGE>();
+      if constexpr (NH == 1) {
+        half_block(std::integral_constant<int, 0>{}, bi);
+      } else {
+        const unsigned span = (unsigned)(hhi - hlo);
+        if ((unsigned)(bi * NH - hlo) < span) half_block(std::integral_constant<int, 0>{}, bi * NH);
+        if ((unsigned)(bi * NH + 1 - hlo) < span) half_block(std::integral_constant<int, 1>{}, bi * NH + 1);
       }
-      const int later = min(kStages - 1, bl_hi - 1 - bi);     // blocks requested after this one
-      if (later >= 2) wait_vmem<2 * L_STAGE>();
-      else if (later == 1) wait_vmem<L_STAGE>();
-      else wait_vmem<0>();
-#pragma unroll
-      for (int h = 0; h < NH; ++h) {
-        const int hb = bi * NH + h;
-        if (hb >= hlo && hb < hhi) half_block(st, hb);
-      }
+      const int step = (st == kStages - 1) ? -(kStages - 1) * kStageBytes : kStageBytes;
+      kbase += step; vbase += step; tbase += step; tsbase += step;
+      st = (st == kStages - 1) ? 0 : st + 1;
+      dst_ahead = (st_ahead == kStages - 1) ? ring_lds : dst_ahead + kStageBytes;
+      st_ahead = (st_ahead == kStages - 1) ? 0 : st_ahead + 1;
     }
+    wait_vmem<0>();                              // the out-of-range requests have landed too
     dma_reuse_fence();                           // the ring is reused (next segment, merge)
     // ---- fold the segment into O ----
     //   subnormal codes:   sum_t w code = acc 2^(24 - P),  sum_t w = acc1
