@@ -139,16 +139,13 @@ __device__ inline _Float16 split_part(float x, int part) {
   const _Float16 lo = (_Float16)((x - (float)hi) * kLoScale);
   return part ? lo : hi;
 }
-// The same for the query operand, whose residual is NOT scaled: its column then comes out
-// of the matrix cores in the unit of the value column and the two are simply added.
-// A residual below 2^-14 is an fp16 subnormal (absolute step 2^-24), which bounds
-// the error of a logit by 2^-25 per channel and code unit: far below the fp32 sum's own.
-__device__ inline _Float16 split_q(float x, int part, float& represented) {
-  const _Float16 hi = (_Float16)x;
-  const float hif = (float)hi;
-  const _Float16 lo = (_Float16)(x - hif);
-  represented = hif + (float)lo;
-  return part ? lo : hi;
+__device__ inline float half_lo_to_float(uint32_t w) {
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  return (float)__builtin_bit_cast(h2, w).x;
+}
+__device__ inline float half_hi_to_float(uint32_t w) {
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  return (float)__builtin_bit_cast(h2, w).y;
 }
 
 __device__ inline float xor1(float x) {   // value of the neighbouring lane (lane ^ 1)
@@ -224,9 +221,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   constexpr int KS = D / 32;     // k-steps of the logit product
   constexpr int NR = D / 64;     // 16-byte V loads per lane and block
   constexpr int MG = ZC_MAX_GROUP;
-  __shared__ u4 sqB[KS][64];              // query operand of the current segment
-  __shared__ float ssum[2][KS][64];
-  __shared__ float svc[2][D];             // channel scale and zero of V for the current segment
+  __shared__ __align__(16) float svc[4][2][D];   // per wave: channel scale and zero of V for its current segment
   // Per wave a ring of kStages staging buffers for one block of the packed cache
   // each: K codes (D * 16 bytes), V codes (D * 16 bytes), then 256 bytes each of
   // V token scale, V token zero, K token scale, K token zero.  After its last block a
@@ -271,7 +266,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 
   // this workgroup's share of the cost line (half-blocks + kSegCost per segment start)
   const int sp = max(a.S_packed, 1);
-  const int u0 = (int)((int64_t)a.n_units * s / sp), u1 = (int)((int64_t)a.n_units * (s + 1) / sp);
+  const int g_u0 = (int)((int64_t)a.n_units * s / sp), g_u1 = (int)((int64_t)a.n_units * (s + 1) / sp);
+  // ... of which every wave takes a contiguous quarter
+  const int u0 = g_u0 + (g_u1 - g_u0) * wave / 4, u1 = g_u0 + (g_u1 - g_u0) * (wave + 1) / 4;
 
   // The running maximum of a head is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
@@ -297,47 +294,41 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     }
   };
 
-  // The query operand of a segment, built once per workgroup: wave w computes
-  // k-step w.  MODE 4 / 2: codes of that width, q' = q cs sm_scale log2(e) times
-  // the factor of its operand register, in the channel order the unpacked K words
-  // have; MODE 0: the tail, q itself in natural order.
+  // The query operand of a segment.  Every wave builds its own (all k-steps): the
+  // waves of a workgroup then share nothing until the final merge, so each can
+  // work through its own run of segments without a barrier.
+  // MODE 4 / 2: codes of that width, q' = q cs sm_scale log2(e) times the factor of
+  // its operand register, in the channel order the unpacked K words have; MODE 0:
+  // the tail, q itself in natural order.
   // Returns the operand registers and sum(q'), sum(q' cz) over all channels.
   auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, const float* vcs, const float* vcz,
                                  u4 (&qB)[KS], float& sumqq, float& sumqqcz) {
     constexpr int MODE = decltype(mode_c)::value;
-    // q and the channel parameters of this lane's k-step, straight from global
-    // memory (issued together with the first block's loads by the caller)
-    float q8[8], cs8[8], cz8[8];
-    const int ks0 = wave;
+    // q and the channel parameters of this lane's elements of every k-step, straight
+    // from global memory (issued together with the first blocks' loads by the caller)
+    float q8[KS][8], cs8[KS][8], cz8[KS][8];
+    const int64_t qoff = (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { q8[i] = 0.f; cs8[i] = 1.f; cz8[i] = 0.f; }
-    if (ks0 < KS) {
-      const int64_t qoff = (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH;
+    for (int ks0 = 0; ks0 < KS; ++ks0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { cs8[ks0][i] = 1.f; cz8[ks0][i] = 0.f; }
       if constexpr (MODE == 2) {
         // slots (i, half) are channels base + 4 (ks0 & 1) + i + 8 half of a 16-channel word
-        const int base = grp * (D / 4) + 16 * (ks0 >> 1);
+        const int base = grp * (D / 4) + 16 * (ks0 >> 1) + 4 * (ks0 & 1);
         float qa[8], qb[8];
-        load8<DT>(a.q, qoff + base, qa);
-        load8<DT>(a.q, qoff + base + 8, qb);
-        const float4 ca = *reinterpret_cast<const float4*>(kcs + base + 4 * (ks0 & 1));
-        const float4 cb = *reinterpret_cast<const float4*>(kcs + base + 8 + 4 * (ks0 & 1));
-        const float4 za = *reinterpret_cast<const float4*>(kcz + base + 4 * (ks0 & 1));
-        const float4 zb = *reinterpret_cast<const float4*>(kcz + base + 8 + 4 * (ks0 & 1));
+        load8<DT>(a.q, qoff + base - 4 * (ks0 & 1), qa);
+        load8<DT>(a.q, qoff + base - 4 * (ks0 & 1) + 8, qb);
+        const float4 ca = *reinterpret_cast<const float4*>(kcs + base);
+        const float4 cb = *reinterpret_cast<const float4*>(kcs + base + 8);
+        const float4 za = *reinterpret_cast<const float4*>(kcz + base);
+        const float4 zb = *reinterpret_cast<const float4*>(kcz + base + 8);
         const float csa[4] = {ca.x, ca.y, ca.z, ca.w}, csb[4] = {cb.x, cb.y, cb.z, cb.w};
         const float cza[4] = {za.x, za.y, za.z, za.w}, czb[4] = {zb.x, zb.y, zb.z, zb.w};
-        // (a wave-uniform branch with constant indices: a select between array
-        // elements would put the arrays in scratch memory)
-        if (ks0 & 1) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) { q8[2 * i] = qa[4 + i]; q8[2 * i + 1] = qb[4 + i]; }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) { q8[2 * i] = qa[i]; q8[2 * i + 1] = qb[i]; }
-        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          cs8[2 * i] = csa[i]; cs8[2 * i + 1] = csb[i];
-          cz8[2 * i] = cza[i]; cz8[2 * i + 1] = czb[i];
+          q8[ks0][2 * i] = qa[4 * (ks0 & 1) + i]; q8[ks0][2 * i + 1] = qb[4 * (ks0 & 1) + i];
+          cs8[ks0][2 * i] = csa[i]; cs8[ks0][2 * i + 1] = csb[i];
+          cz8[ks0][2 * i] = cza[i]; cz8[ks0][2 * i + 1] = czb[i];
         }
       } else {
         // MODE 4: slots (i, half) are channels base + i + 4 half; MODE 0: base + 2 i + half
@@ -356,53 +347,60 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
             const int e = (MODE == 4) ? i + 4 * half : 2 * i + half;
-            q8[2 * i + half] = qa[e]; cs8[2 * i + half] = ca[e]; cz8[2 * i + half] = za[e];
+            q8[ks0][2 * i + half] = qa[e]; cs8[ks0][2 * i + half] = ca[e]; cz8[ks0][2 * i + half] = za[e];
           }
       }
     }
-    // the V channel parameters wait in LDS until the segment is folded
-    float vparam = 0.f;
-    if (MODE != 0 && tid < 2 * D) vparam = (tid < D) ? vcs[tid] : vcz[tid - D];
-    __syncthreads();     // sqB / ssum / svc of the previous segment are no longer read
-    if (MODE != 0 && tid < 2 * D) svc[tid / D][tid % D] = vparam;
-    if (ks0 < KS) {
+    // the V channel parameters wait in this wave's part of LDS until the segment is folded
+    if constexpr (MODE != 0) {
+      if (lane < D / 2) {
+        const bool zero_half = lane >= D / 4;
+        const int c4 = 4 * (zero_half ? lane - D / 4 : lane);
+        const float4 t = *reinterpret_cast<const float4*>((zero_half ? vcz : vcs) + c4);
+        *reinterpret_cast<float4*>(&svc[wave][zero_half ? 1 : 0][c4]) = t;
+      }
+    }
+    // Value and residual columns: the residual of the query operand is NOT scaled, so its
+    // column comes out of the matrix cores in the unit of the value column and the two are
+    // simply added.  A residual below 2^-14 is an fp16 subnormal (absolute step 2^-24),
+    // which bounds the error of a logit by 2^-25 per channel and code unit.
+    // Unused columns get q' = 0.  For 16-bit tensors the sums take q' itself rather than
+    // the value the two fp16 columns represent (they differ by 2^-22 relative: nothing
+    // next to the rounding of a 16-bit output); fp32 tensors take the represented value.
+    const float lane_scale = nvalid ? a.scale_log2 : 0.f;
+    float sq = 0.f, sqz = 0.f;
+#pragma unroll
+    for (int ks0 = 0; ks0 < KS; ++ks0) {
       uint32_t regs[4];
-      float sq = 0.f, sqz = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        _Float16 hv[2];
         const float comp = (MODE == 0) ? 1.f : code_comp<MODE == 0 ? 4 : MODE, SUBN>(i);
-        const float inv_comp = 1.f / comp;      // powers of two
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const float qv = nvalid ? q8[2 * i + half] * a.scale_log2 * cs8[2 * i + half] * comp : 0.f;
-          float rep;
-          if constexpr (QSPLIT) {
-            hv[half] = split_q(qv, part, rep);
+        const float qn0 = q8[ks0][2 * i] * lane_scale * cs8[ks0][2 * i], qn1 = q8[ks0][2 * i + 1] * lane_scale * cs8[ks0][2 * i + 1];
+        const float qv0 = qn0 * comp, qv1 = qn1 * comp;
+        if constexpr (QSPLIT) {
+          const uint32_t hi2 = pack_f2(qv0, qv1);                       // both values rounded to fp16
+          const float h0 = half_lo_to_float(hi2), h1 = half_hi_to_float(hi2);
+          const uint32_t lo2 = pack_f2(qv0 - h0, qv1 - h1);             // the residuals (exact differences), rounded
+          regs[i] = part ? lo2 : hi2;
+          if constexpr (SUBN) {
+            sq += qn0 + qn1;
+            sqz = fmaf(qn0, cz8[ks0][2 * i], fmaf(qn1, cz8[ks0][2 * i + 1], sqz));
           } else {
-            hv[half] = (_Float16)qv;
-            rep = (float)hv[half];
+            const float inv_comp = 1.f / comp;      // a power of two
+            const float r0 = (h0 + half_lo_to_float(lo2)) * inv_comp, r1 = (h1 + half_hi_to_float(lo2)) * inv_comp;
+            sq += r0 + r1;
+            sqz = fmaf(r0, cz8[ks0][2 * i], fmaf(r1, cz8[ks0][2 * i + 1], sqz));
           }
-          sq = fmaf(rep, inv_comp, sq);
-          sqz = fmaf(rep * inv_comp, cz8[2 * i + half], sqz);
+        } else {
+          regs[i] = pack_f2(qv0, qv1);
+          sq += qn0 + qn1;
+          sqz = fmaf(qn0, cz8[ks0][2 * i], fmaf(qn1, cz8[ks0][2 * i + 1], sqz));
         }
-        regs[i] = pack_h2(hv[0], hv[1]);
       }
-      u4 t; t.x = regs[0]; t.y = regs[1]; t.z = regs[2]; t.w = regs[3];
-      sqB[ks0][lane] = t;
-      ssum[0][ks0][lane] = sq;
-      ssum[1][ks0][lane] = sqz;
+      qB[ks0].x = regs[0]; qB[ks0].y = regs[1]; qB[ks0].z = regs[2]; qB[ks0].w = regs[3];
     }
-    __syncthreads();
-    sumqq = 0.f; sumqqcz = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      qB[ks] = sqB[ks][lane];
-      sumqq += ssum[0][ks][lane];
-      sumqqcz += ssum[1][ks][lane];
-    }
-    sumqq = grp_sum(sumqq);
-    sumqqcz = grp_sum(sumqqcz);
+    sumqq = grp_sum(sq);
+    sumqqcz = grp_sum(sqz);
   };
 
   // Combines the (m, Z, o) the four waves left in LDS and writes the workgroup's
@@ -588,8 +586,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     constexpr float UNSCALE = code_unscale<BITS, SUBN>();
     constexpr float SC = (BITS == 4) ? 16.f : 4.f;     // normalized encoding: 1 + code / SC
     const int64_t chan_off = ((int64_t)(ci * 2 + sub) * a.B + b) * (a.Hkv * D) + hk * D;
-    // lo, hi: this workgroup's range of the segment in half-blocks; split over the waves
-    const int hlo = lo + (hi - lo) * wave / 4, hhi = lo + (hi - lo) * (wave + 1) / 4;
+    // lo, hi: this wave's range of the segment in half-blocks (not empty)
+    const int hlo = lo, hhi = hi;
 
     // Buffer resources over this (batch, KV head)'s part of each array: the
     // per-lane offset is fixed, the half-block adds a scalar offset, reads past
@@ -641,7 +639,6 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     u4 qB[KS];
     float Aq, sumqcz;
     build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz);
-    if (hlo >= hhi) return;
     const float kconst = SUBN ? -sumqcz : -(SC * Aq + sumqcz);   // normalized codes: the "1" terms add SC sum(q')
     // factor of operand register v of the weights.  When the weights are not split,
     // the second row of a head carries p instead of w = p ts: its product with the
@@ -824,8 +821,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-      const float4 vcs4 = *reinterpret_cast<const float4*>(&svc[0][4 * (n + 16 * r)]);
-      const float4 vcz4 = *reinterpret_cast<const float4*>(&svc[1][4 * (n + 16 * r)]);
+      const float4 vcs4 = *reinterpret_cast<const float4*>(&svc[wave][0][4 * (n + 16 * r)]);
+      const float4 vcz4 = *reinterpret_cast<const float4*>(&svc[wave][1][4 * (n + 16 * r)]);
       const float cs[4] = {vcs4.x, vcs4.y, vcs4.z, vcs4.w}, cz[4] = {vcz4.x, vcz4.y, vcz4.z, vcz4.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
