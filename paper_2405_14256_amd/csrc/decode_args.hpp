@@ -7,7 +7,7 @@ namespace zc {
 
 constexpr int kTailUnit = 16;    // tail tokens per work unit of the MFMA decode kernel (a multiple of 16)
 constexpr int kMaxSplits = 128;
-constexpr int kTailSplits = 8;    // most workgroups per (batch, KV head) that share the tail
+constexpr int kTailSplits = 8;    // 4 * kTailSplits: most waves per (batch, KV head) that share the tail
 constexpr int kSegCost = 3;        // cost, in blocks, charged for starting a segment (query operand)
 constexpr int kInlineChunks = 12;  // chunk-table rows that travel in the kernel arguments
 
@@ -39,7 +39,8 @@ struct DecArgs {
   int tail_len;
   float scale_log2;
   int S, n_units;  // workgroups per (batch, KV head); length of the packed cache's cost line
-  int S_packed;    // the first S_packed workgroups split the packed cache, the others the tail
+  int n_pw, n_tw;  // waves per (batch, KV head) that share the packed cache / the tail; n_pw + n_tw = 4 S
+  int tw_full, tw_rem;   // n_tw = tw_full * S + tw_rem: tail waves per workgroup, and workgroups with one more
   int n_cu;        // compute units of the device
   float* part_m;   // [B, Hq, S]
   float* part_z;   // [B, Hq, S]

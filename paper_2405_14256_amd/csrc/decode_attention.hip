@@ -439,7 +439,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     a.n_cu = ncu;
   }
   int S = split_cap(q->B, q->H);
-  a.S_packed = 0;
+  a.n_pw = 0; a.n_tw = 0; a.tw_full = 0; a.tw_rem = 0;
   if (mfma_path) {
     const int64_t heads = q->B * Kp->H;
     const int64_t tail_units = ceil_div64(tail_len, kTailUnit);
@@ -460,14 +460,34 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
       }
       S = (int)best;
     }
-    // Tail: one unit (a wave's work) per workgroup while the launch stays below one
-    // workgroup per CU, else eight units per workgroup.
-    int64_t TW = (heads * (S + tail_units) <= a.n_cu) ? tail_units : ceil_div64(tail_units, 8);
-    if (TW > kTailSplits) TW = kTailSplits;
-    if (S > 32 - TW) S = 32 - (int)TW;
-    if (S + TW == 0) S = 1;          // empty cache: one workgroup writes the zeros
-    a.S_packed = S;
-    S += (int)TW;
+    // Tail: waves of its own.  One unit (16 tokens) per wave while the launch stays
+    // below one workgroup per CU; else a share of the waves in proportion to its cost
+    // (about two half-blocks' worth per unit, plus a start).
+    int64_t n_tw = 0;
+    bool extra_waves = false;
+    if (tail_units > 0) {
+      if (units == 0 || heads * (S + ceil_div64(tail_units, 4)) <= a.n_cu) {
+        n_tw = tail_units;
+        extra_waves = true;
+      } else {
+        const int64_t tail_cost = 2 * tail_units + kSegCost;
+        n_tw = (4 * S * tail_cost + (units + tail_cost) / 2) / (units + tail_cost);
+        if (n_tw < 1) n_tw = 1;
+        if (n_tw > 4 * S - 1) n_tw = 4 * S - 1;
+      }
+      if (n_tw > tail_units) n_tw = tail_units;
+      if (n_tw > 4 * kTailSplits) n_tw = 4 * kTailSplits;
+    }
+    if (units == 0) S = 0;
+    int64_t WG = extra_waves ? ceil_div64(4 * (int64_t)S + n_tw, 4) : S;
+    if (WG > 32) WG = 32;
+    if (WG < 1) WG = 1;              // empty cache: one workgroup writes the zeros
+    if (units == 0) n_tw = 4 * WG;   // every wave is a tail wave (those past the last unit idle)
+    a.n_tw = (int)n_tw;
+    a.n_pw = (int)(4 * WG - n_tw);
+    a.tw_full = (int)(n_tw / WG);
+    a.tw_rem = (int)(n_tw % WG);
+    S = (int)WG;
   } else if (S > units) {
     S = (int)(units > 0 ? units : 1);
   }

@@ -264,11 +264,18 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) { O[r][j][0] = 0.f; O[r][j][1] = 0.f; }
 
-  // this workgroup's share of the cost line (half-blocks + kSegCost per segment start)
-  const int sp = max(a.S_packed, 1);
-  const int g_u0 = (int)((int64_t)a.n_units * s / sp), g_u1 = (int)((int64_t)a.n_units * (s + 1) / sp);
-  // ... of which every wave takes a contiguous quarter
-  const int u0 = g_u0 + (g_u1 - g_u0) * wave / 4, u1 = g_u0 + (g_u1 - g_u0) * (wave + 1) / 4;
+  // The waves of the workgroups of one (batch, KV head) are workers of their own:
+  // n_tw of them take the full-precision tail, the other n_pw share the cost line of
+  // the packed cache (half-blocks + kSegCost per segment start, a contiguous run each).
+  // The tail waves are spread over the workgroups -- the last wave of the last
+  // workgroups first -- because the tail's loads are many small rows, and one CU
+  // has only so many misses in flight.
+  const int my_tails = a.tw_full + (s >= a.S - a.tw_rem ? 1 : 0);
+  const bool tail_wave = wave >= 4 - my_tails;
+  const int pw = 4 * s - a.tw_full * s - max(0, s - (a.S - a.tw_rem)) + wave;    // index among the packed waves
+  const int npw = max(a.n_pw, 1);
+  const int u0 = tail_wave ? 0 : (int)((int64_t)a.n_units * pw / npw);
+  const int u1 = tail_wave ? 0 : (int)((int64_t)a.n_units * (pw + 1) / npw);
 
   // The running maximum of a head is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
@@ -430,17 +437,16 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     }
   };
 
-  // ---------------- full-precision tail: workgroups of its own ----------------------------
-  // One wave per unit of kTailUnit tokens (one 16-row MFMA tile).  All K and V rows of the unit are
+  // ---------------- full-precision tail: waves of its own ---------------------------------
+  // Units of kTailUnit tokens (one 16-row MFMA tile).  All K and V rows of a unit are
   // requested before the query operand is built, so the unit costs one trip to
   // memory.  Logits on the matrix cores (K rows as the A operand); the weighted
   // sum of V on the vector ALUs, lane = (token mod TPI, 8 channels).
-  if (s >= a.S_packed && a.tail_len > 0) {
+  if (tail_wave) {
     constexpr int LPT = D / 8, TPI = 64 / LPT, NI = kTailUnit / TPI, NJ = kTailUnit / 16;
-    const int tw = s - a.S_packed, n_tw = a.S - a.S_packed;
+    const int tw = (3 - wave) * a.S + (a.S - 1 - s), n_tw = max(a.n_tw, 1);     // index among the tail waves
     const int n_tail = ceil_div(a.tail_len, kTailUnit);
-    const int tlo = (int)((int64_t)n_tail * tw / n_tw), thi = (int)((int64_t)n_tail * (tw + 1) / n_tw);
-    const int wlo = tlo + (thi - tlo) * wave / 4, whi = tlo + (thi - tlo) * (wave + 1) / 4;
+    const int wlo = (int)((int64_t)n_tail * tw / n_tw), whi = (int)((int64_t)n_tail * (tw + 1) / n_tw);
     const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
     const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
     const int vtok = lane / LPT, vch = 8 * (lane % LPT);
@@ -460,8 +466,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       for (int i = 0; i < NI; ++i)
         bf.v[i] = raw_load8<DT>(a.tail_v, vb + (int64_t)(t0 + i * TPI + vtok) * a.tv_sL + vch, i * TPI + vtok < ntok);
     };
-    TBuf bf;
-    if (wlo < whi) load_unit(wlo, bf);
+    // 16-bit tensors: two units are in flight, so a wave with at most two units pays one
+    // trip to memory (fp32 rows take twice the registers: one unit at a time)
+    constexpr bool kTwoUnits = (DT != ZC_F32);
+    TBuf bf0, bf1;
+    if (wlo < whi) load_unit(wlo, bf0);
+    if (kTwoUnits && wlo + 1 < whi) load_unit(wlo + 1, bf1);
     u4 qB[KS];
     float dummy0, dummy1;
     build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, nullptr, nullptr, qB, dummy0, dummy1);
@@ -471,8 +481,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) Ot[gg][i] = 0.f;
 
-    for (int tu = wlo; tu < whi; ++tu) {
-      if (tu > wlo) load_unit(tu, bf);
+    auto tail_unit = [&](int tu, const TBuf& bf) {
       const int ntok = min(kTailUnit, a.tail_len - tu * kTailUnit);
       float U[NJ][4];
 #pragma unroll
@@ -555,6 +564,21 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
           }
         }
       }
+    };
+    if constexpr (kTwoUnits) {
+      for (int tu = wlo; tu < whi; tu += 2) {
+        tail_unit(tu, bf0);
+        if (tu + 2 < whi) load_unit(tu + 2, bf0);
+        if (tu + 1 < whi) {
+          tail_unit(tu + 1, bf1);
+          if (tu + 3 < whi) load_unit(tu + 3, bf1);
+        }
+      }
+    } else {
+      for (int tu = wlo; tu < whi; ++tu) {
+        if (tu > wlo) load_unit(tu, bf0);
+        tail_unit(tu, bf0);
+      }
     }
     // merge: sum the token sub-rows, then the four waves through LDS
     const float z_tot = grp_sum(z_part);
@@ -571,9 +595,6 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         }
       }
     }
-    __syncthreads();
-    write_result();
-    return;
   }
 
   int cursor = 0;
@@ -834,53 +855,55 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     }
   };
 
-  for (int ci = 0; ci < a.n_chunks; ++ci) {
-    for (int sub = 0; sub < 2; ++sub) {
-      // The row of the chunk table: from the kernel arguments (a scalar load) when the
-      // table travels there, else from memory.  The empty asm statements pin each
-      // source's values in scalar registers, so that the two loads are not merged
-      // into one load through a selected (then generic) pointer.
-      int begin, len;
-      if (a.chunks_inline) {
-        begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1];
-        asm volatile("" : "+s"(begin), "+s"(len));
-      } else {
-        begin = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub]);
-        len = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub + 1]);
-        asm volatile("" : "+s"(begin), "+s"(len));
+  if (!tail_wave) {
+    for (int ci = 0; ci < a.n_chunks; ++ci) {
+      for (int sub = 0; sub < 2; ++sub) {
+        // The row of the chunk table: from the kernel arguments (a scalar load) when the
+        // table travels there, else from memory.  The empty asm statements pin each
+        // source's values in scalar registers, so that the two loads are not merged
+        // into one load through a selected (then generic) pointer.
+        int begin, len;
+        if (a.chunks_inline) {
+          begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1];
+          asm volatile("" : "+s"(begin), "+s"(len));
+        } else {
+          begin = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub]);
+          len = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub + 1]);
+          asm volatile("" : "+s"(begin), "+s"(len));
+        }
+        const int bits = a.bits[sub];
+        const int TB = 4 * (32 / bits);
+        const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
+        if (nb == 0) continue;
+        const int seg0 = cursor + kSegCost;        // the segment's half-blocks sit after its start-up slots
+        cursor = seg0 + nb;
+        const int lo = max(u0 - seg0, 0), hi = min(u1 - seg0, nb);
+        if (lo >= hi) continue;
+        if (bits == 4) segment(std::integral_constant<int, 4>{}, ci, sub, begin, len, lo, hi);
+        else segment(std::integral_constant<int, 2>{}, ci, sub, begin, len, lo, hi);
       }
-      const int bits = a.bits[sub];
-      const int TB = 4 * (32 / bits);
-      const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
-      if (nb == 0) continue;
-      const int seg0 = cursor + kSegCost;        // the segment's half-blocks sit after its start-up slots
-      cursor = seg0 + nb;
-      const int lo = max(u0 - seg0, 0), hi = min(u1 - seg0, nb);
-      if (lo >= hi) continue;
-      if (bits == 4) segment(std::integral_constant<int, 4>{}, ci, sub, begin, len, lo, hi);
-      else segment(std::integral_constant<int, 2>{}, ci, sub, begin, len, lo, hi);
     }
-  }
 
-  // ---------------- merge the four waves --------------------------------------------------
-  if constexpr (WSPLIT) {
-    const float z_tot = grp_sum(z_part);
-    if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
-  } else {
-    if (nvalid && part == 0 && grp == 0) mM[wave][g] = m_run;
-    if (n == 0) {
-      if (g0 < G) mZ[wave][g0] = Zrun0;
-      if (g1 < G) mZ[wave][g1] = Zrun1;
+    // ---------------- this wave's partial, for the merge of the four waves ---------------
+    if constexpr (WSPLIT) {
+      const float z_tot = grp_sum(z_part);
+      if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
+    } else {
+      if (nvalid && part == 0 && grp == 0) mM[wave][g] = m_run;
+      if (n == 0) {
+        if (g0 < G) mZ[wave][g0] = Zrun0;
+        if (g1 < G) mZ[wave][g1] = Zrun1;
+      }
     }
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = 4 * (n + 16 * r) + j;
+        if (g0 < G) mO(wave, g0, c) = O[r][j][0];
+        if (g1 < G) mO(wave, g1, c) = O[r][j][1];
+      }
   }
-#pragma unroll
-  for (int r = 0; r < NR; ++r)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = 4 * (n + 16 * r) + j;
-      if (g0 < G) mO(wave, g0, c) = O[r][j][0];
-      if (g1 < G) mO(wave, g1, c) = O[r][j][1];
-    }
   __syncthreads();
   write_result();
 }
