@@ -3,16 +3,16 @@
 //
 // The packed cache is a cost line of half-blocks (32 slots: 512 B x D/32 of K
 // codes and as many of V codes, equal compute at either bit width) in which
-// every segment (chunk x subset) start also counts as kSegCost half-blocks, so
-// that small streaming chunks do not pile up on one workgroup.  The first
-// S_packed workgroups of a (batch, KV head) cut that line into equal runs; for
-// every segment in its run the four waves of a workgroup build the query operand
-// together, then each wave walks its share of the half-blocks with its own
-// online-softmax state in registers, loading half-block i+1 while it computes
-// half-block i; there is no barrier inside that loop.  The full-precision tail
-// goes to workgroups of its own (one wave per 32 tokens), off the critical path
-// of the packed ones.  The waves merge through LDS; when several workgroups
-// share one (batch, KV head) each writes a partial (m, Z, o) and
+// every segment (chunk x subset) start also counts as kSegCost half-blocks.
+// The waves of the S workgroups of a (batch, KV head) are workers of their own:
+// the packed waves cut that line into equal contiguous runs, one each; a wave
+// builds the query operand of every segment its run touches by itself (there is
+// no barrier at a segment start, so the small chunks of a streaming cache spread
+// over waves instead of serializing a workgroup), then walks its half-blocks with
+// its own online-softmax state in registers while the blocks ahead stream into
+// its LDS ring.  The full-precision tail is the role of a few waves spread over
+// the workgroups.  The four waves of a workgroup merge through LDS; when several
+// workgroups share one (batch, KV head) each writes a partial (m, Z, o) and
 // k_decode_reduce reduces them (a kernel boundary is the cheapest device-wide
 // release / acquire on this part: in-kernel fences cost more).
 //
@@ -654,8 +654,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       }
     };
     // the first blocks are in flight while the operand is built
-    issue(ring_lds, bl_lo, bl_lo < bl_hi);
-    issue(ring_lds + kStageBytes, bl_lo + 1, bl_lo + 1 < bl_hi);
+#pragma unroll
+    for (int i = 0; i < kStages - 1; ++i) issue(ring_lds + i * kStageBytes, bl_lo + i, bl_lo + i < bl_hi);
 
     u4 qB[KS];
     float Aq, sumqcz;
@@ -807,7 +807,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     for (int bi = bl_lo; bi < bl_hi; ++bi) {
       dma_reuse_fence();                         // the reads of the buffer about to be refilled are complete
       issue(dst_ahead, bi + kStages - 1, bi + kStages - 1 < bl_hi);
-      wait_vmem<2 * L_STAGE>();
+      wait_vmem<(kStages - 1) * L_STAGE>();
       if constexpr (NH == 1) {
         half_block(std::integral_constant<int, 0>{}, bi);
       } else {

@@ -183,6 +183,59 @@ def test_decode_tail_only_and_no_tail():
     assert np.abs(lse.cpu().numpy() - lse_o).max() < 1e-4
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,d,dtype,L0,bsel", [
+    (2, 8, 2, 128, torch.bfloat16, 500, (0, 1)),      # grouped heads, few workgroups: one tail unit per wave
+    (2, 4, 4, 128, torch.float16, 333, (0, 1)),       # one query head per KV head
+    (1, 8, 8, 64, torch.float32, 257, (0,)),          # fp32: split weights, normalized codes
+    (40, 8, 8, 64, torch.float16, 300, (0, 39)),      # more (batch, KV head) pairs than CUs: the tail shares waves by cost
+])
+def test_decode_many_chunks_and_tails(B, Hq, Hkv, d, dtype, L0, bsel):
+    """A streaming cache of up to seven chunks (a prefill and six 100-token flushes, so
+    most segments are a few half-blocks long) with tails from nothing to 700 tokens:
+    every split of the packed cost line and of the tail over the waves is exercised,
+    against the oracle's attention over the de-quantized GPU codes."""
+    from tests.pipeline_check import packed_to_chunks
+    g = torch.Generator().manual_seed(1234 + B + d)
+    n_flush, T_max = 6, 700
+    L_all = L0 + 100 * n_flush + T_max
+    K = torch.randn(B, Hkv, L_all, d, generator=g).to(dtype)
+    V = torch.randn(B, Hkv, L_all, d, generator=g).to(dtype)
+    K[:, :, :, 3] *= 12.0                                        # an outlier channel
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    lib = zb.load()
+    k0, kt = int(0.4 * L0), 40
+    cap_hi = lib.zc_arena_slots(k0 + n_flush * kt, 1 + n_flush)
+    cap_lo = lib.zc_arena_slots(L0 - k0 + n_flush * (100 - kt), 1 + n_flush)
+    Kp = zb.PackedTensor(B, Hkv, d, cap_hi, cap_lo, 4, 2, "channel", zb.ZC_LAYOUT_ROW, max_chunks=1 + n_flush, device=DEV)
+    Vp = zb.PackedTensor(B, Hkv, d, cap_hi, cap_lo, 4, 2, "cst", zb.ZC_LAYOUT_TGROUP, max_chunks=1 + n_flush, device=DEV)
+    atol = 1e-4 if dtype == torch.float32 else 2e-2
+    n_packed = 0
+    for c in range(1 + n_flush):
+        n_new, k_new = (L0, k0) if c == 0 else (100, kt)
+        sc = torch.rand(B, n_new, generator=g).to(DEV)
+        sal, reg = zb.zc_select_salient(sc, k_new)
+        sl = slice(n_packed, n_packed + n_new)
+        zb.zc_quantize_pack(Kd[:, :, sl], sal, reg, Kp, pos_offset=n_packed)
+        zb.zc_quantize_pack(Vd[:, :, sl], sal, reg, Vp, pos_offset=n_packed)
+        n_packed += n_new
+        if c not in (0, 1, n_flush):
+            continue
+        chunks_k, chunks_v = packed_to_chunks(Kp, bsel), packed_to_chunks(Vp, bsel)
+        for T in (0, 1, 16, 17, 100, 300, 700):
+            q = torch.randn(B, Hq, d, generator=g).to(dtype)
+            lse = torch.empty(B, Hq, dtype=torch.float32, device=DEV)
+            tk, tv = Kd[:, :, n_packed:n_packed + T_max], Vd[:, :, n_packed:n_packed + T_max]
+            out = zb.zc_decode_attention(q.to(DEV), Kp, Vp, tk if T else None, tv if T else None, T, lse_out=lse)
+            sel = list(bsel)
+            tko = K[sel, :, n_packed:n_packed + T].double().numpy() if T else None
+            tvo = V[sel, :, n_packed:n_packed + T].double().numpy() if T else None
+            Kc, Vc = zo.cache_matrices(chunks_k, chunks_v, Hkv, tko, tvo)
+            ref, lse_o, _ = zo.decode_attention(q[sel].double().numpy(), Kc, Vc)
+            err = np.abs(out[sel].cpu().double().numpy() - ref).max()
+            lerr = np.abs(lse[sel].cpu().numpy() - lse_o).max()
+            assert err <= atol and lerr <= max(atol, 1e-3) * 0.5, (c + 1, T, err, lerr)
+
+
 def test_results_are_deterministic():
     w = scaled(WORKLOADS["llama3_8b_4k"], L=900)
     from paper_2405_14256_amd import probes
