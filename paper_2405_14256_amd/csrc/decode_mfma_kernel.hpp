@@ -759,8 +759,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
             vtz[jj][v] = live ? vtz[jj][v] : 0.f;
           }
       }
-      const float lmax = fmaxf(fmaxf(fmaxf(lg[0][0], lg[0][1]), fmaxf(lg[0][2], lg[0][3])),
-                               fmaxf(fmaxf(lg[1][0], lg[1][1]), fmaxf(lg[1][2], lg[1][3])));
+      const float lmax = fmaxf(fmaxf(fmaxf(fmaxf(lg[0][0], lg[0][1]), lg[0][2]), fmaxf(fmaxf(lg[0][3], lg[1][0]), lg[1][1])),
+                               fmaxf(lg[1][2], lg[1][3]));       // three v_max3 and one v_max
       update_max(lmax, a1, acc, acc1);
       // weights w = p ts and the A operand of the output product
       float w2[2][4];
