@@ -21,7 +21,7 @@
 // probe that can see it and a row tile stops at its last row's position.
 // Inputs in fp16 / bf16 use the 32x32x16 MFMA, fp32 inputs the 32x32x2 fp32 MFMA
 // (no rounding of the operands); accumulation and softmax are fp32.
-#include "zc_common.hpp"
+#include "lds_dma.hpp"
 
 namespace zc {
 
@@ -36,7 +36,7 @@ struct ProbeArgs {
   const void* q;
   const void* k;
   int64_t q_sB, q_sH, q_sL, k_sB, k_sH, k_sL;
-  int B, Hq, Hkv, G, Lk, P;
+  int B, Hq, Hkv, G, Lk, Lq, P;
   const int32_t* probe_rows;
   const int32_t* probe_pos;
   float scale_log2;
@@ -69,9 +69,16 @@ template <int DT, int D>
 struct Tile {
   static constexpr int EB = (DT == ZC_F32) ? 4 : 2;
   static constexpr int ROWB = D * EB;          // bytes of one row
-  static constexpr int CPR = ROWB / 16;        // 16-byte chunks per row
-  static constexpr int STRIDE = ROWB + 16;     // padded LDS row stride
+  static constexpr int CPR = ROWB / 16;        // 16-byte chunks per row (8, 16 or 32)
   static constexpr int NKC = ROWB / 32;        // operand chunks per lane and row
+  static constexpr int RPI = 64 / CPR;         // rows one 64-lane transfer covers
+  // Rows sit in LDS unpadded (a transfer writes 64 consecutive chunks); chunk c of
+  // a row goes to chunk slot c ^ swz(row), which spreads the 16 rows that one
+  // quarter-wave reads at the same c over all 64 banks.
+  static constexpr int SW = CPR < 16 ? CPR : 16;
+  static constexpr int RP256 = ROWB >= 256 ? 1 : 256 / ROWB;
+  __device__ static int swz(int row) { return (row / RP256) % SW; }
+  __device__ static int slot(int row, int c) { return row * ROWB + ((c ^ swz(row)) << 4); }
 };
 
 // Workgroups are handed to the 8 XCDs round-robin by their linear index, and
@@ -87,101 +94,110 @@ __device__ inline int xcd_contiguous(int id, int n) {
 // in half-wave kh.
 __device__ inline int acc_row(int v, int kh) { return 8 * (v >> 2) + 4 * kh + (v & 3); }
 
+constexpr int kBufFlags = 0x00020000;          // raw 32-bit data, no swizzle
+constexpr int kOutOfRange = (int)0xFFFFF000u;  // a per-lane offset past the end of every admitted buffer
+
+constexpr int kLseRows = 128;                  // probe rows per workgroup of sweep 1
+constexpr int kLseCols = 64;                   // columns per K tile of sweep 1
+
 template <int DT, int D>
-__global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
+__global__ __launch_bounds__(256, 2) void k_probe_lse(ProbeArgs a) {
   using T = Tile<DT, D>;
-  // the probe rows go through the same LDS space as the K tiles: they are in
-  // registers before the first tile arrives (four workgroups fit a CU this way)
-  __shared__ __align__(16) uint8_t Ks[128 * T::STRIDE];
-  uint8_t* Qs = Ks;
-  __shared__ int spos[64];
-  __shared__ float sm[4][64], sz[4][64];
+  constexpr int TILE_B = kLseCols * T::ROWB;
+  constexpr int NI = kLseCols / T::RPI / 4;     // transfers per wave and K tile
+  __shared__ __align__(16) uint8_t Ks[2][TILE_B];
+  __shared__ int spos[kLseRows];
+  __shared__ float sm[2][kLseRows], sz[2][kLseRows];
 
   // logical order: probe-row block fastest, then column range, then query head, then batch
-  const int nrb = ceil_div(a.P, 64);
+  const int nrb = ceil_div(a.P, kLseRows);
   int j = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int rb0 = (j % nrb) * 64; j /= nrb;
+  const int rb0 = (j % nrb) * kLseRows; j /= nrb;
   const int split = j % a.nsplit; j /= a.nsplit;
   const int hq = j % a.Hq, b = j / a.Hq, hk = hq / a.G;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, kh = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rh = w >> 1, ch = w & 1;            // this wave: rows rh * 64 .. + 63, columns ch * 32 .. + 31 of a tile
   const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
   const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
+  const uint32_t k_rowb = (uint32_t)(a.k_sL * T::EB), q_rowb = (uint32_t)(a.q_sL * T::EB);
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(kb), 0, (uint32_t)(a.Lk - 1) * k_rowb + T::ROWB, kBufFlags);
+  const auto rs_q = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(qb), 0, (uint32_t)(a.Lq - 1) * q_rowb + T::ROWB, kBufFlags);
 
-  // the block's last row decides how many column tiles it sees; read it first so
-  // that the first K tile is requested together with the probe rows
-  const int nvalid = min(64, a.P - rb0);
+  // the block's last row decides how many column tiles it sees
+  const int nvalid = min(kLseRows, a.P - rb0);
   const int pmax = min(a.probe_pos[rb0 + nvalid - 1], a.Lk - 1);
-  const int ntiles = pmax / 128 + 1;
+  const int ntiles = pmax / kLseCols + 1;
   // this workgroup's share of the column tiles
   const int per = ceil_div(ntiles, a.nsplit);
   const int t_begin = split * per, t_end = min(t_begin + per, ntiles);
 
-  // a K tile travels global -> registers -> LDS; the next tile's loads are in
-  // flight while the current one is multiplied
-  constexpr int KCH = 128 * T::CPR / 256;      // 16-byte chunks per thread and tile
-  u32x4 kreg[KCH];
-  auto fetch = [&](int t) {
+  // A K tile goes global -> LDS directly, every wave a quarter of its transfers;
+  // the per-lane part of the addresses is fixed, the tile adds a scalar.
+  const uint32_t ks_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&Ks[0][0];
+  int kvoff[NI];
 #pragma unroll
-    for (int j = 0; j < KCH; ++j) {
-      const int i = tid + j * 256;
-      const int row = i / T::CPR, cc = i % T::CPR;
-      const int col = t * 128 + row;
-      kreg[j] = u32x4{0, 0, 0, 0};
-      if (col < a.Lk) kreg[j] = *reinterpret_cast<const u32x4*>(kb + (int64_t)col * a.k_sL * T::EB + cc * 16);
-    }
-  };
-  if (t_begin < t_end) fetch(t_begin);
-
-  for (int i = tid; i < 64 * T::CPR; i += 256) {
-    const int row = i / T::CPR, cc = i % T::CPR;
-    const int p = rb0 + row;
-    u32x4 v = {0, 0, 0, 0};
-    if (p < a.P) {
-      const int64_t qrow = a.probe_rows ? a.probe_rows[p] : a.probe_pos[p];
-      v = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
-    }
-    *reinterpret_cast<u32x4*>(Qs + row * T::STRIDE + cc * 16) = v;
+  for (int jj = 0; jj < NI; ++jj) {
+    const int row = (w + 4 * jj) * T::RPI + lane / T::CPR;
+    kvoff[jj] = (int)(row * k_rowb) + (((lane % T::CPR) ^ T::swz(row)) << 4);
   }
-  if (tid < 64) spos[tid] = (rb0 + tid < a.P) ? a.probe_pos[rb0 + tid] : -1;
-  __syncthreads();
+  // (the tile's offset goes into the per-lane offset, which is what the range check
+  // sees: rows past the end of K then arrive as zeros)
+  auto issue = [&](int t, int buf) {
+    const int toff = (int)((uint32_t)t * kLseCols * k_rowb);
+#pragma unroll
+    for (int jj = 0; jj < NI; ++jj) dma16<0>(ks_lds + buf * TILE_B + (w + 4 * jj) * 1024, rs_k, kvoff[jj] + toff, 0);
+  };
+  if (t_begin < t_end) issue(t_begin, 0);
 
+  // the probe rows of this wave, straight into operand registers
   u32x4 qf[2][T::NKC];
+  int myp[2];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < 2; ++rb) {
+    const int p = rb0 + rh * 64 + rb * 32 + r;
+    int voff = kOutOfRange;
+    myp[rb] = -1;
+    if (p < a.P) {
+      myp[rb] = a.probe_pos[p];
+      voff = (int)((uint32_t)(a.probe_rows ? a.probe_rows[p] : myp[rb]) * q_rowb) + kh * 16;
+    }
 #pragma unroll
-    for (int kc = 0; kc < T::NKC; ++kc)
-      qf[rb][kc] = *reinterpret_cast<const u32x4*>(Qs + (rb * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
-  const int myp[2] = {spos[r], spos[32 + r]};
+    for (int kc = 0; kc < T::NKC; ++kc) qf[rb][kc] = __builtin_amdgcn_raw_buffer_load_b128(rs_q, voff + kc * 32, 0, 0);
+  }
+  if (tid < kLseRows) spos[tid] = (rb0 + tid < a.P) ? a.probe_pos[rb0 + tid] : -1;
+  __syncthreads();
+  // rows are sorted by position: the wave's first row bounds what is fully visible,
+  // its last real row what is visible at all
+  const int pos_first = spos[rh * 64];
+  int pos_last = -1;
+  if (rb0 + rh * 64 < a.P) pos_last = spos[min(rh * 64 + 63, nvalid - 1)];
   float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
+  const int krow = ch * 32 + r;                  // this lane's column inside a tile
 
   for (int t = t_begin; t < t_end; ++t) {
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < KCH; ++j) {
-      const int i = tid + j * 256;
-      *reinterpret_cast<u32x4*>(Ks + (i / T::CPR) * T::STRIDE + (i % T::CPR) * 16) = kreg[j];
-    }
-    __syncthreads();
-    if (t + 1 < t_end) fetch(t + 1);
+    const int cur = (t - t_begin) & 1;
+    wait_vmem<0>();      // this wave's transfers of tile t have landed ...
+    __syncthreads();     // ... and everyone's; nobody still reads the other buffer
+    if (t + 1 < t_end) issue(t + 1, cur ^ 1);
+    if (t * kLseCols > pos_last) continue;       // nothing of this tile is visible to the wave's rows
     v16f acc[2];
 #pragma unroll
     for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
 #pragma unroll
     for (int kc = 0; kc < T::NKC; ++kc) {
-      const u32x4 af = *reinterpret_cast<const u32x4*>(Ks + (w * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+      const u32x4 af = *reinterpret_cast<const u32x4*>(&Ks[cur][T::slot(krow, 2 * kc + kh)]);
       mma_chunk<DT>(acc[0], af, qf[0][kc]);
       mma_chunk<DT>(acc[1], af, qf[1][kc]);
     }
-    const int colb = t * 128 + w * 32;
-    // rows are sorted by position: when the tile's last column is visible to the
-    // block's first row, nothing in the tile is masked
-    const bool tile_full = t * 128 + 127 <= spos[0];
+    const int colb = t * kLseCols + ch * 32;
+    const bool tile_full = t * kLseCols + kLseCols - 1 <= pos_first;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
       if (tile_full) {
-        float tmax = acc[rb][0];
+        float tmax = fmaxf(acc[rb][0], acc[rb][1]);
 #pragma unroll
-        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[rb][v]);
+        for (int v = 2; v < 16; v += 2) tmax = fmaxf(fmaxf(tmax, acc[rb][v]), acc[rb][v + 1]);
         const float m_new = fmaxf(m[rb], tmax * a.scale_log2);
         float sum = 0.f;
 #pragma unroll
@@ -209,23 +225,20 @@ __global__ __launch_bounds__(256) void k_probe_lse(ProbeArgs a) {
       }
     }
   }
-  // merge the two half-waves, then the four waves
+  // merge the two half-waves, then the two column halves
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const float mo = __shfl_xor(m[rb], 32), zo = __shfl_xor(z[rb], 32);
     const float M = fmaxf(m[rb], mo);
     float Z = 0.f;
     if (M > -INFINITY) Z = z[rb] * exp2f(m[rb] - M) + zo * exp2f(mo - M);
-    if (kh == 0) { sm[w][rb * 32 + r] = M; sz[w][rb * 32 + r] = Z; }
+    if (kh == 0) { sm[ch][rh * 64 + rb * 32 + r] = M; sz[ch][rh * 64 + rb * 32 + r] = Z; }
   }
   __syncthreads();
-  if (tid < 64 && rb0 + tid < a.P) {
-    float M = fmaxf(fmaxf(sm[0][tid], sm[1][tid]), fmaxf(sm[2][tid], sm[3][tid]));
+  if (tid < kLseRows && rb0 + tid < a.P) {
+    const float M = fmaxf(sm[0][tid], sm[1][tid]);
     float Z = 0.f;
-    if (M > -INFINITY) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) Z += sz[i][tid] * exp2f(sm[i][tid] - M);
-    }
+    if (M > -INFINITY) Z = sz[0][tid] * exp2f(sm[0][tid] - M) + sz[1][tid] * exp2f(sm[1][tid] - M);
     const int64_t row = ((int64_t)b * a.Hq + hq) * a.P + rb0 + tid;
     if (a.nsplit == 1) a.lse2[row] = M + log2f(Z);
     else a.lse_part[row * a.nsplit + split] = make_float2(M, Z);
@@ -258,14 +271,18 @@ __device__ inline int lower_bound_pos(const int32_t* pos, int n, int key) {
   return lo;
 }
 
+constexpr int kPosTable = 4096;     // probe positions kept in LDS (larger sets are read from memory)
+
 template <int DT, int D>
-__global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
+__global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
   using T = Tile<DT, D>;
-  // one LDS space: first the K tile (until its fragments are in registers), then
-  // the probe positions followed by the current tile of probe rows
-  __shared__ __align__(16) uint8_t Ks[128 * T::STRIDE];
-  __shared__ int spos[64];
-  __shared__ float slse[64];
+  constexpr int QT = 64;                        // probe rows per tile
+  constexpr int TILE_B = QT * T::ROWB;
+  constexpr int NI = QT / T::RPI / 4;           // transfers per wave and tile
+  __shared__ __align__(16) uint8_t Qs[2][TILE_B];
+  __shared__ int32_t lpos[kPosTable];
+  __shared__ __align__(16) int spos[2][QT];
+  __shared__ __align__(16) float slse[2][QT];
   __shared__ float scol[2][128];
 
   // logical order: column tile fastest, then query head, then batch
@@ -273,102 +290,89 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
   int j = xcd_contiguous(blockIdx.x, gridDim.x);
   const int col0 = (j % nct) * 128; j /= nct;
   const int hq = j % a.Hq, b = j / a.Hq, hk = hq / a.G;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, kh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, kh = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rbw = w >> 1, cbp = w & 1;
   const uint8_t* qb = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hq * a.q_sH) * T::EB;
   const uint8_t* kb = reinterpret_cast<const uint8_t*>(a.k) + ((int64_t)b * a.k_sB + (int64_t)hk * a.k_sH) * T::EB;
   const int64_t lrow = ((int64_t)b * a.Hq + hq) * a.P;
+  const uint32_t k_rowb = (uint32_t)(a.k_sL * T::EB), q_rowb = (uint32_t)(a.q_sL * T::EB);
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(kb), 0, (uint32_t)(a.Lk - 1) * k_rowb + T::ROWB, kBufFlags);
+  const auto rs_q = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(qb), 0, (uint32_t)(a.Lq - 1) * q_rowb + T::ROWB, kBufFlags);
+  const auto rs_pos = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.probe_pos), 0, (uint32_t)a.P * 4u, kBufFlags);
+  const float* lse_src = (a.lse_in ? a.lse_in : a.lse2) + lrow;
+  const auto rs_lse = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse_src), 0, (uint32_t)a.P * 4u, kBufFlags);
+  const float lse_unit = a.lse_in ? kLog2e : 1.f;      // an external log-sum-exp is in natural units
 
-  for (int i = tid; i < 128 * T::CPR; i += 256) {
-    const int row = i / T::CPR, cc = i % T::CPR;
-    const int col = col0 + row;
-    u32x4 v = {0, 0, 0, 0};
-    if (col < a.Lk) v = *reinterpret_cast<const u32x4*>(kb + (int64_t)col * a.k_sL * T::EB + cc * 16);
-    *reinterpret_cast<u32x4*>(Ks + row * T::STRIDE + cc * 16) = v;
-  }
-  __syncthreads();
+  // this wave's K columns, straight into operand registers (columns past the end: zeros)
   u32x4 kf[2][T::NKC];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb)
+  for (int cb = 0; cb < 2; ++cb) {
+    const int col = col0 + (cbp * 2 + cb) * 32 + r;
+    const int voff = col < a.Lk ? (int)((uint32_t)col * k_rowb) + kh * 16 : kOutOfRange;
 #pragma unroll
-    for (int kc = 0; kc < T::NKC; ++kc)
-      kf[cb][kc] = *reinterpret_cast<const u32x4*>(Ks + ((cbp * 2 + cb) * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
-
-  // the K tile is in registers now: its LDS space takes the probe positions, so
-  // that the two binary searches of this workgroup do not go to memory
-  __syncthreads();
-  constexpr int kPosCap = (128 - 64) * T::STRIDE / 4;     // what the tile of probe rows leaves free
+    for (int kc = 0; kc < T::NKC; ++kc) kf[cb][kc] = __builtin_amdgcn_raw_buffer_load_b128(rs_k, voff + kc * 32, 0, 0);
+  }
+  // the probe positions go to LDS, so that the binary searches and the row addresses
+  // of this workgroup do not go to memory
   const int32_t* ppos = a.probe_pos;
-  uint8_t* Qs = Ks + 64 * T::STRIDE;
-  if (a.P <= kPosCap) {
-    int32_t* lp = reinterpret_cast<int32_t*>(Ks);
-    for (int i = tid; i < a.P; i += 256) lp[i] = a.probe_pos[i];
+  if (a.P <= kPosTable) {
+    for (int i = tid; i < a.P; i += 256) lpos[i] = a.probe_pos[i];
     __syncthreads();
-    ppos = lp;
+    ppos = lpos;
   }
   const int pstart = lower_bound_pos(ppos, a.P, col0);
   float colsum[2] = {0.f, 0.f};
 
-  // a tile of 64 probe rows travels global -> registers -> LDS, the next one in
-  // flight while the current one is multiplied; threads 0..63 also carry the
-  // row's position and its log-sum-exp (log2 units)
-  constexpr int QCH = 64 * T::CPR / 256;
-  u32x4 qreg[QCH];
-  int pos_reg = -1;
-  float lse_reg = 0.f;
-  auto fetch = [&](int pr) {
+  // A tile of 64 probe rows goes global -> LDS directly, every wave a quarter of its
+  // transfers; wave 0 also brings the rows' positions and log-sum-exps.
+  const uint32_t qs_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&Qs[0][0];
+  const uint32_t spos_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&spos[0][0];
+  const uint32_t slse_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)&slse[0][0];
+  auto issue = [&](int pr, int buf) {
 #pragma unroll
-    for (int j = 0; j < QCH; ++j) {
-      const int i = tid + j * 256;
-      const int row = i / T::CPR, cc = i % T::CPR;
+    for (int jj = 0; jj < NI; ++jj) {
+      const int row = (w + 4 * jj) * T::RPI + lane / T::CPR;
       const int p = pr + row;
-      qreg[j] = u32x4{0, 0, 0, 0};
+      int voff = kOutOfRange;
       if (p < a.P) {
-        // (the positions are in LDS by now: no second trip to memory for the row address)
-        const int64_t qrow = a.probe_rows ? a.probe_rows[p] : ppos[p];
-        qreg[j] = *reinterpret_cast<const u32x4*>(qb + qrow * a.q_sL * T::EB + cc * 16);
+        const uint32_t qrow = (uint32_t)(a.probe_rows ? a.probe_rows[p] : ppos[p]);
+        voff = (int)(qrow * q_rowb) + (((lane % T::CPR) ^ T::swz(row)) << 4);
       }
+      dma16<0>(qs_lds + buf * TILE_B + (w + 4 * jj) * 1024, rs_q, voff, 0);
     }
-    if (tid < 64) {
-      const int p = pr + tid;
-      pos_reg = p < a.P ? ppos[p] : -1;
-      lse_reg = 0.f;
-      if (p < a.P) {
-        lse_reg = a.lse_in ? a.lse_in[lrow + p] * kLog2e : a.lse2[lrow + p];
-      }
+    if (w == 0) {
+      dma4(spos_lds + buf * (QT * 4), rs_pos, (pr + lane) * 4, 0);
+      dma4(slse_lds + buf * (QT * 4), rs_lse, (pr + lane) * 4, 0);
     }
   };
-  if (pstart < a.P) fetch(pstart);
+  if (pstart < a.P) issue(pstart, 0);
+  const int qrow_l = rbw * 32 + r;               // this lane's row inside a tile
 
-  for (int pr = pstart; pr < a.P; pr += 64) {
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < QCH; ++j) {
-      const int i = tid + j * 256;
-      *reinterpret_cast<u32x4*>(Qs + (i / T::CPR) * T::STRIDE + (i % T::CPR) * 16) = qreg[j];
-    }
-    if (tid < 64) { spos[tid] = pos_reg; slse[tid] = lse_reg; }
-    __syncthreads();
-    if (pr + 64 < a.P) fetch(pr + 64);
+  for (int pr = pstart; pr < a.P; pr += QT) {
+    const int cur = ((pr - pstart) / QT) & 1;
+    wait_vmem<0>();      // this wave's transfers of the tile have landed ...
+    __syncthreads();     // ... and everyone's; nobody still reads the other buffer
+    if (pr + QT < a.P) issue(pr + QT, cur ^ 1);
     int rp[16];
     float rl[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      rp[v] = spos[rbw * 32 + acc_row(v, kh)];
-      rl[v] = slse[rbw * 32 + acc_row(v, kh)];
+      rp[v] = spos[cur][rbw * 32 + acc_row(v, kh)];
+      rl[v] = slse[cur][rbw * 32 + acc_row(v, kh)] * lse_unit;
     }
     v16f acc[2];
 #pragma unroll
     for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
 #pragma unroll
     for (int kc = 0; kc < T::NKC; ++kc) {
-      const u32x4 af = *reinterpret_cast<const u32x4*>(Qs + (rbw * 32 + r) * T::STRIDE + kc * 32 + kh * 16);
+      const u32x4 af = *reinterpret_cast<const u32x4*>(&Qs[cur][T::slot(qrow_l, 2 * kc + kh)]);
       mma_chunk<DT>(acc[0], af, kf[0][kc]);
       mma_chunk<DT>(acc[1], af, kf[1][kc]);
     }
     // a tile of 64 real rows whose first position is past this workgroup's last
     // column needs no mask
-    const bool tile_full = pr + 64 <= a.P && col0 + 127 <= spos[0];
+    const bool tile_full = pr + QT <= a.P && col0 + 127 <= spos[cur][0];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
       const int col = col0 + (cbp * 2 + cb) * 32 + r;
@@ -379,7 +383,8 @@ __global__ __launch_bounds__(256) void k_probe_colsum(ProbeArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const float e = __builtin_amdgcn_exp2f(fmaf(acc[cb][v], a.scale_log2, -rl[v]));
-          colsum[cb] += (col <= rp[v]) ? e : 0.f;
+          const bool seen = col <= rp[v] && pr + rbw * 32 + acc_row(v, kh) < a.P;    // (rows past the last probe arrive as zeros)
+          colsum[cb] += seen ? e : 0.f;
         }
       }
     }
@@ -419,7 +424,7 @@ __global__ __launch_bounds__(256) void k_probe_mean(const float* __restrict__ pe
 template <int DT, int D>
 static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStream_t st) {
   if (need_lse) {
-    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3((unsigned)((int64_t)ceil_div(a.P, 64) * a.Hq * a.B * a.nsplit)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_probe_lse<DT, D>), dim3((unsigned)((int64_t)ceil_div(a.P, kLseRows) * a.Hq * a.B * a.nsplit)), dim3(256), 0, st, a);
     ZC_LAUNCH_CHECK();
     if (a.nsplit > 1) {
       const int64_t rows = (int64_t)a.B * a.Hq * a.P;
@@ -440,7 +445,7 @@ using namespace zc;
 
 // column ranges per row block of sweep 1: enough workgroups to fill the chip
 static int probe_splits(int64_t B, int64_t Hq, int64_t P) {
-  const int64_t wgs = B * Hq * ceil_div64(P, 64);
+  const int64_t wgs = B * Hq * ceil_div64(P, kLseRows);
   int64_t ns = 1024 / wgs;      // four workgroups fit a CU
   return (int)(ns < 1 ? 1 : (ns > kMaxProbeSplit ? kMaxProbeSplit : ns));
 }
@@ -465,6 +470,12 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   if (P < 1 || !probe_pos || !scores || k->L < 1 || q->L < 1) return ZC_ERR_INVALID_ARG;
   if (q->B > 65535 || q->H > 65535 || k->L > 0x7fffffff - 256) return ZC_ERR_UNSUPPORTED;
   if ((reinterpret_cast<uintptr_t>(probe_pos) & 3) || (reinterpret_cast<uintptr_t>(scores) & 3)) return ZC_ERR_INVALID_ARG;
+  {
+    // the kernels address one (batch, head) slab of q and of k with 32-bit byte offsets,
+    // and request "nothing" at offset 0xFFFFF000, which must lie past the end of a slab
+    const int64_t eb = q->dtype == ZC_F32 ? 4 : 2;
+    if (q->L * q->sL * eb >= 0xFFFFF000ll || k->L * k->sL * eb >= 0xFFFFF000ll || (int64_t)P * 4 >= 0xFFFFF000ll) return ZC_ERR_UNSUPPORTED;
+  }
   const size_t need = zc_probe_saliency_workspace(q->B, q->H, k->L, P);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
 
@@ -472,7 +483,7 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   a.q = q->ptr; a.k = k->ptr;
   a.q_sB = q->sB; a.q_sH = q->sH; a.q_sL = q->sL;
   a.k_sB = k->sB; a.k_sH = k->sH; a.k_sL = k->sL;
-  a.B = (int)q->B; a.Hq = (int)q->H; a.Hkv = (int)k->H; a.G = a.Hq / a.Hkv; a.Lk = (int)k->L; a.P = P;
+  a.B = (int)q->B; a.Hq = (int)q->H; a.Hkv = (int)k->H; a.G = a.Hq / a.Hkv; a.Lk = (int)k->L; a.Lq = (int)q->L; a.P = P;
   a.probe_rows = probe_rows; a.probe_pos = probe_pos;
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)q->D) : sm_scale) * kLog2e;
   float* ws_ph = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(ws) + lse_bytes(q->B, q->H, P));
@@ -480,7 +491,7 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   a.lse_part = reinterpret_cast<float2*>(ws);
   a.lse2 = reinterpret_cast<float*>(a.lse_part + (int64_t)q->B * q->H * P * kMaxProbeSplit);
   a.nsplit = probe_splits(q->B, q->H, P);
-  if ((int64_t)ceil_div64(P, 64) * q->H * q->B * a.nsplit > 0x7fffffff || (int64_t)ceil_div64(k->L, 128) * q->H * q->B > 0x7fffffff)
+  if ((int64_t)ceil_div64(P, kLseRows) * q->H * q->B * a.nsplit > 0x7fffffff || (int64_t)ceil_div64(k->L, 128) * q->H * q->B > 0x7fffffff)
     return ZC_ERR_UNSUPPORTED;
   a.per_head = scores_per_head ? scores_per_head : ws_ph;
 
