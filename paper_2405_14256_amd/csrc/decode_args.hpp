@@ -41,6 +41,7 @@ struct DecArgs {
   int S, n_units;  // workgroups per (batch, KV head); length of the packed cache's cost line
   int n_pw, n_tw;  // waves per (batch, KV head) that share the packed cache / the tail; n_pw + n_tw = 4 S
   int tw_full, tw_rem;   // n_tw = tw_full * S + tw_rem: tail waves per workgroup, and workgroups with one more
+  int tail_alone;        // 1: instead, the last n_tw workgroups hold one tail wave each and no packed wave
   int n_cu;        // compute units of the device
   float* part_m;   // [B, Hq, S]
   float* part_z;   // [B, Hq, S]

@@ -439,7 +439,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     a.n_cu = ncu;
   }
   int S = split_cap(q->B, q->H);
-  a.n_pw = 0; a.n_tw = 0; a.tw_full = 0; a.tw_rem = 0;
+  a.n_pw = 0; a.n_tw = 0; a.tw_full = 0; a.tw_rem = 0; a.tail_alone = 0;
   if (mfma_path) {
     const int64_t heads = q->B * Kp->H;
     const int64_t tail_units = ceil_div64(tail_len, kTailUnit);
@@ -479,12 +479,21 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
       if (n_tw > 4 * kTailSplits) n_tw = 4 * kTailSplits;
     }
     if (units == 0) S = 0;
-    int64_t WG = extra_waves ? ceil_div64(4 * (int64_t)S + n_tw, 4) : S;
+    a.tail_alone = 0;
+    int64_t WG = S;
+    if (extra_waves) {
+      if (units > 0 && heads * (S + n_tw) <= a.n_cu && S + n_tw <= 32 && S + n_tw <= split_cap(q->B, q->H) + kTailSplits) {
+        a.tail_alone = 1;            // plenty of idle CUs: a workgroup per tail unit, nothing else in it
+        WG = S + n_tw;
+      } else {
+        WG = ceil_div64(4 * (int64_t)S + n_tw, 4);
+      }
+    }
     if (WG > 32) WG = 32;
     if (WG < 1) WG = 1;              // empty cache: one workgroup writes the zeros
     if (units == 0) n_tw = 4 * WG;   // every wave is a tail wave (those past the last unit idle)
     a.n_tw = (int)n_tw;
-    a.n_pw = (int)(4 * WG - n_tw);
+    a.n_pw = a.tail_alone ? (int)(4 * S) : (int)(4 * WG - n_tw);
     a.tw_full = (int)(n_tw / WG);
     a.tw_rem = (int)(n_tw % WG);
     S = (int)WG;

@@ -251,9 +251,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // The tail waves are spread over the workgroups -- the last wave of the last
   // workgroups first -- because the tail's loads are many small rows, and one CU
   // has only so many misses in flight.
-  const int my_tails = a.tw_full + (s >= a.S - a.tw_rem ? 1 : 0);
+  // (tail_alone, for launches well below one workgroup per CU where only latency counts:
+  // the last n_tw workgroups carry one tail wave each and nothing else)
+  const int my_tails = a.tail_alone ? (s >= a.S - a.n_tw ? 4 : 0) : a.tw_full + (s >= a.S - a.tw_rem ? 1 : 0);
   const bool tail_wave = wave >= 4 - my_tails;
-  const int pw = 4 * s - a.tw_full * s - max(0, s - (a.S - a.tw_rem)) + wave;    // index among the packed waves
+  const int pw = a.tail_alone ? 4 * s + wave
+                              : 4 * s - a.tw_full * s - max(0, s - (a.S - a.tw_rem)) + wave;    // index among the packed waves
   const int npw = max(a.n_pw, 1);
   const int u0 = tail_wave ? 0 : (int)((int64_t)a.n_units * pw / npw);
   const int u1 = tail_wave ? 0 : (int)((int64_t)a.n_units * (pw + 1) / npw);
@@ -427,7 +430,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     constexpr int LPT = D / 8, TPI = 64 / LPT, NI = kTailUnit / TPI, NJ = kTailUnit / 16;
     const int tw = (3 - wave) * a.S + (a.S - 1 - s), n_tw = max(a.n_tw, 1);     // index among the tail waves
     const int n_tail = ceil_div(a.tail_len, kTailUnit);
-    const int wlo = (int)((int64_t)n_tail * tw / n_tw), whi = (int)((int64_t)n_tail * (tw + 1) / n_tw);
+    const bool working = tw < a.n_tw;              // (tail_alone: only the last wave of a tail workgroup works)
+    const int wlo = working ? (int)((int64_t)n_tail * tw / n_tw) : 0, whi = working ? (int)((int64_t)n_tail * (tw + 1) / n_tw) : 0;
     const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
     const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
     const int vtok = lane / LPT, vch = 8 * (lane % LPT);
