@@ -302,7 +302,6 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
   const auto rs_pos = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(a.probe_pos), 0, (uint32_t)a.P * 4u, kBufFlags);
   const float* lse_src = (a.lse_in ? a.lse_in : a.lse2) + lrow;
   const auto rs_lse = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse_src), 0, (uint32_t)a.P * 4u, kBufFlags);
-  const float lse_unit = a.lse_in ? kLog2e : 1.f;      // an external log-sum-exp is in natural units
 
   // this wave's K columns, straight into operand registers (columns past the end: zeros)
   u32x4 kf[2][T::NKC];
@@ -315,13 +314,16 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
   }
   // the probe positions go to LDS, so that the binary searches and the row addresses
   // of this workgroup do not go to memory
-  const int32_t* ppos = a.probe_pos;
-  if (a.P <= kPosTable) {
+  const bool pos_in_lds = a.P <= kPosTable;
+  if (pos_in_lds) {
     for (int i = tid; i < a.P; i += 256) lpos[i] = a.probe_pos[i];
     __syncthreads();
-    ppos = lpos;
   }
-  const int pstart = lower_bound_pos(ppos, a.P, col0);
+  const bool rows_in_lds = pos_in_lds && !a.probe_rows;              // the rows of q are the positions themselves
+  const auto lds_tab = (__attribute__((address_space(3))) const int32_t*)lpos;
+  const auto g_rows = (__attribute__((address_space(1))) const int32_t*)a.probe_rows;
+  const auto g_pos = (__attribute__((address_space(1))) const int32_t*)a.probe_pos;
+  const int pstart = pos_in_lds ? lower_bound_pos(lpos, a.P, col0) : lower_bound_pos(a.probe_pos, a.P, col0);
   float colsum[2] = {0.f, 0.f};
 
   // A tile of 64 probe rows goes global -> LDS directly, every wave a quarter of its
@@ -333,12 +335,14 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
 #pragma unroll
     for (int jj = 0; jj < NI; ++jj) {
       const int row = (w + 4 * jj) * T::RPI + lane / T::CPR;
-      const int p = pr + row;
-      int voff = kOutOfRange;
-      if (p < a.P) {
-        const uint32_t qrow = (uint32_t)(a.probe_rows ? a.probe_rows[p] : ppos[p]);
-        voff = (int)(qrow * q_rowb) + (((lane % T::CPR) ^ T::swz(row)) << 4);
-      }
+      const int p = pr + row, pc = min(p, a.P - 1);
+      uint32_t qrow;
+      // (uniform branches over pointers of known address space: an LDS read or a global
+      // one, never one through a generic pointer)
+      if (rows_in_lds) qrow = (uint32_t)lds_tab[pc];
+      else if (a.probe_rows) qrow = (uint32_t)g_rows[pc];
+      else qrow = (uint32_t)g_pos[pc];
+      const int voff = p < a.P ? (int)(qrow * q_rowb) + (((lane % T::CPR) ^ T::swz(row)) << 4) : kOutOfRange;
       dma16<0>(qs_lds + buf * TILE_B + (w + 4 * jj) * 1024, rs_q, voff, 0);
     }
     if (w == 0) {
@@ -354,12 +358,12 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
     wait_vmem<0>();      // this wave's transfers of the tile have landed ...
     __syncthreads();     // ... and everyone's; nobody still reads the other buffer
     if (pr + QT < a.P) issue(pr + QT, cur ^ 1);
-    int rp[16];
     float rl[16];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      rp[v] = spos[cur][rbw * 32 + acc_row(v, kh)];
-      rl[v] = slse[cur][rbw * 32 + acc_row(v, kh)] * lse_unit;
+    for (int v = 0; v < 16; ++v) rl[v] = slse[cur][rbw * 32 + acc_row(v, kh)];
+    if (a.lse_in) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) rl[v] *= kLog2e;       // an external log-sum-exp is in natural units
     }
     v16f acc[2];
 #pragma unroll
@@ -383,7 +387,8 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const float e = __builtin_amdgcn_exp2f(fmaf(acc[cb][v], a.scale_log2, -rl[v]));
-          const bool seen = col <= rp[v] && pr + rbw * 32 + acc_row(v, kh) < a.P;    // (rows past the last probe arrive as zeros)
+          const int row = rbw * 32 + acc_row(v, kh);
+          const bool seen = col <= spos[cur][row] && pr + row < a.P;    // (rows past the last probe arrive as zeros)
           colsum[cb] += seen ? e : 0.f;
         }
       }
@@ -398,7 +403,7 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
   if (tid < 128 && col0 + tid < a.Lk) {
     const int col = col0 + tid;
     const float total = scol[0][tid] + scol[1][tid];
-    const int cnt = a.P - lower_bound_pos(ppos, a.P, col);
+    const int cnt = a.P - (pos_in_lds ? lower_bound_pos(lpos, a.P, col) : lower_bound_pos(a.probe_pos, a.P, col));
     a.per_head[((int64_t)b * a.Hq + hq) * a.Lk + col] = cnt > 0 ? total / (float)cnt : 0.f;
   }
 }
