@@ -92,6 +92,29 @@ def _rand_scores(B, L, seed):
     return torch.rand(B, L, generator=g)
 
 
+def test_probe_more_rows_than_the_position_table():
+    """4200 probe rows: more than the kernels keep in LDS, so the binary searches and the
+    row addresses of the column sweep take their path through memory; also a sequence
+    length that is no multiple of any tile and head_dim 64."""
+    from paper_2405_14256_amd import probes
+    L, d = 21013, 64
+    g = torch.Generator().manual_seed(77)
+    Q = torch.randn(1, 1, L, d, generator=g).to(torch.bfloat16)
+    K = torch.randn(1, 1, L, d, generator=g).to(torch.bfloat16)
+    K[:, :, 0] += 2.0
+    pos = probes.probe_positions(L, 0.2, seed=5)
+    assert len(pos) > 4096
+    per_head = torch.empty(1, 1, L, dtype=torch.float32, device=DEV)
+    sc = zb.zc_probe_saliency(Q.to(DEV), K.to(DEV), torch.from_numpy(pos).to(DEV), scores_per_head=per_head)
+    ref, ref_ph = zo.saliency_scores(Q.double().numpy(), K.double().numpy(), pos)
+    got = sc.cpu().double().numpy()
+    assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max()
+    assert np.abs(per_head.cpu().double().numpy() - ref_ph).max() <= 1e-4 * np.abs(ref_ph).max()
+    # each probe row's probabilities sum to one: the column sums times their counts add up to P per head
+    cnt = zo.unmasked_count(pos.astype(np.int64), L)
+    assert np.allclose((per_head.cpu().double().numpy() * cnt).sum(-1), len(pos), rtol=1e-4)
+
+
 @pytest.mark.parametrize("L,k", [(1, 0), (1, 1), (7, 3), (1000, 0), (1000, 1000), (1024, 1), (5000, 4999), (40000, 4000)])
 def test_select_edges(L, k):
     sc = _rand_scores(2, L, L + k)
