@@ -259,6 +259,36 @@ def test_decode_many_chunks_and_tails(B, Hq, Hkv, d, dtype, L0, bsel):
             assert err <= atol and lerr <= max(atol, 1e-3) * 0.5, (c + 1, T, err, lerr)
 
 
+def test_decode_same_answer_under_any_split():
+    """The same sequence alone (few workgroups: many waves per head, a workgroup per tail
+    unit) and replicated 48 times (more heads than CUs: two or three workgroups per
+    head, the tail sharing waves): the split of the cost line must not show in the
+    result beyond the rounding of the partial sums."""
+    Hq, Hkv, d, L, T = 16, 8, 128, 3000, 77
+    g = torch.Generator().manual_seed(4242)
+    K1 = torch.randn(1, Hkv, L + T, d, generator=g).to(torch.bfloat16)
+    V1 = torch.randn(1, Hkv, L + T, d, generator=g).to(torch.bfloat16)
+    q1 = torch.randn(1, Hq, d, generator=g).to(torch.bfloat16)
+    sc1 = torch.rand(1, L, generator=g)
+    lib = zb.load()
+    k = 1200
+    outs, lses = [], []
+    for B in (1, 48):
+        Kd, Vd = K1.expand(B, -1, -1, -1).contiguous().to(DEV), V1.expand(B, -1, -1, -1).contiguous().to(DEV)
+        sal, reg = zb.zc_select_salient(sc1.expand(B, -1).contiguous().to(DEV), k)
+        Kp = zb.PackedTensor(B, Hkv, d, lib.zc_arena_slots(k, 1), lib.zc_arena_slots(L - k, 1), 4, 2, "channel", zb.ZC_LAYOUT_ROW, max_chunks=1, device=DEV)
+        Vp = zb.PackedTensor(B, Hkv, d, lib.zc_arena_slots(k, 1), lib.zc_arena_slots(L - k, 1), 4, 2, "cst", zb.ZC_LAYOUT_TGROUP, max_chunks=1, device=DEV)
+        zb.zc_quantize_pack(Kd[:, :, :L], sal, reg, Kp)
+        zb.zc_quantize_pack(Vd[:, :, :L], sal, reg, Vp)
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=DEV)
+        out = zb.zc_decode_attention(q1.expand(B, -1, -1).contiguous().to(DEV), Kp, Vp, Kd[:, :, L:], Vd[:, :, L:], T, lse_out=lse)
+        outs.append(out.float().cpu())
+        lses.append(lse.cpu())
+    assert torch.equal(outs[1], outs[1][:1].expand_as(outs[1]))          # every replica alike (deterministic)
+    assert (lses[1] - lses[0]).abs().max() <= 2e-5
+    assert (outs[1] - outs[0]).abs().max() <= 2.0 ** -7 * outs[0].abs().max()    # one bf16 rounding step at most
+
+
 def test_results_are_deterministic():
     w = scaled(WORKLOADS["llama3_8b_4k"], L=900)
     from paper_2405_14256_amd import probes
