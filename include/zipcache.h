@@ -147,6 +147,18 @@ int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
                       float* scores, float* scores_per_head,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* ---- Eq. 7 (the accumulated attention score the paper argues against) ------
+ * Same arguments, workspace and error behaviour as zc_probe_saliency; the
+ * column sums are NOT divided by the number of probes that see the column:
+ *   scores[b, i] = mean over query heads of sum_{p : probe_pos[p] >= i} A[p, i].
+ * With all rows as probes this is Eq. 7 itself (earlier tokens accumulate more
+ * terms: the bias of Section 4.2); serves as the comparison metric. */
+int zc_probe_accumulated(const zc_tensor4* q, const zc_tensor4* k,
+                         const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
+                         float sm_scale, const float* lse_ext,
+                         float* scores, float* scores_per_head,
+                         void* ws, size_t ws_bytes, void* stream);
+
 /* ---- Algorithm 2, Split(., p~, r%) ------------------------------------------
  * scores: device float [B, L] (must not contain NaN).  For every batch row
  * the k largest scores are salient; among equal scores the lower index wins.

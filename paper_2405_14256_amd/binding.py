@@ -70,6 +70,8 @@ def load() -> C.CDLL:
     lib.zc_probe_saliency_workspace.argtypes = [I64, I64, I64, I64]
     lib.zc_probe_saliency.restype = C.c_int
     lib.zc_probe_saliency.argtypes = [T4, T4, P, P, I32, F, P, P, P, P, SZ, P]
+    lib.zc_probe_accumulated.restype = C.c_int
+    lib.zc_probe_accumulated.argtypes = [T4, T4, P, P, I32, F, P, P, P, P, SZ, P]
     lib.zc_select_salient_workspace.restype = SZ
     lib.zc_select_salient_workspace.argtypes = [I64, I64]
     lib.zc_select_salient.restype = C.c_int
@@ -178,7 +180,7 @@ class PackedTensor:
 def zc_probe_saliency(q: torch.Tensor, k: torch.Tensor, probe_pos: torch.Tensor,
                       probe_rows: Optional[torch.Tensor] = None, sm_scale: float = 0.0,
                       lse_ext: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
-                      scores_per_head: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      scores_per_head: Optional[torch.Tensor] = None, _entry: str = "zc_probe_saliency") -> torch.Tensor:
     lib = load()
     B, Hq, _, _ = q.shape
     Lk = k.shape[2]
@@ -188,11 +190,16 @@ def zc_probe_saliency(q: torch.Tensor, k: torch.Tensor, probe_pos: torch.Tensor,
     need = lib.zc_probe_saliency_workspace(B, Hq, Lk, P)
     ws = _workspace(need, q.device)
     tq, tk = tensor4(q), tensor4(k)
-    _check("zc_probe_saliency",
-           lib.zc_probe_saliency(C.byref(tq), C.byref(tk), _ptr(probe_rows), _ptr(probe_pos), P, float(sm_scale),
-                                 _ptr(lse_ext), _ptr(scores), _ptr(scores_per_head), ws.data_ptr(), ws.numel(),
-                                 _stream()))
+    _check(_entry,
+           getattr(lib, _entry)(C.byref(tq), C.byref(tk), _ptr(probe_rows), _ptr(probe_pos), P, float(sm_scale),
+                                _ptr(lse_ext), _ptr(scores), _ptr(scores_per_head), ws.data_ptr(), ws.numel(),
+                                _stream()))
     return scores
+
+
+def zc_probe_accumulated(q: torch.Tensor, k: torch.Tensor, probe_pos: torch.Tensor, **kw) -> torch.Tensor:
+    """Eq. 7: as zc_probe_saliency, without the division by the unmasked count."""
+    return zc_probe_saliency(q, k, probe_pos, _entry="zc_probe_accumulated", **kw)
 
 
 def zc_select_salient(scores: torch.Tensor, k: int, salient_idx: Optional[torch.Tensor] = None,

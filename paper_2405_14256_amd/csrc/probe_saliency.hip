@@ -45,6 +45,7 @@ struct ProbeArgs {
   float2* lse_part;      // [B, Hq, P, nsplit] (running maximum in log2 units, sum) when nsplit > 1
   int nsplit;            // column ranges a row block's sweep 1 is split into
   float* per_head;       // [B, Hq, Lk]
+  int normalize;         // 1: divide a column's sum by the number of probes that see it (Eq. 8); 0: Eq. 7
 };
 
 // One 16-byte operand chunk per lane: a single 32x32x16 MFMA for 16-bit types,
@@ -274,7 +275,7 @@ __device__ inline int lower_bound_pos(const int32_t* pos, int n, int key) {
 constexpr int kPosTable = 4096;     // probe positions kept in LDS (larger sets are read from memory)
 
 template <int DT, int D>
-__global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
+__global__ __launch_bounds__(256, (DT == ZC_F32 && D == 128) ? 1 : 2) void k_probe_colsum(ProbeArgs a) {
   using T = Tile<DT, D>;
   constexpr int QT = 64;                        // probe rows per tile
   constexpr int TILE_B = QT * T::ROWB;
@@ -404,7 +405,7 @@ __global__ __launch_bounds__(256, 2) void k_probe_colsum(ProbeArgs a) {
     const int col = col0 + tid;
     const float total = scol[0][tid] + scol[1][tid];
     const int cnt = a.P - (pos_in_lds ? lower_bound_pos(lpos, a.P, col) : lower_bound_pos(a.probe_pos, a.P, col));
-    a.per_head[((int64_t)b * a.Hq + hq) * a.Lk + col] = cnt > 0 ? total / (float)cnt : 0.f;
+    a.per_head[((int64_t)b * a.Hq + hq) * a.Lk + col] = !a.normalize ? total : (cnt > 0 ? total / (float)cnt : 0.f);
   }
 }
 
@@ -461,11 +462,11 @@ extern "C" size_t zc_probe_saliency_workspace(int64_t B, int64_t Hq, int64_t Lk,
   return lse_bytes(B, Hq, P) + (size_t)B * Hq * Lk * 4;
 }
 
-extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
-                                 const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
-                                 float sm_scale, const float* lse_ext,
-                                 float* scores, float* scores_per_head,
-                                 void* ws, size_t ws_bytes, void* stream) {
+static int probe_scores(const zc_tensor4* q, const zc_tensor4* k,
+                        const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
+                        float sm_scale, const float* lse_ext,
+                        float* scores, float* scores_per_head,
+                        void* ws, size_t ws_bytes, void* stream, bool normalize) {
   int rc = zc_validate_tensor(q);
   if (rc) return rc;
   rc = zc_validate_tensor(k);
@@ -499,6 +500,7 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   if ((int64_t)ceil_div64(P, kLseRows) * q->H * q->B * a.nsplit > 0x7fffffff || (int64_t)ceil_div64(k->L, 128) * q->H * q->B > 0x7fffffff)
     return ZC_ERR_UNSUPPORTED;
   a.per_head = scores_per_head ? scores_per_head : ws_ph;
+  a.normalize = normalize ? 1 : 0;
 
   hipStream_t st = (hipStream_t)stream;
   const bool need_lse = lse_ext == nullptr;
@@ -507,4 +509,20 @@ extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
   if (q->dtype == ZC_F16) return ZC_PROBE(ZC_F16);
   return ZC_PROBE(ZC_BF16);
 #undef ZC_PROBE
+}
+
+extern "C" int zc_probe_saliency(const zc_tensor4* q, const zc_tensor4* k,
+                                 const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
+                                 float sm_scale, const float* lse_ext,
+                                 float* scores, float* scores_per_head,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  return probe_scores(q, k, probe_rows, probe_pos, P, sm_scale, lse_ext, scores, scores_per_head, ws, ws_bytes, stream, true);
+}
+
+extern "C" int zc_probe_accumulated(const zc_tensor4* q, const zc_tensor4* k,
+                                    const int32_t* probe_rows, const int32_t* probe_pos, int32_t P,
+                                    float sm_scale, const float* lse_ext,
+                                    float* scores, float* scores_per_head,
+                                    void* ws, size_t ws_bytes, void* stream) {
+  return probe_scores(q, k, probe_rows, probe_pos, P, sm_scale, lse_ext, scores, scores_per_head, ws, ws_bytes, stream, false);
 }

@@ -20,11 +20,29 @@ def probe_counts(L: int, probe_ratio: float):
     return n_recent, n_random
 
 
-def probe_positions(L: int, probe_ratio: float = 0.10, seed: int = 0) -> np.ndarray:
-    """Sorted unique positions: the last n_recent tokens plus n_random tokens
-    drawn without replacement from the remaining ones."""
+STRATEGIES = ("random+recent", "recent", "random", "all")
+
+
+def probe_positions(L: int, probe_ratio: float = 0.10, seed: int = 0, strategy: str = "random+recent") -> np.ndarray:
+    """Sorted unique probe positions.
+
+    "random+recent" (the method's choice): the last n_recent tokens plus
+    n_random tokens drawn without replacement from the remaining ones.
+    The alternatives of the probe-strategy comparison (Section 4.3, Table 2) take
+    the same number of probes: "recent" the last ones only, "random" a uniform
+    draw over the whole sequence, "all" every token (the full attention matrix).
+    A column after the last probe is seen by no probe and scores 0: only "random"
+    can leave such columns."""
+    if strategy not in STRATEGIES:
+        raise ValueError(f"unknown probe strategy {strategy!r}")
     n_recent, n_random = probe_counts(L, probe_ratio)
     rng = np.random.Generator(np.random.PCG64(seed))
+    if strategy == "all":
+        return np.arange(L, dtype=np.int32)
+    if strategy == "recent":
+        return np.arange(L - min(L, n_recent + n_random), L, dtype=np.int32)
+    if strategy == "random":
+        return np.sort(rng.choice(L, size=min(L, n_recent + n_random), replace=False)).astype(np.int32)
     rand = rng.choice(L - n_recent, size=n_random, replace=False) if n_random else np.zeros(0, np.int64)
     pos = np.concatenate([np.sort(rand), np.arange(L - n_recent, L)])
     return pos.astype(np.int32)

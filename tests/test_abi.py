@@ -22,7 +22,8 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = zb.load()
     names = declared_functions()
-    assert {"zc_probe_saliency", "zc_select_salient", "zc_quantize_pack", "zc_decode_attention", "zc_unpack"} <= set(names)
+    assert {"zc_probe_saliency", "zc_select_salient", "zc_quantize_pack", "zc_decode_attention", "zc_unpack",
+            "zc_probe_accumulated"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in zipcache.h but not exported"
     assert lib.zc_version() >= 1

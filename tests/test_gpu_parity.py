@@ -115,6 +115,37 @@ def test_probe_more_rows_than_the_position_table():
     assert np.allclose((per_head.cpu().double().numpy() * cnt).sum(-1), len(pos), rtol=1e-4)
 
 
+def test_accumulated_scores_and_probe_strategies():
+    """Eq. 7 (no division by the unmasked count) and the probe choices of the strategy
+    comparison (Section 4.3): every variant against the oracle on the same probes; with
+    every token as a probe the normalized score is Eq. 8 on the full matrix, and the
+    accumulated score of token 0 exceeds one (the bias the normalization removes)."""
+    from paper_2405_14256_amd import probes
+    from paper_2405_14256_amd.workloads import make_prefill
+    w = scaled(WORKLOADS["llama3_8b_4k"], L=901, Hq=8, Hkv=2)
+    inp = make_prefill(w)
+    Q, K = inp["Q"].to(DEV), inp["K"].to(DEV)
+    Qo, Ko = inp["Q"].double().numpy(), inp["K"].double().numpy()
+    k = w.k_salient
+    picked = {}
+    for strategy in probes.STRATEGIES:
+        pos = probes.probe_positions(w.L, w.probe_ratio, seed=11, strategy=strategy)
+        pos_d = torch.from_numpy(pos).to(DEV)
+        for normalized, fn in ((True, zb.zc_probe_saliency), (False, zb.zc_probe_accumulated)):
+            got = fn(Q, K, pos_d).cpu().double().numpy()
+            ref, _ = zo.saliency_scores(Qo, Ko, pos, normalized=normalized)
+            assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max(), (strategy, normalized)
+            if strategy == "all" and not normalized:
+                assert got[0, 0] > 1.0 and abs(got[0].sum() - w.L) <= 1e-3 * w.L     # every row of A sums to one
+            if normalized:
+                sal, _ = zb.zc_select_salient(torch.from_numpy(got).float().to(DEV), k)
+                picked[strategy] = set(sal[0].cpu().tolist())
+    # what each strategy selects, against what the full attention matrix selects (Table 2's question)
+    overlap = {s: len(picked[s] & picked["all"]) / k for s in picked}
+    print("overlap with the full-matrix salient set:", overlap)
+    assert overlap["all"] == 1.0 and all(0.0 <= v <= 1.0 for v in overlap.values())
+
+
 @pytest.mark.parametrize("L,k", [(1, 0), (1, 1), (7, 3), (1000, 0), (1000, 1000), (1024, 1), (5000, 4999), (40000, 4000)])
 def test_select_edges(L, k):
     sc = _rand_scores(2, L, L + k)

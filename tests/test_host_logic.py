@@ -22,6 +22,23 @@ def test_probe_positions(L, ratio):
         assert not np.array_equal(pos, probes.probe_positions(L, ratio, seed=4))
 
 
+def test_probe_strategies_take_the_same_number_of_probes():
+    L, ratio = 4096, 0.10
+    hybrid = probes.probe_positions(L, ratio, seed=2)
+    recent = probes.probe_positions(L, ratio, seed=2, strategy="recent")
+    rand = probes.probe_positions(L, ratio, seed=2, strategy="random")
+    every = probes.probe_positions(L, ratio, seed=2, strategy="all")
+    assert len(recent) == len(rand) == len(hybrid) == 410
+    assert list(recent) == list(range(L - 410, L))
+    assert np.all(np.diff(rand) > 0) and rand.min() >= 0 and rand.max() < L
+    assert not np.array_equal(rand, hybrid)
+    assert list(every) == list(range(L))
+    for p in (hybrid, recent, rand, every):
+        assert p.dtype == np.int32
+    with pytest.raises(ValueError):
+        probes.probe_positions(L, ratio, strategy="special")
+
+
 def test_probe_counts_match_the_five_configs():
     assert probes.probe_counts(256, 0.10) == (13, 13)
     assert probes.probe_counts(4096, 0.10) == (205, 205)
