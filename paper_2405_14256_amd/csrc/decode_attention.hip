@@ -399,7 +399,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     units += nh + nl;
     if (mfma_path) units += (nh > 0 ? kSegCost : 0) + (nl > 0 ? kSegCost : 0);   // the MFMA kernel splits a cost line
   }
-  if (!mfma_path) units += ceil_div64(tail_len, kTailBlock);   // the MFMA kernel gives the tail workgroups of its own
+  if (!mfma_path) units += ceil_div64(tail_len, kTailBlock);   // (the MFMA kernel gives the tail to waves of its own)
   if (units > 0x7fffffff) return ZC_ERR_UNSUPPORTED;
 
   DecArgs a;
