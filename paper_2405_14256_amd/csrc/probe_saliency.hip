@@ -196,15 +196,29 @@ __global__ __launch_bounds__(256, 2) void k_probe_lse(ProbeArgs a) {
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
       if (tile_full) {
-        float tmax = fmaxf(acc[rb][0], acc[rb][1]);
+        // Every logit of the tile counts.  The reference point m of a row only has to keep
+        // exp2 in range, not to be the maximum: it is taken from the row's first tile
+        // and moved only when a tile's sum shows that some logit lies 2^60 above it
+        // (the log-sum-exp m + log2(z) does not depend on the choice).
+        bool redo = __builtin_amdgcn_ballot_w64(m[rb] == -INFINITY) != 0;
+        if (!redo) {
+          float sum = 0.f;
 #pragma unroll
-        for (int v = 2; v < 16; v += 2) tmax = fmaxf(fmaxf(tmax, acc[rb][v]), acc[rb][v + 1]);
-        const float m_new = fmaxf(m[rb], tmax * a.scale_log2);
-        float sum = 0.f;
+          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][v], a.scale_log2, -m[rb]));
+          redo = __builtin_amdgcn_ballot_w64(!(sum < 0x1p60f)) != 0;
+          if (!redo) z[rb] += sum;
+        }
+        if (redo) {
+          float tmax = fmaxf(acc[rb][0], acc[rb][1]);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][v], a.scale_log2, -m_new));
-        z[rb] = z[rb] * __builtin_amdgcn_exp2f(m[rb] - m_new) + sum;
-        m[rb] = m_new;
+          for (int v = 2; v < 16; v += 2) tmax = fmaxf(fmaxf(tmax, acc[rb][v]), acc[rb][v + 1]);
+          const float m_new = fmaxf(m[rb], tmax * a.scale_log2);
+          float sum = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][v], a.scale_log2, -m_new));
+          z[rb] = z[rb] * __builtin_amdgcn_exp2f(m[rb] - m_new) + sum;
+          m[rb] = m_new;
+        }
       } else {
         float sv[16];
         float tmax = -INFINITY;
