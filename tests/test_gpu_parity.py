@@ -290,6 +290,57 @@ def test_decode_many_chunks_and_tails(B, Hq, Hkv, d, dtype, L0, bsel):
             assert err <= atol and lerr <= max(atol, 1e-3) * 0.5, (c + 1, T, err, lerr)
 
 
+def test_decode_randomized_shapes():
+    """Thirty seeded draws of (batch, heads, group size, head_dim, dtype, bit widths, K scheme,
+    prefill length, number and size of flushed chunks, tail length): the decode entry
+    point against the oracle's attention over the de-quantized GPU codes."""
+    from tests.pipeline_check import packed_to_chunks
+    rng = np.random.Generator(np.random.PCG64(20240514))
+    lib = zb.load()
+    for case in range(30):
+        d = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        B = int(rng.choice([1, 2, 3, 37])) if Hkv * G <= 16 else int(rng.choice([1, 2]))
+        dtype = [torch.bfloat16, torch.float16, torch.float32][int(rng.integers(3))]
+        bits_hi, bits_lo = [(4, 2), (4, 4), (2, 2)][int(rng.integers(3))]
+        k_scheme = ["channel", "cst"][int(rng.integers(2))]
+        L0 = int(rng.integers(1, 700))
+        n_flush = int(rng.integers(0, 4))
+        T = int(rng.choice([0, 1, 15, 16, 33, 100, 257]))
+        sizes = [L0] + [int(rng.integers(1, 130)) for _ in range(n_flush)]
+        ks = [int(rng.integers(0, n + 1)) for n in sizes]
+        g = torch.Generator().manual_seed(1000 + case)
+        L_all = sum(sizes) + max(T, 1)
+        K = torch.randn(B, Hkv, L_all, d, generator=g).to(dtype)
+        V = torch.randn(B, Hkv, L_all, d, generator=g).to(dtype)
+        Kd, Vd = K.to(DEV), V.to(DEV)
+        cap_hi = lib.zc_arena_slots(sum(ks), len(sizes))
+        cap_lo = lib.zc_arena_slots(sum(sizes) - sum(ks), len(sizes))
+        Kp = zb.PackedTensor(B, Hkv, d, cap_hi, cap_lo, bits_hi, bits_lo, k_scheme, zb.ZC_LAYOUT_ROW, max_chunks=len(sizes), device=DEV)
+        Vp = zb.PackedTensor(B, Hkv, d, cap_hi, cap_lo, bits_hi, bits_lo, "cst", zb.ZC_LAYOUT_TGROUP, max_chunks=len(sizes), device=DEV)
+        n_packed = 0
+        for n_new, k_new in zip(sizes, ks):
+            sal, reg = zb.zc_select_salient(torch.rand(B, n_new, generator=g).to(DEV), k_new)
+            sl = slice(n_packed, n_packed + n_new)
+            zb.zc_quantize_pack(Kd[:, :, sl], sal, reg, Kp, pos_offset=n_packed)
+            zb.zc_quantize_pack(Vd[:, :, sl], sal, reg, Vp, pos_offset=n_packed)
+            n_packed += n_new
+        bsel = sorted({0, B - 1})
+        q = torch.randn(B, Hkv * G, d, generator=g).to(dtype)
+        lse = torch.empty(B, Hkv * G, dtype=torch.float32, device=DEV)
+        tk, tv = Kd[:, :, n_packed:], Vd[:, :, n_packed:]
+        out = zb.zc_decode_attention(q.to(DEV), Kp, Vp, tk if T else None, tv if T else None, T, lse_out=lse)
+        tko = K[bsel, :, n_packed:n_packed + T].double().numpy() if T else None
+        tvo = V[bsel, :, n_packed:n_packed + T].double().numpy() if T else None
+        Kc, Vc = zo.cache_matrices(packed_to_chunks(Kp, bsel), packed_to_chunks(Vp, bsel), Hkv, tko, tvo)
+        ref, lse_o, _ = zo.decode_attention(q[bsel].double().numpy(), Kc, Vc)
+        atol = 1e-4 if dtype == torch.float32 else 2e-2
+        what = (case, B, Hkv, G, d, str(dtype), bits_hi, bits_lo, k_scheme, sizes, ks, T)
+        assert np.abs(out[bsel].cpu().double().numpy() - ref).max() <= atol, what
+        assert np.abs(lse[bsel].cpu().numpy() - lse_o).max() <= max(atol, 1e-3) * 0.5, what
+
+
 def test_decode_same_answer_under_any_split():
     """The same sequence alone (few workgroups: many waves per head, a workgroup per tail
     unit) and replicated 48 times (more heads than CUs: two or three workgroups per
