@@ -115,6 +115,40 @@ def test_probe_more_rows_than_the_position_table():
     assert np.allclose((per_head.cpu().double().numpy() * cnt).sum(-1), len(pos), rtol=1e-4)
 
 
+def test_probe_randomized_shapes():
+    """Sixteen seeded draws of (batch, heads, group size, head_dim, dtype, key length, probe set):
+    normalized scores against the oracle; every other case takes the decode-time form
+    (probe queries in rows of their own, external log-normalisers)."""
+    rng = np.random.Generator(np.random.PCG64(424242))
+    for case in range(16):
+        d = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 2, 4]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        B = int(rng.choice([1, 2, 5]))
+        dtype = [torch.bfloat16, torch.float16, torch.float32][int(rng.integers(3))]
+        Lk = int(rng.integers(1, 1500))
+        P = int(rng.integers(1, min(Lk, 400) + 1))
+        pos = np.sort(rng.choice(Lk, size=P, replace=False)).astype(np.int32)
+        g = torch.Generator().manual_seed(5000 + case)
+        K = torch.randn(B, Hkv, Lk, d, generator=g).to(dtype)
+        kw, kwo = {}, {}
+        if case % 2:
+            Q = torch.randn(B, Hkv * G, P + 3, d, generator=g).to(dtype)        # probe queries in rows of their own
+            rows = rng.permutation(P + 3)[:P].astype(np.int32)
+            # log-normalisers of a softmax that also covered tokens outside k: anything >= the window's own
+            own = np.stack([[zo.probe_attention(Q[b, h, rows].double().numpy(), pos, K[b, h // G].double().numpy())[1]
+                             for h in range(Hkv * G)] for b in range(B)])
+            ext = own + rng.random(own.shape) * 2.0
+            kw = dict(probe_rows=torch.from_numpy(rows).to(DEV), lse_ext=torch.from_numpy(ext).float().to(DEV))
+            kwo = dict(probe_rows=rows, lse_ext=ext.astype(np.float32).astype(np.float64))
+        else:
+            Q = torch.randn(B, Hkv * G, Lk, d, generator=g).to(dtype)
+        got = zb.zc_probe_saliency(Q.to(DEV), K.to(DEV), torch.from_numpy(pos).to(DEV), **kw).cpu().double().numpy()
+        ref, _ = zo.saliency_scores(Q.double().numpy(), K.double().numpy(), pos, **kwo)
+        what = (case, B, Hkv, G, d, str(dtype), Lk, P)
+        assert np.abs(got - ref).max() <= 1e-4 * max(np.abs(ref).max(), 1e-30), what
+
+
 def test_accumulated_scores_and_probe_strategies():
     """Eq. 7 (no division by the unmasked count) and the probe choices of the strategy
     comparison (Section 4.3): every variant against the oracle on the same probes; with
