@@ -83,6 +83,13 @@ class HotPath:
         self.sal_t = torch.empty(w.B, self.k_tail, **i32)
         self.reg_t = torch.empty(w.B, FLUSH_INTERVAL - self.k_tail, **i32)
         self.lse_p = torch.empty(w.B, w.Hq, len(self.probe_off_np), **f32)
+        # the log-sum-exp of a probe step goes straight to its row of lse_probe[f] (the other
+        # steps' go to self.lse): the flush then needs one transposing copy, no gather
+        self.lse_probe = [torch.empty(len(self.probe_off_np), w.B, w.Hq, **f32) for _ in range(self.n_flush)]
+        self.lse_slot = {}
+        for f in range(self.n_flush):
+            for i, off in enumerate(self.probe_off_np.tolist()):
+                self.lse_slot[f * FLUSH_INTERVAL + off] = self.lse_probe[f][i]
         self.flush_rows = []
         for f in range(self.n_flush):
             r = (self.probe_off + f * FLUSH_INTERVAL).to(torch.int32)
@@ -143,7 +150,7 @@ class HotPath:
                 for j in range(j0, j1):
                     T = j - base + 1
                     zb.zc_decode_attention(self.q_all[:, :, j:j + 1], self.Kp, self.Vp, self.tail_k[:, :, base:],
-                                           self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse[j])
+                                           self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse_slot.get(j, self.lse[j]))
                     hi = sum(c[1] for c in self.Kp.chunks); lo = sum(c[3] for c in self.Kp.chunks)
                     nbytes += self.decode_bytes(hi, lo, self.Kp.c.n_chunks, T)
                 fn.nbytes = nbytes
@@ -153,7 +160,7 @@ class HotPath:
             def fn():
                 base = f * FLUSH_INTERVAL
                 rows, rows_long = self.flush_rows[f]
-                self.lse_p.copy_(self.lse.index_select(0, rows_long).permute(1, 2, 0))
+                self.lse_p.copy_(self.lse_probe[f].permute(1, 2, 0))
                 tk = self.tail_k[:, :, base:base + FLUSH_INTERVAL]
                 tv = self.tail_v[:, :, base:base + FLUSH_INTERVAL]
                 zb.zc_probe_saliency(self.q_all, tk, self.probe_off, probe_rows=rows, lse_ext=self.lse_p,
