@@ -76,7 +76,6 @@ class HotPath:
         self.sal = torch.empty(w.B, self.k, **i32)
         self.reg = torch.empty(w.B, w.L - self.k, **i32)
         self.out = torch.empty(S, w.B, w.Hq, w.d, dtype=w.torch_dtype, device=dev)
-        self.lse = torch.empty(S, w.B, w.Hq, **f32)
         self.probe_off_np = probes.decode_probe_offsets(FLUSH_INTERVAL, seed=w.seed)
         self.probe_off = torch.from_numpy(self.probe_off_np).to(dev)
         self.tail_scores = torch.empty(w.B, FLUSH_INTERVAL, **f32)
@@ -84,7 +83,7 @@ class HotPath:
         self.reg_t = torch.empty(w.B, FLUSH_INTERVAL - self.k_tail, **i32)
         self.lse_p = torch.empty(w.B, w.Hq, len(self.probe_off_np), **f32)
         # the log-sum-exp of a probe step goes straight to its row of lse_probe[f] (the other
-        # steps' go to self.lse): the flush then needs one transposing copy, no gather
+        # steps do not ask for it): the flush then needs one transposing copy, no gather
         self.lse_probe = [torch.empty(len(self.probe_off_np), w.B, w.Hq, **f32) for _ in range(self.n_flush)]
         self.lse_slot = {}
         for f in range(self.n_flush):
@@ -150,7 +149,7 @@ class HotPath:
                 for j in range(j0, j1):
                     T = j - base + 1
                     zb.zc_decode_attention(self.q_all[:, :, j:j + 1], self.Kp, self.Vp, self.tail_k[:, :, base:],
-                                           self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse_slot.get(j, self.lse[j]))
+                                           self.tail_v[:, :, base:], T, out=self.out[j], lse_out=self.lse_slot.get(j))    # only probe steps need it (Alg. 3)
                     hi = sum(c[1] for c in self.Kp.chunks); lo = sum(c[3] for c in self.Kp.chunks)
                     nbytes += self.decode_bytes(hi, lo, self.Kp.c.n_chunks, T)
                 fn.nbytes = nbytes
