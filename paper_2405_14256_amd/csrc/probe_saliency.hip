@@ -494,7 +494,9 @@ static int probe_scores(const zc_tensor4* q, const zc_tensor4* k,
     // the kernels address one (batch, head) slab of q and of k with 32-bit byte offsets,
     // and request "nothing" at offset 0xFFFFF000, which must lie past the end of a slab
     const int64_t eb = q->dtype == ZC_F32 ? 4 : 2;
-    if (q->L * q->sL * eb >= 0xFFFFF000ll || k->L * k->sL * eb >= 0xFFFFF000ll || (int64_t)P * 4 >= 0xFFFFF000ll) return ZC_ERR_UNSUPPORTED;
+    // (a K tile may start up to 63 rows before the end of k and reach as far past it: those
+    // offsets must not wrap either)
+    if (q->L * q->sL * eb >= 0xFFFFF000ll || (k->L + 128) * k->sL * eb >= 0xFFFFF000ll || (int64_t)P * 4 >= 0xFFFFF000ll) return ZC_ERR_UNSUPPORTED;
   }
   const size_t need = zc_probe_saliency_workspace(q->B, q->H, k->L, P);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
