@@ -79,6 +79,11 @@ def test_probe_rejects_bad_arguments_before_launch():
     assert call(_t4(H=32, ptr=0x1004), k) == -1                  # misaligned
     bad = _t4(H=32); bad.sL = 100
     assert call(bad, k) == -1                                    # stride not a multiple of 8 / < D
+    # one (batch, head) slab of q or k beyond what a 32-bit byte offset reaches: refused, not wrapped
+    huge = 1 << 24                                               # 16 M tokens x 128 x 2 bytes = 4 GiB per slab
+    big_ws = lib.zc_probe_saliency_workspace(1, 32, huge, 4)
+    assert call(_t4(H=32, L=huge), _t4(H=8, L=huge), wsz=big_ws) == -2
+    assert lib.zc_probe_accumulated(C.byref(q), C.byref(k), None, None, 4, 0.0, None, 0x4000, None, 0x5000, ws, None) == -1
 
 
 def _packed(layout, scheme=zb.ZC_SCHEME_CST, cap=128, n_chunks=0, max_chunks=2, table=None):
