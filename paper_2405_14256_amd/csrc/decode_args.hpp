@@ -42,6 +42,8 @@ struct DecArgs {
   int n_pw, n_tw;  // waves per (batch, KV head) that share the packed cache / the tail; n_pw + n_tw = 4 S
   int tw_full, tw_rem;   // n_tw = tw_full * S + tw_rem: tail waves per workgroup, and workgroups with one more
   int tail_alone;        // 1: instead, the last n_tw workgroups hold one tail wave each and no packed wave
+  int pw_q, pw_r;        // n_units = pw_q * n_pw + pw_r: cost units per packed wave, and waves with one more
+  int tu_q, tu_r;        // tail units = tu_q * n_tw + tu_r, likewise
   int n_cu;        // compute units of the device
   float* part_m;   // [B, Hq, S]
   float* part_z;   // [B, Hq, S]

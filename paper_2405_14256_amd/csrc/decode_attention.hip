@@ -440,6 +440,7 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   }
   int S = split_cap(q->B, q->H);
   a.n_pw = 0; a.n_tw = 0; a.tw_full = 0; a.tw_rem = 0; a.tail_alone = 0;
+  a.pw_q = a.pw_r = a.tu_q = a.tu_r = 0;
   if (mfma_path) {
     const int64_t heads = q->B * Kp->H;
     const int64_t tail_units = ceil_div64(tail_len, kTailUnit);
@@ -496,6 +497,10 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     a.n_pw = a.tail_alone ? (int)(4 * S) : (int)(4 * WG - n_tw);
     a.tw_full = (int)(n_tw / WG);
     a.tw_rem = (int)(n_tw % WG);
+    a.pw_q = a.n_pw > 0 ? (int)(units / a.n_pw) : 0;
+    a.pw_r = a.n_pw > 0 ? (int)(units % a.n_pw) : 0;
+    a.tu_q = a.n_tw > 0 ? (int)(tail_units / a.n_tw) : 0;
+    a.tu_r = a.n_tw > 0 ? (int)(tail_units % a.n_tw) : 0;
     S = (int)WG;
   } else if (S > units) {
     S = (int)(units > 0 ? units : 1);

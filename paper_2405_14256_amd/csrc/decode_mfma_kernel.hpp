@@ -257,9 +257,10 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   const bool tail_wave = wave >= 4 - my_tails;
   const int pw = a.tail_alone ? 4 * s + wave
                               : 4 * s - a.tw_full * s - max(0, s - (a.S - a.tw_rem)) + wave;    // index among the packed waves
-  const int npw = max(a.n_pw, 1);
-  const int u0 = tail_wave ? 0 : (int)((int64_t)a.n_units * pw / npw);
-  const int u1 = tail_wave ? 0 : (int)((int64_t)a.n_units * (pw + 1) / npw);
+  // (unit j of the line belongs to packed wave j / q for the first r * (q + 1) units, where the
+  // host has divided n_units = q * n_pw + r: the first r waves take one unit more; no division here)
+  const int u0 = tail_wave ? 0 : a.pw_q * pw + min(pw, a.pw_r);
+  const int u1 = tail_wave ? 0 : a.pw_q * (pw + 1) + min(pw + 1, a.pw_r);
 
   // The running maximum of a head is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
@@ -428,10 +429,10 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // sum of V on the vector ALUs, lane = (token mod TPI, 8 channels).
   if (tail_wave) {
     constexpr int LPT = D / 8, TPI = 64 / LPT, NI = kTailUnit / TPI, NJ = kTailUnit / 16;
-    const int tw = (3 - wave) * a.S + (a.S - 1 - s), n_tw = max(a.n_tw, 1);     // index among the tail waves
-    const int n_tail = ceil_div(a.tail_len, kTailUnit);
+    const int tw = (3 - wave) * a.S + (a.S - 1 - s);     // index among the tail waves
     const bool working = tw < a.n_tw;              // (tail_alone: only the last wave of a tail workgroup works)
-    const int wlo = working ? (int)((int64_t)n_tail * tw / n_tw) : 0, whi = working ? (int)((int64_t)n_tail * (tw + 1) / n_tw) : 0;
+    // the tail's units over its waves, as above: units = tu_q * n_tw + tu_r
+    const int wlo = working ? a.tu_q * tw + min(tw, a.tu_r) : 0, whi = working ? a.tu_q * (tw + 1) + min(tw + 1, a.tu_r) : 0;
     const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
     const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
     const int vtok = lane / LPT, vch = 8 * (lane % LPT);
