@@ -245,6 +245,29 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) { O[r][j][0] = 0.f; O[r][j][1] = 0.f; }
 
+  // Everything the start of a wave needs from the kernel arguments is requested here, in
+  // one batch of scalar loads: left to itself the compiler fetches each field where the
+  // control flow first needs it, a dozen dependent round trips before the first load of data.
+  {
+    int i0 = a.S, i1 = a.n_pw, i2 = a.n_tw, i3 = a.tw_full, i4 = a.tw_rem, i5 = a.tail_alone, i6 = a.pw_q, i7 = a.pw_r,
+        i8 = a.tu_q, i9 = a.tu_r, i10 = a.n_chunks, i11 = a.chunks_inline, i12 = a.G, i13 = a.Hq, i14 = a.Hkv, i15 = a.B,
+        i16 = a.tail_len, i17 = a.bits[0], i18 = a.bits[1], i19 = a.chunk_rows[0], i20 = a.chunk_rows[1],
+        i21 = a.chunk_rows[2], i22 = a.chunk_rows[3];
+    float f0 = a.scale_log2;
+    int64_t l0 = a.q_sB, l1 = a.q_sH, l2 = a.cap[0], l3 = a.cap[1];
+    const void *p0 = a.q, *p1 = a.kc[0], *p2 = a.kc[1], *p3 = a.vc[0], *p4 = a.vc[1], *p5 = a.k_cs, *p6 = a.k_cz,
+               *p7 = a.v_cs, *p8 = a.v_cz, *p9 = a.v_ts[0], *p10 = a.v_ts[1], *p11 = a.v_tz[0], *p12 = a.v_tz[1],
+               *p13 = a.chunk_table;
+    asm volatile("" :: "s"(i0), "s"(i1), "s"(i2), "s"(i3), "s"(i4), "s"(i5), "s"(i6), "s"(i7), "s"(i8), "s"(i9), "s"(i10),
+                 "s"(i11), "s"(i12), "s"(i13), "s"(i14), "s"(i15), "s"(i16), "s"(i17), "s"(i18), "s"(i19), "s"(i20), "s"(i21),
+                 "s"(i22), "s"(f0));
+    int64_t t0 = a.tk_sB, t1 = a.tk_sH, t2 = a.tk_sL, t3 = a.tv_sB, t4 = a.tv_sH, t5 = a.tv_sL;
+    const void *t6 = a.tail_k, *t7 = a.tail_v;
+    asm volatile("" :: "s"(t0), "s"(t1), "s"(t2), "s"(t3), "s"(t4), "s"(t5), "s"(t6), "s"(t7));
+    asm volatile("" :: "s"(l0), "s"(l1), "s"(l2), "s"(l3), "s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6),
+                 "s"(p7), "s"(p8), "s"(p9), "s"(p10), "s"(p11), "s"(p12), "s"(p13));
+  }
+
   // The waves of the workgroups of one (batch, KV head) are workers of their own:
   // n_tw of them take the full-precision tail, the other n_pw share the cost line of
   // the packed cache (half-blocks + kSegCost per segment start, a contiguous run each).
