@@ -375,6 +375,9 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
     if (tail_k->B != q->B || tail_v->B != q->B || tail_k->H != Kp->H || tail_v->H != Kp->H ||
         tail_k->D != q->D || tail_v->D != q->D || tail_k->L < tail_len || tail_v->L < tail_len)
       return ZC_ERR_INVALID_ARG;
+    // the matrix-core kernel addresses the tail rows of one (batch, KV head) with 32-bit byte offsets
+    const int64_t eb = q->dtype == ZC_F32 ? 4 : 2;
+    if (tail_len * tail_k->sL * eb >= 0xFFFFF000ll || tail_len * tail_v->sL * eb >= 0xFFFFF000ll) return ZC_ERR_UNSUPPORTED;
   }
   if (q->B > 65535 || Kp->H > 65535) return ZC_ERR_UNSUPPORTED;
   // the matrix-core kernel addresses one (batch, KV head) part of an arena with 32-bit offsets,

@@ -167,19 +167,6 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 template <int DT> struct Raw8 { uint4 a; };
 template <> struct Raw8<ZC_F32> { uint4 a, b; };
 template <int DT>
-__device__ inline Raw8<DT> raw_load8(const void* base, int64_t off, bool valid) {
-  Raw8<DT> r;
-  const uint4 zero = uint4{0u, 0u, 0u, 0u};
-  if constexpr (DT == ZC_F32) {
-    const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(base) + off);
-    r.a = valid ? p[0] : zero;
-    r.b = valid ? p[1] : zero;
-  } else {
-    r.a = valid ? *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + off) : zero;
-  }
-  return r;
-}
-template <int DT>
 __device__ inline void raw_to_float(const Raw8<DT>& r, float (&v)[8]) {
   if constexpr (DT == ZC_F32) {
     v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
@@ -456,9 +443,27 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const bool working = tw < a.n_tw;              // (tail_alone: only the last wave of a tail workgroup works)
     // the tail's units over its waves, as above: units = tu_q * n_tw + tu_r
     const int wlo = working ? a.tu_q * tw + min(tw, a.tu_r) : 0, whi = working ? a.tu_q * (tw + 1) + min(tw + 1, a.tu_r) : 0;
-    const int64_t kb = (int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH;
-    const int64_t vb = (int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH;
+    // Buffer resources over this (batch, KV head)'s rows of the tail: rows past its end are
+    // asked for at an offset beyond the buffer and arrive as zeros (no branch per load).
+    constexpr int EB = (DT == ZC_F32) ? 4 : 2;
+    constexpr int kTailFlags = 0x00020000;
+    constexpr int kTailOOR = (int)0xFFFFF000u;
+    const uint8_t* tkp = reinterpret_cast<const uint8_t*>(a.tail_k) + ((int64_t)b * a.tk_sB + (int64_t)hk * a.tk_sH) * EB;
+    const uint8_t* tvp = reinterpret_cast<const uint8_t*>(a.tail_v) + ((int64_t)b * a.tv_sB + (int64_t)hk * a.tv_sH) * EB;
+    const uint32_t tk_rowb = (uint32_t)a.tk_sL * EB, tv_rowb = (uint32_t)a.tv_sL * EB;
+    const auto rs_tk = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(tkp), 0, (uint32_t)(a.tail_len - 1) * tk_rowb + D * EB, kTailFlags);
+    const auto rs_tv = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(tvp), 0, (uint32_t)(a.tail_len - 1) * tv_rowb + D * EB, kTailFlags);
     const int vtok = lane / LPT, vch = 8 * (lane % LPT);
+    auto load8 = [&](__amdgpu_buffer_rsrc_t rs, int voff) {
+      Raw8<DT> r;
+      const u4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, 0, 0);
+      r.a = uint4{x.x, x.y, x.z, x.w};
+      if constexpr (DT == ZC_F32) {
+        const u4 y = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16, 0, 0);
+        r.b = uint4{y.x, y.y, y.z, y.w};
+      }
+      return r;
+    };
     struct TBuf {
       Raw8<DT> k[NJ][KS];
       Raw8<DT> v[NI];
@@ -467,13 +472,17 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       const int t0 = tu * kTailUnit;
       const int ntok = min(kTailUnit, a.tail_len - t0);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j)
+      for (int j = 0; j < NJ; ++j) {
+        const int row = 16 * j + n;
+        const int voff = row < ntok ? (int)((uint32_t)(t0 + row) * tk_rowb) + 8 * grp * EB : kTailOOR;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          bf.k[j][ks] = raw_load8<DT>(a.tail_k, kb + (int64_t)(t0 + 16 * j + n) * a.tk_sL + 32 * ks + 8 * grp, 16 * j + n < ntok);
+        for (int ks = 0; ks < KS; ++ks) bf.k[j][ks] = load8(rs_tk, voff + 32 * ks * EB);
+      }
 #pragma unroll
-      for (int i = 0; i < NI; ++i)
-        bf.v[i] = raw_load8<DT>(a.tail_v, vb + (int64_t)(t0 + i * TPI + vtok) * a.tv_sL + vch, i * TPI + vtok < ntok);
+      for (int i = 0; i < NI; ++i) {
+        const int row = i * TPI + vtok;
+        bf.v[i] = load8(rs_tv, row < ntok ? (int)((uint32_t)(t0 + row) * tv_rowb) + vch * EB : kTailOOR);
+      }
     };
     // 16-bit tensors: two units are in flight, so a wave with at most two units pays one
     // trip to memory (fp32 rows take twice the registers: one unit at a time)
