@@ -632,17 +632,24 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     // per-lane offset is fixed, the half-block adds a scalar offset, reads past
     // the end return zeros.  (The host checks that each part is below 4 GiB.)
     const int64_t bh = (int64_t)b * a.Hkv + hk;
-    const uint32_t code_bytes = (uint32_t)(a.cap[sub] * ROWB);
-    const uint32_t tok_bytes = (uint32_t)(a.cap[sub] * 4);
+    // (selects between the two subsets' kernel arguments, which are in registers already:
+    // an index would be another scalar load and another wait)
+    const int64_t cap = sub ? a.cap[1] : a.cap[0];
+    const uint8_t* kc = sub ? a.kc[1] : a.kc[0];
+    const uint32_t* vc = sub ? a.vc[1] : a.vc[0];
+    const float *k_ts = sub ? a.k_ts[1] : a.k_ts[0], *k_tz = sub ? a.k_tz[1] : a.k_tz[0];
+    const float *v_ts = sub ? a.v_ts[1] : a.v_ts[0], *v_tz = sub ? a.v_tz[1] : a.v_tz[0];
+    const uint32_t code_bytes = (uint32_t)(cap * ROWB);
+    const uint32_t tok_bytes = (uint32_t)(cap * 4);
     constexpr int kRsrcFlags = 0x00020000;              // raw 32-bit data, no swizzle
-    const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.kc[sub] + bh * (int64_t)code_bytes), 0, code_bytes, kRsrcFlags);
+    const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(kc + bh * (int64_t)code_bytes), 0, code_bytes, kRsrcFlags);
     const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(a.vc[sub]) + bh * (int64_t)code_bytes), 0, code_bytes, kRsrcFlags);
-    const int64_t tokbase = (int64_t)b * a.cap[sub];
-    const auto rs_kts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? a.k_ts[sub] + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
-    const auto rs_ktz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? a.k_tz[sub] + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
-    const auto rs_vts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? a.v_ts[sub] + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
-    const auto rs_vtz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? a.v_tz[sub] + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
+        const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(vc) + bh * (int64_t)code_bytes), 0, code_bytes, kRsrcFlags);
+    const int64_t tokbase = (int64_t)b * cap;
+    const auto rs_kts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? k_ts + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
+    const auto rs_ktz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(KTOK ? k_tz + tokbase : nullptr), 0, KTOK ? tok_bytes : 0, kRsrcFlags);
+    const auto rs_vts = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? v_ts + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
+    const auto rs_vtz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? v_tz + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
     // Staging: block bi of the segment is D * 16 contiguous bytes of K codes and as
     // many of V codes; each goes to LDS with KCH 1 KB transfers.  (Token parameters:
     // 64 floats per array, of which a 4-bit block uses the first 32.)
@@ -889,7 +896,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
           len = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub + 1]);
           asm volatile("" : "+s"(begin), "+s"(len));
         }
-        const int bits = a.bits[sub];
+        const int bits = sub ? a.bits[1] : a.bits[0];
         const int TB = 4 * (32 / bits);
         const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
         if (nb == 0) continue;
