@@ -214,6 +214,54 @@ def cpu_baseline(hp: HotPath, decode_sample: int = 4):
                       f"extrapolated to one whole step of the whole batch"}, sal
 
 
+def machine_peaks(args):
+    """What the GPU attains on the simplest code: a streaming read and a streaming copy of
+    2 GiB (eight times the Infinity Cache, so every byte comes from HBM) and a register-only
+    loop of 32x32x16 matrix instructions; best and median of `--steps` launches each."""
+    import ctypes as C
+    lib = C.CDLL(os.path.join(ROOT, "paper_2405_14256_amd", "libzc_peaks.so"))
+    lib.zc_peak_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.zc_peak_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.zc_peak_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    st = torch.cuda.current_stream().cuda_stream
+    nbytes = 2 << 30
+    src = torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    iters, wgs = 512, n_cu * 8
+    flops = wgs * 4 * iters * 8 * 2 * 32 * 32 * 16
+
+    def timed(fn):
+        for _ in range(max(args.warmup, 1)):
+            assert fn() == 0
+        ts = []
+        for _ in range(max(args.steps, 3)):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            assert fn() == 0
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e-3)
+        ts.sort()
+        return ts[0], ts[len(ts) // 2]
+
+    rd = timed(lambda: lib.zc_peak_read(src.data_ptr(), nbytes, sink.data_ptr(), st))
+    cp = timed(lambda: lib.zc_peak_copy(dst.data_ptr(), src.data_ptr(), nbytes, st))
+    assert torch.equal(dst[-4096:], src[-4096:]) and torch.equal(dst[:4096], src[:4096])
+    mb = timed(lambda: lib.zc_peak_mfma(2, wgs, iters, sink.data_ptr(), st))
+    mh = timed(lambda: lib.zc_peak_mfma(1, wgs, iters, sink.data_ptr(), st))
+    print(json.dumps({
+        "machine_peaks": {
+            "read_TBps": {"best": nbytes / rd[0] / 1e12, "median": nbytes / rd[1] / 1e12, "bytes": nbytes},
+            "copy_TBps_read_plus_write": {"best": 2 * nbytes / cp[0] / 1e12, "median": 2 * nbytes / cp[1] / 1e12, "bytes": 2 * nbytes},
+            "mfma_bf16_PFLOPs": {"best": flops / mb[0] / 1e15, "median": flops / mb[1] / 1e15},
+            "mfma_f16_PFLOPs": {"best": flops / mh[0] / 1e15, "median": flops / mh[1] / 1e15},
+            "data_sheet": {"hbm_TBps": 8.0, "mfma_16bit_PFLOPs": 2.5},
+            "compute_units": n_cu, "launches_timed": max(args.steps, 3),
+        }}))
+
+
 def decode_sweep(args):
     """Decode entry point alone at the metric's layer shape, batch 1 -> 64: each size is
     timed "warm" (the same packed cache every call: it stays in the last-level cache) and
@@ -294,6 +342,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain copies of 256 MiB (a kernel of known traffic, "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="instead of the step: time the machine-peak probes (streaming read, streaming copy, a loop "
+                         "of matrix instructions) and print what this GPU attains as one JSON line")
     ap.add_argument("--decode-sweep", action="store_true",
                     help="instead of the step: time the decode entry point alone at batch 1..64 of the "
                          "workload's layer shape, cold and warm caches, and print that table as one JSON line")
@@ -305,6 +356,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     zb.load()
+    if args.peaks:
+        machine_peaks(args)
+        return
     if args.decode_sweep:
         decode_sweep(args)
         return

@@ -31,6 +31,28 @@ def test_library_exports_every_declared_symbol():
     assert b"workspace" in lib.zc_status_string(-3)
 
 
+def test_peak_probe_library_exports_its_header_and_checks_arguments():
+    """The machine-peak probes of bench.py --peaks live in a library of their own."""
+    src = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "zc_peaks.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(zc_peak_[a-z_]+)\s*\(", src)))
+    assert names == ["zc_peak_copy", "zc_peak_mfma", "zc_peak_read"]
+    lib = C.CDLL(os.path.join(ROOT, "paper_2405_14256_amd", "libzc_peaks.so"))
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in zc_peaks.h but not exported"
+    lib.zc_peak_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.zc_peak_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.zc_peak_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    # host-side refusals (nothing is launched): null, misaligned, overlapping, bad type
+    assert lib.zc_peak_read(None, 16, 0x1000, None) == -1
+    assert lib.zc_peak_read(0x1008, 16, 0x1000, None) == -1
+    assert lib.zc_peak_read(0x1000, 24, 0x1000, None) == -1
+    assert lib.zc_peak_copy(0x1000, 0x1010, 32, None) == -1
+    assert lib.zc_peak_copy(0x1000, None, 32, None) == -1
+    assert lib.zc_peak_mfma(0, 1, 1, 0x1000, None) == -1
+    assert lib.zc_peak_mfma(2, 0, 1, 0x1000, None) == -1
+    assert lib.zc_peak_mfma(2, 1, 1, None, None) == -1
+
+
 def test_struct_sizes_match_header_layout():
     # 8-byte alignment, no hidden padding surprises
     assert C.sizeof(zb.zc_tensor4) == 8 + 4 + 4 + 7 * 8
