@@ -187,21 +187,67 @@ __global__ __launch_bounds__(256) void k_chan_finalize(QPArgs a) {
   }
 }
 
-// ---- wave64 all-reduce through DPP (no LDS traffic) --------------------------------
-template <int CTRL, int ROW_MASK>
-__device__ inline float dpp_move(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+// ---- minima of N values over a wave at once -----------------------------------------
+// Every lane brings N = 8 or 16 values; afterwards lane l holds the minimum over the
+// wave of value number value_of_lane<N>(l).  Each step halves the values a lane still
+// carries: two lanes that differ in one bit of the lane number exchange the half the
+// other one keeps and reduce the half they keep themselves, so the whole reduction is
+// about 2 N instructions instead of 6 per value.  Lane bit 4 and 5 (rows, halves of the
+// wave) go through the register-pair swaps, bit 3 and 2 through DPP with a bank mask
+// (one instruction per kept half), the last one or two steps (bits 0, 1, and 2 when
+// N = 8) reduce the one remaining value over all lanes of a group.  All 64 lanes must
+// be active.
+__device__ inline float swap_min_rows(float a, float b) {      // rows 0, 2: a over the row pair; rows 1, 3: b
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-template <bool IS_MAX>
-__device__ inline float wave_allreduce(float v) {
-  auto op = [](float x, float y) { return IS_MAX ? fmaxf(x, y) : fminf(x, y); };
-  v = op(v, dpp_move<0xB1, 0xF>(v));    // quad_perm [1,0,3,2]
-  v = op(v, dpp_move<0x4E, 0xF>(v));    // quad_perm [2,3,0,1]
-  v = op(v, dpp_move<0x141, 0xF>(v));   // row_half_mirror
-  v = op(v, dpp_move<0x140, 0xF>(v));   // row_mirror: every lane of a 16-lane row has the row result
-  v = op(v, dpp_move<0x142, 0xA>(v));   // row_bcast15 into rows 1 and 3
-  v = op(v, dpp_move<0x143, 0xC>(v));   // row_bcast31 into rows 2 and 3: lane 63 has the total
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+__device__ inline float swap_min_halves(float a, float b) {    // lanes 0-31: a over both halves; lanes 32-63: b
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+// (the two wait states are what a DPP read of a register needs after the vector
+// instruction that wrote it; the compiler does not look inside the block)
+__device__ inline float dpp_min_xor8_keep(float a, float b) {  // lanes 0-7 of a row: a; lanes 8-15: b
+  asm volatile("s_nop 1\n\t"
+               "v_min_f32_dpp %0, %0, %0 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+               "v_min_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xc" : "+v"(a) : "v"(b));
+  return a;
+}
+__device__ inline float dpp_min_mirror8_keep(float a, float b) {  // lanes 0-3 of every eight: a; lanes 4-7: b
+  asm volatile("s_nop 1\n\t"
+               "v_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+               "v_min_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xa" : "+v"(a) : "v"(b));
+  return a;
+}
+__device__ inline float dpp_min_mirror8(float a) {
+  asm volatile("s_nop 1\n\tv_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf" : "+v"(a));
+  return a;
+}
+__device__ inline float dpp_min_quad(float a) {
+  asm volatile("s_nop 1\n\t"
+               "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+               "s_nop 1\n\t"
+               "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "+v"(a));
+  return a;
+}
+template <int N>
+__device__ inline int value_of_lane(int lane) {
+  const int b2 = (lane >> 2) & 1, b3 = (lane >> 3) & 1, b4 = (lane >> 4) & 1, b5 = (lane >> 5) & 1;
+  return N == 16 ? 8 * b4 + 4 * b5 + 2 * b3 + b2 : 4 * b4 + 2 * b5 + b3;
+}
+template <int N>
+__device__ inline float wave_min_many(float (&v)[N]) {
+  static_assert(N == 8 || N == 16, "two values (min, -max) for 4 or 8 tokens");
+#pragma unroll
+  for (int j = 0; j < N / 2; ++j) v[j] = swap_min_rows(v[j], v[j + N / 2]);
+#pragma unroll
+  for (int j = 0; j < N / 4; ++j) v[j] = swap_min_halves(v[j], v[j + N / 4]);
+#pragma unroll
+  for (int j = 0; j < N / 8; ++j) v[j] = dpp_min_xor8_keep(v[j], v[j + N / 8]);
+  float r;
+  if constexpr (N == 16) r = dpp_min_mirror8_keep(v[0], v[1]);
+  else r = dpp_min_mirror8(v[0]);
+  return dpp_min_quad(r);
 }
 
 __device__ inline int tile_of_field_group(int bits, int jf) {
@@ -324,24 +370,26 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
       }
     }
     if constexpr (TOKWISE) {
-      // (min, -max) of every token over the wave
-      float lo[TBAT], nhi[TBAT];
+      // (min, -max) of every token over the wave: values 0 .. TBAT-1 the minima,
+      // TBAT .. 2 TBAT-1 the negated maxima
+      float mm[2 * TBAT];
 #pragma unroll
       for (int t = 0; t < TBAT; ++t) {
         float l = xs[t][0], hneg = -xs[t][0];
 #pragma unroll
         for (int i = 1; i < 8; ++i) { l = fminf(l, xs[t][i]); hneg = fminf(hneg, -xs[t][i]); }
         if (!vvalid) { l = INFINITY; hneg = INFINITY; }
-        lo[t] = wave_allreduce<false>(l);
-        nhi[t] = wave_allreduce<false>(hneg);
+        mm[t] = l;
+        mm[TBAT + t] = hneg;
       }
+      const float wmin = wave_min_many<2 * TBAT>(mm);
       // through LDS: lane j < 16 ends up with value j (min of token j, or -max of token j - 8)
       // over all waves.  One barrier per batch: the scratch alternates, and the barrier
       // of the next batch separates these reads from the writes of the batch after it.
       float* mine = &red[parity][wave][0];
-      if (lane == 0) {
-#pragma unroll
-        for (int t = 0; t < TBAT; ++t) { mine[t] = lo[t]; mine[8 + t] = nhi[t]; }
+      if ((lane & 3) == 0) {
+        const int vi = value_of_lane<2 * TBAT>(lane);
+        mine[vi < TBAT ? vi : 8 + vi - TBAT] = wmin;
       }
       if (nwaves > 1) __syncthreads();
       float r = red[parity][0][lane & 15];

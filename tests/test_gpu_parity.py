@@ -225,6 +225,43 @@ def test_quantize_empty_subsets_and_degenerate_rows():
             assert P.chunks == [(0, k, 0, L - k)]
 
 
+def test_quantize_randomized_shapes():
+    """Seeded random shapes of zc_quantize_pack against the oracle: row widths from a
+    fraction of a wave to ten waves (teams with a ragged last wave included), all three
+    schemes, both layouts, every bit-width pair, all three input types, ragged subsets."""
+    from tests.pipeline_check import compare_subset, packed_to_chunks
+    rng = np.random.default_rng(20240521)
+    total = mism = 0
+    for case in range(24):
+        D = int(rng.choice([64, 128]))
+        H = int(rng.choice([1, 2, 3, 5, 8, 12, 40] if D == 128 else [1, 3, 8, 9, 16]))
+        B = int(rng.integers(1, 4)) if H * D <= 2048 else 1
+        L = int(rng.integers(1, 300))
+        k = int(rng.integers(0, L + 1))
+        dtype = [torch.float32, torch.float16, torch.bfloat16][case % 3]
+        bits_hi, bits_lo = [(4, 2), (8, 4), (2, 2), (8, 2)][int(rng.integers(0, 4))]
+        scheme, layout = [("cst", zb.ZC_LAYOUT_TGROUP), ("channel", zb.ZC_LAYOUT_ROW), ("token", zb.ZC_LAYOUT_ROW),
+                          ("cst", zb.ZC_LAYOUT_ROW), ("channel", zb.ZC_LAYOUT_TGROUP)][case % 5]
+        g = torch.Generator().manual_seed(1000 + case)
+        X = (torch.randn(B, H, L, D, generator=g) * (1 + 9 * (torch.rand(1, H, 1, D, generator=g) > 0.9))).to(dtype)
+        perm = torch.stack([torch.randperm(L, generator=g) for _ in range(B)])
+        sal = perm[:, :k].sort(dim=1).values.to(torch.int32)
+        reg = perm[:, k:].sort(dim=1).values.to(torch.int32)
+        cap = zb.load().zc_arena_slots(L, 1)
+        P = zb.PackedTensor(B, H, D, cap, cap, bits_hi, bits_lo, scheme, layout, max_chunks=1, device=DEV)
+        what = f"case {case}: B={B} H={H} D={D} L={L} k={k} {dtype} {bits_hi}/{bits_lo} {scheme} layout={layout}"
+        print(what, flush=True)
+        zb.zc_quantize_pack(X.to(DEV), sal.to(DEV), reg.to(DEV), P)
+        torch.cuda.synchronize()
+        got = packed_to_chunks(P, list(range(B)))[0]
+        ref = zo.compress_tensor(X.double().numpy(), sal.numpy(), reg.numpy(), bits_hi, bits_lo, scheme)
+        for name, a, b in (("hi", got.hi, ref.hi), ("lo", got.lo, ref.lo)):
+            r = compare_subset(a, b, f"{what} {name}")
+            total += r["n_codes"]
+            mism += r["n_mismatch"]
+    assert mism <= 1e-4 * total, (mism, total)
+
+
 @pytest.mark.parametrize("bits_hi,bits_lo", [(4, 2), (8, 4), (2, 2)])
 def test_unpack_inverts_the_packing(bits_hi, bits_lo):
     # zc_unpack against the reference decoder written from the header (tests/packfmt.py)
