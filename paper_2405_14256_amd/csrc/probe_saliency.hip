@@ -466,7 +466,7 @@ using namespace zc;
 // column ranges per row block of sweep 1: enough workgroups to fill the chip
 static int probe_splits(int64_t B, int64_t Hq, int64_t P) {
   const int64_t wgs = B * Hq * ceil_div64(P, kLseRows);
-  int64_t ns = 1024 / wgs;      // four workgroups fit a CU
+  int64_t ns = 768 / wgs;       // three workgroups fit a CU: one round of them
   return (int)(ns < 1 ? 1 : (ns > kMaxProbeSplit ? kMaxProbeSplit : ns));
 }
 static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * (kMaxProbeSplit * (int64_t)sizeof(float2) + 4), 256); }
