@@ -37,7 +37,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per decode call from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for a plain 256 MiB copy); the summary of those runs and their
 # commands are in profiles/decode_traffic_llama3_8b_4k.txt.  Not measurable from inside this script.
-MEASURED_DECODE_TRAFFIC = {"llama3_8b_4k": 5311249.0}
+MEASURED_DECODE_TRAFFIC = {"llama3_8b_4k": 4963231.0}
 FLUSH_INTERVAL = 100
 
 
