@@ -188,8 +188,8 @@ __global__ __launch_bounds__(256) void k_chan_finalize(QPArgs a) {
 }
 
 // ---- minima of N values over a wave at once -----------------------------------------
-// Every lane brings N = 8 or 16 values; afterwards lane l holds the minimum over the
-// wave of value number value_of_lane<N>(l).  Each step halves the values a lane still
+// Every lane brings N = 8 or 16 values (value j + N / 2 paired with value j in the first
+// step); afterwards lane l holds the minimum over the wave of value number value_of_lane<N>(l).  Each step halves the values a lane still
 // carries: two lanes that differ in one bit of the lane number exchange the half the
 // other one keeps and reduce the half they keep themselves, so the whole reduction is
 // about 2 N instructions instead of 6 per value.  Lane bit 4 and 5 (rows, halves of the
@@ -235,11 +235,11 @@ __device__ inline int value_of_lane(int lane) {
   const int b2 = (lane >> 2) & 1, b3 = (lane >> 3) & 1, b4 = (lane >> 4) & 1, b5 = (lane >> 5) & 1;
   return N == 16 ? 8 * b4 + 4 * b5 + 2 * b3 + b2 : 4 * b4 + 2 * b5 + b3;
 }
+// v[j] holds value j in the even rows of the wave and value j + N / 2 in the odd rows,
+// already reduced over each row pair (swap_min_rows): the remaining steps.
 template <int N>
-__device__ inline float wave_min_many(float (&v)[N]) {
+__device__ inline float wave_min_rest(float (&v)[N / 2]) {
   static_assert(N == 8 || N == 16, "two values (min, -max) for 4 or 8 tokens");
-#pragma unroll
-  for (int j = 0; j < N / 2; ++j) v[j] = swap_min_rows(v[j], v[j + N / 2]);
 #pragma unroll
   for (int j = 0; j < N / 4; ++j) v[j] = swap_min_halves(v[j], v[j + N / 4]);
 #pragma unroll
@@ -372,17 +372,18 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
     if constexpr (TOKWISE) {
       // (min, -max) of every token over the wave: values 0 .. TBAT-1 the minima,
       // TBAT .. 2 TBAT-1 the negated maxima
-      float mm[2 * TBAT];
+      // (the first step - rows - pairs a token's minimum with its negated maximum, so
+      // it is taken as soon as the two exist: TBAT registers live, not 2 TBAT)
+      float mm[TBAT];
 #pragma unroll
       for (int t = 0; t < TBAT; ++t) {
         float l = xs[t][0], hneg = -xs[t][0];
 #pragma unroll
         for (int i = 1; i < 8; ++i) { l = fminf(l, xs[t][i]); hneg = fminf(hneg, -xs[t][i]); }
         if (!vvalid) { l = INFINITY; hneg = INFINITY; }
-        mm[t] = l;
-        mm[TBAT + t] = hneg;
+        mm[t] = swap_min_rows(l, hneg);
       }
-      const float wmin = wave_min_many<2 * TBAT>(mm);
+      const float wmin = wave_min_rest<2 * TBAT>(mm);
       // through LDS: lane j < 16 ends up with value j (min of token j, or -max of token j - 8)
       // over all waves.  One barrier per batch: the scratch alternates, and the barrier
       // of the next batch separates these reads from the writes of the batch after it.
