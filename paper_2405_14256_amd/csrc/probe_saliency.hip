@@ -98,6 +98,14 @@ __device__ inline int acc_row(int v, int kh) { return 8 * (v >> 2) + 4 * kh + (v
 constexpr int kBufFlags = 0x00020000;          // raw 32-bit data, no swizzle
 constexpr int kOutOfRange = (int)0xFFFFF000u;  // a per-lane offset past the end of every admitted buffer
 
+// The tile transfers (inline assembly) are invisible to the compiler, ordinary loads - the
+// stationary operand before the loop, table look-ups inside it - are tracked by it.  If it
+// believes one of "its" loads may still be in flight somewhere in the tile loop it waits for
+// it with a count that also covers the transfers of the next tile, issued just before: the
+// prefetch is waited for at once.  A wait it understands (all vector-memory loads of the
+// wave done), where the loop waits for its transfers anyway, leaves it nothing to wait for.
+__device__ inline void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0) only
+
 constexpr int kLseRows = 128;                  // probe rows per workgroup of sweep 1
 constexpr int kLseCols = 64;                   // columns per K tile of sweep 1
 
@@ -178,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void k_probe_lse(ProbeArgs a) {
 
   for (int t = t_begin; t < t_end; ++t) {
     const int cur = (t - t_begin) & 1;
-    wait_vmem<0>();      // this wave's transfers of tile t have landed ...
+    wait_all_loads();    // this wave's transfers of tile t have landed ...
     __syncthreads();     // ... and everyone's; nobody still reads the other buffer
     if (t + 1 < t_end) issue(t + 1, cur ^ 1);
     if (t * kLseCols > pos_last) continue;       // nothing of this tile is visible to the wave's rows
@@ -347,17 +355,27 @@ __global__ __launch_bounds__(256, (DT == ZC_F32 && D == 128) ? 1 : 2) void k_pro
   const uint32_t spos_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&spos[0][0];
   const uint32_t slse_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)&slse[0][0];
   auto issue = [&](int pr, int buf) {
+    // the rows of q this lane fetches: from the LDS table, or from memory (uniform branches
+    // over pointers of known address space: never a read through a generic pointer); the
+    // reads from memory are waited for here, where their values are needed anyway, so that
+    // the compiler carries no load of its own into the rest of the loop (see wait_all_loads)
+    uint32_t qrow[NI];
+    if (rows_in_lds) {
+#pragma unroll
+      for (int jj = 0; jj < NI; ++jj) qrow[jj] = (uint32_t)lds_tab[min(pr + (w + 4 * jj) * T::RPI + lane / T::CPR, a.P - 1)];
+    } else {
+#pragma unroll
+      for (int jj = 0; jj < NI; ++jj) {
+        const int pc = min(pr + (w + 4 * jj) * T::RPI + lane / T::CPR, a.P - 1);
+        qrow[jj] = a.probe_rows ? (uint32_t)g_rows[pc] : (uint32_t)g_pos[pc];
+      }
+      wait_all_loads();
+    }
 #pragma unroll
     for (int jj = 0; jj < NI; ++jj) {
       const int row = (w + 4 * jj) * T::RPI + lane / T::CPR;
-      const int p = pr + row, pc = min(p, a.P - 1);
-      uint32_t qrow;
-      // (uniform branches over pointers of known address space: an LDS read or a global
-      // one, never one through a generic pointer)
-      if (rows_in_lds) qrow = (uint32_t)lds_tab[pc];
-      else if (a.probe_rows) qrow = (uint32_t)g_rows[pc];
-      else qrow = (uint32_t)g_pos[pc];
-      const int voff = p < a.P ? (int)(qrow * q_rowb) + (((lane % T::CPR) ^ T::swz(row)) << 4) : kOutOfRange;
+      const int p = pr + row;
+      const int voff = p < a.P ? (int)(qrow[jj] * q_rowb) + (((lane % T::CPR) ^ T::swz(row)) << 4) : kOutOfRange;
       dma16<0>(qs_lds + buf * TILE_B + (w + 4 * jj) * 1024, rs_q, voff, 0);
     }
     if (w == 0) {
@@ -370,7 +388,7 @@ __global__ __launch_bounds__(256, (DT == ZC_F32 && D == 128) ? 1 : 2) void k_pro
 
   for (int pr = pstart; pr < a.P; pr += QT) {
     const int cur = ((pr - pstart) / QT) & 1;
-    wait_vmem<0>();      // this wave's transfers of the tile have landed ...
+    wait_all_loads();    // this wave's transfers of the tile have landed ...
     __syncthreads();     // ... and everyone's; nobody still reads the other buffer
     if (pr + QT < a.P) issue(pr + QT, cur ^ 1);
     float rl[16];

@@ -442,6 +442,30 @@ def test_decode_same_answer_under_any_split():
     assert (outs[1] - outs[0]).abs().max() <= 2.0 ** -7 * outs[0].abs().max()    # one bf16 rounding step at most
 
 
+def test_machine_peak_probes_run_and_copy_exactly():
+    """The probes of bench.py --peaks: the copy is exact (ragged size, loop tail included), the
+    read and the matrix-instruction loop launch and finish."""
+    import ctypes as C
+    import os
+    lib = C.CDLL(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                              "paper_2405_14256_amd", "libzc_peaks.so"))
+    lib.zc_peak_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.zc_peak_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.zc_peak_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    st = torch.cuda.current_stream().cuda_stream
+    n = (37 << 20) + 16 * 12345                      # bytes: not a multiple of the grid's stride
+    src = torch.randint(0, 2 ** 31 - 1, (n // 4,), dtype=torch.int32, device=DEV)
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(16, dtype=torch.float32, device=DEV)
+    assert lib.zc_peak_copy(dst.data_ptr(), src.data_ptr(), n, st) == 0
+    assert lib.zc_peak_read(src.data_ptr(), n, sink.data_ptr(), st) == 0
+    assert lib.zc_peak_mfma(2, 64, 8, sink.data_ptr(), st) == 0
+    assert lib.zc_peak_mfma(1, 64, 8, sink.data_ptr(), st) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert float(sink.abs().sum()) == 0.0
+
+
 def test_results_are_deterministic():
     w = scaled(WORKLOADS["llama3_8b_4k"], L=900)
     from paper_2405_14256_amd import probes
