@@ -481,10 +481,16 @@ static int launch_probe(const ProbeArgs& a, bool need_lse, float* scores, hipStr
 
 using namespace zc;
 
-// column ranges per row block of sweep 1: enough workgroups to fill the chip
-static int probe_splits(int64_t B, int64_t Hq, int64_t P) {
+// Column ranges per row block of sweep 1.  Enough workgroups to fill the chip once (three fit
+// a CU); and, however many there are, up to four ranges of at least 16 tiles each: a row block
+// near the end of a long prompt sees ten times the columns of one near the start, and whole
+// row blocks as units leave the chip half empty while the long ones finish.
+static int probe_splits(int64_t B, int64_t Hq, int64_t P, int64_t Lk) {
   const int64_t wgs = B * Hq * ceil_div64(P, kLseRows);
-  int64_t ns = 768 / wgs;       // three workgroups fit a CU: one round of them
+  const int64_t fill = 768 / wgs;
+  int64_t even = ceil_div64(Lk, kLseCols) / 16;
+  if (even > 4) even = 4;
+  const int64_t ns = fill > even ? fill : even;
   return (int)(ns < 1 ? 1 : (ns > kMaxProbeSplit ? kMaxProbeSplit : ns));
 }
 static size_t lse_bytes(int64_t B, int64_t Hq, int64_t P) { return (size_t)align_up64(B * Hq * P * (kMaxProbeSplit * (int64_t)sizeof(float2) + 4), 256); }
@@ -530,7 +536,7 @@ static int probe_scores(const zc_tensor4* q, const zc_tensor4* k,
   a.lse_in = lse_ext;
   a.lse_part = reinterpret_cast<float2*>(ws);
   a.lse2 = reinterpret_cast<float*>(a.lse_part + (int64_t)q->B * q->H * P * kMaxProbeSplit);
-  a.nsplit = probe_splits(q->B, q->H, P);
+  a.nsplit = probe_splits(q->B, q->H, P, k->L);
   if ((int64_t)ceil_div64(P, kLseRows) * q->H * q->B * a.nsplit > 0x7fffffff || (int64_t)ceil_div64(k->L, 128) * q->H * q->B > 0x7fffffff)
     return ZC_ERR_UNSUPPORTED;
   a.per_head = scores_per_head ? scores_per_head : ws_ph;
