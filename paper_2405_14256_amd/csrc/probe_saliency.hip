@@ -3,19 +3,22 @@
 //
 // The probe rows of A = Softmax(Q_probe K^T / sqrt(d)) are never stored.  Two
 // matrix-core sweeps recompute the logits instead:
-//   k_probe_lse     one workgroup per 64 probe rows and column range (the columns a
-//                   row block can see are split over up to 8 workgroups when the
-//                   launch would not fill the chip): streams 128-column K tiles
-//                   through LDS (the next tile's loads in flight), logits come
-//                   out of the MFMA as D[column][row] so that every lane owns one
-//                   probe row and keeps its running (max, sum) in two registers;
-//                   writes the (max, sum) pair per row and column range.
+//   k_probe_lse     one workgroup per 128 probe rows and column range (the columns a
+//                   row block can see are cut into up to 8 ranges: to fill the chip
+//                   when the launch is small, and to even out row blocks that see
+//                   very different numbers of columns): the probe rows sit in
+//                   registers as matrix operands, 64-column K tiles stream through
+//                   LDS (global -> LDS transfers, the next tile's in flight), logits
+//                   come out of the MFMA as D[column][row] so that every lane owns
+//                   one probe row and keeps its running (reference, sum) in two
+//                   registers; writes the pair per row and column range
+//                   (k_probe_lse_merge joins the ranges).
 //   k_probe_colsum  one workgroup per 128 key columns: K fragments stay in
-//                   registers, 64-row probe tiles stream through LDS (merging the
-//                   (max, sum) pairs of a row into its log-sum-exp on the way), logits
-//                   come out as D[row][column] so that every lane owns one
-//                   column and sums exp(logit - lse) over the rows in registers;
-//                   divides by the number of probes that can see the column.
+//                   registers, 64-row probe tiles stream through LDS with their
+//                   positions and log-sum-exps, logits come out as D[row][column] so
+//                   that every lane owns one column and sums exp(logit - lse) over
+//                   the rows in registers; divides by the number of probes that can
+//                   see the column.
 //   k_probe_mean    mean over query heads.
 // Causality: rows are sorted by position, so a column tile starts at the first
 // probe that can see it and a row tile stops at its last row's position.
