@@ -31,6 +31,13 @@
  *     elements.
  *   - Supported: head dimension D in {64, 128}; dtypes f32, f16, bf16;
  *     code widths in {2, 4, 8}; Hq a multiple of Hkv with Hq/Hkv <= 8.
+ *   - Size limits (beyond them a call returns ZC_ERR_UNSUPPORTED and launches
+ *     nothing): B <= 65535 and heads <= 65535; a token row of a cache tensor at
+ *     most 8192 channels (W = H*D) in zc_quantize_pack; the kernels address one
+ *     (batch, head) slab with 32-bit byte offsets, so the span of such a slab -
+ *     L * sL elements of q, (L + 128) * sL of k in the probe calls, tail_len * sL
+ *     of the tail, cap * D * bits / 8 bytes of a code arena in the decode call -
+ *     must stay below 4 GiB - 4 KiB.
  */
 #ifndef ZIPCACHE_H
 #define ZIPCACHE_H
@@ -45,7 +52,7 @@ extern "C" {
 typedef enum {
   ZC_OK = 0,
   ZC_ERR_INVALID_ARG = -1, /* null / misaligned pointer, bad size or stride  */
-  ZC_ERR_UNSUPPORTED = -2, /* dtype, head dim, bit width, scheme not built   */
+  ZC_ERR_UNSUPPORTED = -2, /* dtype, head dim, bit width, scheme, size limit  */
   ZC_ERR_WORKSPACE = -3,   /* workspace smaller than the *_workspace() size  */
   ZC_ERR_CAPACITY = -4,    /* arena or chunk table of a zc_packed is full    */
   ZC_ERR_HIP = -5          /* the HIP runtime refused a launch               */
