@@ -179,11 +179,18 @@ __global__ __launch_bounds__(256, 2) void k_probe_lse(ProbeArgs a) {
   }
   if (tid < kLseRows) spos[tid] = (rb0 + tid < a.P) ? a.probe_pos[rb0 + tid] : -1;
   __syncthreads();
-  // rows are sorted by position: the wave's first row bounds what is fully visible,
+  // rows are sorted by position: a block's first row bounds what is fully visible,
   // its last real row what is visible at all
-  const int pos_first = spos[rh * 64];
   int pos_last = -1;
   if (rb0 + rh * 64 < a.P) pos_last = spos[min(rh * 64 + 63, nvalid - 1)];
+  // the same per 32-row block: its first row's position (-1: no row) and its last real row's
+  int pfirst[2], plast[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int base = rh * 64 + rb * 32;
+    pfirst[rb] = spos[base];
+    plast[rb] = rb0 + base < a.P ? spos[min(base + 31, nvalid - 1)] : -1;
+  }
   float m[2] = {-INFINITY, -INFINITY}, z[2] = {0.f, 0.f};
   const int krow = ch * 32 + r;                  // this lane's column inside a tile
 
@@ -202,11 +209,11 @@ __global__ __launch_bounds__(256, 2) void k_probe_lse(ProbeArgs a) {
       mma_chunk<DT>(acc[0], af, qf[0][kc]);
       mma_chunk<DT>(acc[1], af, qf[1][kc]);
     }
-    const int colb = t * kLseCols + ch * 32;
-    const bool tile_full = t * kLseCols + kLseCols - 1 <= pos_first;
+    const int colb = t * kLseCols + ch * 32;     // this wave's 32 columns of the tile
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-      if (tile_full) {
+      if (colb > plast[rb]) continue;            // none of them visible to this block's rows
+      if (colb + 31 <= pfirst[rb]) {
         // Every logit of the tile counts.  The reference point m of a row only has to keep
         // exp2 in range, not to be the maximum: it is taken from the row's first tile
         // and moved only when a tile's sum shows that some logit lies 2^60 above it
