@@ -26,7 +26,7 @@ import torch
 from oracle import zipcache_oracle as zo
 from paper_2405_14256_amd import binding as zb
 from paper_2405_14256_amd import probes
-from paper_2405_14256_amd.workloads import Workload, make_decode_step, make_prefill, to_f64
+from paper_2405_14256_amd.workloads import Workload, make_decode_step, make_prefill, needle_positions, to_f64
 from tests import packfmt
 
 SCORE_RTOL = 1e-4
@@ -176,6 +176,16 @@ def run_pipeline_check(w: Workload, decode_steps: Optional[int] = None, bsel: Op
     rep["salient_overlap"] = float(np.mean([len(set(sal_np[b]) & set(zo.select_salient(scores_o[i], k)[0])) / max(k, 1)
                                             for i, b in enumerate(bsel)]))
     log(f"select: exact on fp32 scores; overlap with oracle set {rep['salient_overlap']:.5f}")
+    # the structure the inputs were given must come out as salient, in the oracle and on the GPU:
+    # the attention sink (token 0) and every needle (keys aligned with the recent queries)
+    must = ([0] if w.sink else []) + [int(p) for p in needle_positions(w)]
+    for i, b in enumerate(bsel):
+        sal_o = set(zo.select_salient(scores_o[i], k)[0].tolist())
+        sal_b = set(sal_np[b].tolist())
+        missing = [p for p in must if p not in sal_o or p not in sal_b]
+        assert not missing, f"b={b}: tokens {missing} should be salient (sink / needles)"
+    if must:
+        log(f"select: sink / needle tokens salient in the oracle and on the GPU ({len(must)} of them)")
 
     # ---- quantize + pack -----------------------------------------------------------
     n_flush = (steps // flush_interval) if flush_interval else 0
