@@ -268,7 +268,7 @@ constexpr int kVPT = 1;  // channel vectors (8 channels each) per thread in the 
 //   parameters of tokens 0..7 of the batch, once, and broadcast them.
 //   codes are assembled in float: sum of code * 2^(bits * position) over a 16-bit
 //   group is exact in fp32, so packing costs one FMA per code.
-template <int DT, int BITS, int LAYOUT, bool TOKWISE, bool PIPE>
+template <int DT, int BITS, int LAYOUT, bool TOKWISE, bool EXACT, bool PIPE>
 __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int b, float (*red)[16][16], int32_t* sidx) {
   constexpr int E = 32 / BITS;                       // tokens of a word group
   constexpr int TBAT = E < 8 ? E : 8;                // tokens per batch
@@ -361,6 +361,7 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
 
     float xs[TBAT][8];                               // tokenwise: x' = x / c; channelwise: x
     float sinv[TBAT], zt[TBAT];
+    float rt[TBAT], yt[TBAT];                        // EXACT (the plain tokenwise scheme) only: range and its reciprocal
 #pragma unroll
     for (int t = 0; t < TBAT; ++t) {
       widen(bt, t, xs[t]);
@@ -411,9 +412,22 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
       for (int t = 0; t < TBAT; ++t) {
         sinv[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(si), t));
         zt[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z), t));
+        if constexpr (EXACT) {
+          rt[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(R), t));
+          yt[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y), t));
+        }
       }
     }
 
+    // Code of a tokenwise element before clipping.  With channel normalization x' = x / c is
+    // not on a grid and a plain product decides the rounding; without it (the plain tokenwise
+    // scheme, c = 1) 16-bit inputs sit on a grid where x (2^k - 1) / R hits n + 1/2 exactly
+    // about once in 10^4 elements, so the quotient is the tie-exact one there.
+    auto tok_code = [&](float xv, int t) {
+      if constexpr (!EXACT) return rintf(xv * sinv[t]) + zt[t];
+      else if constexpr (DT == ZC_F32) return rintf(refined_ratio(xv, QMAX, rt[t], yt[t])) + zt[t];
+      else return rintf(refined_div(xv * QMAX, rt[t], yt[t])) + zt[t];      // x * qmax is exact
+    };
     if (!vvalid) return;
 #pragma unroll
     for (int t = 0; t < TBAT; ++t) {
@@ -422,7 +436,7 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         float qv;
-        if constexpr (TOKWISE) qv = rintf(xs[t][i] * sinv[t]) + zt[t];
+        if constexpr (TOKWISE) qv = tok_code(xs[t][i], t);
         else if constexpr (DT == ZC_F32) qv = rintf(refined_ratio(xs[t][i], QMAX, p2[i], p0[i])) + p1[i];
         else qv = rintf(refined_div(xs[t][i] * QMAX, p2[i], p0[i])) + p1[i];   // x * qmax is exact
         code[i] = __builtin_amdgcn_fmed3f(qv, 0.f, QMAX);
@@ -467,7 +481,7 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
           for (int f = 0; f < TPG; ++f) {
             const int t = g * TPG + f;
             float qv;
-            if constexpr (TOKWISE) qv = rintf(xs[t][i] * sinv[t]) + zt[t];
+            if constexpr (TOKWISE) qv = tok_code(xs[t][i], t);
             else if constexpr (DT == ZC_F32) qv = rintf(refined_ratio(xs[t][i], QMAX, p2[i], p0[i])) + p1[i];
             else qv = rintf(refined_div(xs[t][i] * QMAX, p2[i], p0[i])) + p1[i];
             acc = fmaf(__builtin_amdgcn_fmed3f(qv, 0.f, QMAX), mult[t], acc);
@@ -509,7 +523,8 @@ __device__ inline void quant_units(const QPArgs& a, int sub, int g0, int ng, int
 
 // MAXT: most threads of a workgroup (W / 8 rounded up to a wave); it bounds the
 // registers of a thread, and with them whether two batches of rows fit.
-template <int DT, int LAYOUT, bool TOKWISE, int MAXT>
+// EXACT: tokenwise without channel normalization (the plain tokenwise scheme): tie-exact codes.
+template <int DT, int LAYOUT, bool TOKWISE, bool EXACT, int MAXT>
 __global__ __launch_bounds__(MAXT) void k_quant_pack(QPArgs a) {
   constexpr bool PIPE = (DT != ZC_F32) && MAXT <= 768;
   __shared__ float red[2][16][16];   // [turn][wave][min of token 0..7, -max of token 0..7]
@@ -520,20 +535,21 @@ __global__ __launch_bounds__(MAXT) void k_quant_pack(QPArgs a) {
   if (sub) wg -= a.wgs[0];
   const int g0 = wg * a.upw, ng = a.upw;
   const int bits = a.bits[sub];
-  if (bits == 4) quant_units<DT, 4, LAYOUT, TOKWISE, PIPE>(a, sub, g0, ng, b, red, sidx);
-  else if (bits == 2) quant_units<DT, 2, LAYOUT, TOKWISE, PIPE>(a, sub, g0, ng, b, red, sidx);
-  else quant_units<DT, 8, LAYOUT, TOKWISE, PIPE>(a, sub, g0, ng, b, red, sidx);
+  if (bits == 4) quant_units<DT, 4, LAYOUT, TOKWISE, EXACT, PIPE>(a, sub, g0, ng, b, red, sidx);
+  else if (bits == 2) quant_units<DT, 2, LAYOUT, TOKWISE, EXACT, PIPE>(a, sub, g0, ng, b, red, sidx);
+  else quant_units<DT, 8, LAYOUT, TOKWISE, EXACT, PIPE>(a, sub, g0, ng, b, red, sidx);
 }
 
+template <int DT, int LAYOUT, int MAXT>
+static void launch_qp_l(const QPArgs& a, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
+  if (!tokwise) hipLaunchKernelGGL((k_quant_pack<DT, LAYOUT, false, false, MAXT>), grid, block, 0, st, a);
+  else if (a.scheme == ZC_SCHEME_TOKEN) hipLaunchKernelGGL((k_quant_pack<DT, LAYOUT, true, true, MAXT>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((k_quant_pack<DT, LAYOUT, true, false, MAXT>), grid, block, 0, st, a);
+}
 template <int DT, int MAXT>
 static void launch_qp_t(const QPArgs& a, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
-  if (layout == ZC_LAYOUT_ROW) {
-    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, true, MAXT>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_ROW, false, MAXT>), grid, block, 0, st, a);
-  } else {
-    if (tokwise) hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, true, MAXT>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_quant_pack<DT, ZC_LAYOUT_TGROUP, false, MAXT>), grid, block, 0, st, a);
-  }
+  if (layout == ZC_LAYOUT_ROW) launch_qp_l<DT, ZC_LAYOUT_ROW, MAXT>(a, tokwise, grid, block, st);
+  else launch_qp_l<DT, ZC_LAYOUT_TGROUP, MAXT>(a, tokwise, grid, block, st);
 }
 template <int DT>
 static void launch_qp(const QPArgs& a, int layout, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {

@@ -262,6 +262,32 @@ def test_quantize_randomized_shapes():
     assert mism <= 1e-4 * total, (mism, total)
 
 
+def test_plain_tokenwise_codes_are_tie_exact():
+    """Without channel normalization (scheme "token", c = 1) 16-bit inputs sit on a grid where
+    x / s lands on n + 1/2 exactly about once in 10^4 elements: the codes must still be the
+    oracle's (round half to even on the exact quotient), for both 16-bit types and layouts."""
+    from tests.pipeline_check import compare_subset, packed_to_chunks
+    B, H, L, D, k = 2, 4, 1500, 64, 600
+    total = 0
+    for dtype, layout in ((torch.bfloat16, zb.ZC_LAYOUT_ROW), (torch.float16, zb.ZC_LAYOUT_TGROUP), (torch.bfloat16, zb.ZC_LAYOUT_TGROUP)):
+        g = torch.Generator().manual_seed(31)
+        X = torch.randn(B, H, L, D, generator=g).to(dtype)
+        perm = torch.stack([torch.randperm(L, generator=g) for _ in range(B)])
+        sal = perm[:, :k].sort(dim=1).values.to(torch.int32)
+        reg = perm[:, k:].sort(dim=1).values.to(torch.int32)
+        cap = zb.load().zc_arena_slots(L, 1)
+        P = zb.PackedTensor(B, H, D, cap, cap, 4, 2, "token", layout, max_chunks=1, device=DEV)
+        zb.zc_quantize_pack(X.to(DEV), sal.to(DEV), reg.to(DEV), P)
+        torch.cuda.synchronize()
+        got = packed_to_chunks(P, list(range(B)))[0]
+        ref = zo.compress_tensor(X.double().numpy(), sal.numpy(), reg.numpy(), 4, 2, "token")
+        for name, a, b in (("hi", got.hi, ref.hi), ("lo", got.lo, ref.lo)):
+            r = compare_subset(a, b, f"token {dtype} layout={layout} {name}")
+            assert r["n_mismatch"] == 0, (dtype, layout, name, r)
+            total += r["n_codes"]
+    assert total == 3 * B * L * H * D
+
+
 @pytest.mark.parametrize("bits_hi,bits_lo", [(4, 2), (8, 4), (2, 2)])
 def test_unpack_inverts_the_packing(bits_hi, bits_lo):
     # zc_unpack against the reference decoder written from the header (tests/packfmt.py)
