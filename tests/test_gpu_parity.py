@@ -492,6 +492,29 @@ def test_machine_peak_probes_run_and_copy_exactly():
     assert float(sink.abs().sum()) == 0.0
 
 
+def test_pipeline_randomized_configurations():
+    """Seeded draws over what the single-purpose tests fix: input law (all five workloads,
+    scaled down), batch, heads and group size, K / V scheme (channelwise, CST, plain
+    tokenwise), bit-width pair, input type, with and without streaming flushes (interval 64
+    or 100) - the whole path against the oracle, every stage, at the usual bars."""
+    rng = np.random.default_rng(11)
+    names = ["tiny", "llama3_8b_4k", "mistral_7b_8k_b8", "llama2_13b_4k_b16", "llama3_8b_32k"]
+    for case in range(12):
+        base = WORKLOADS[names[int(rng.integers(len(names)))]]
+        G = int(rng.choice([1, 2, 4, 8])); Hkv = int(rng.choice([1, 2, 4])); B = int(rng.choice([1, 2, 3]))
+        L = int(rng.integers(120, 900))
+        fi = int(rng.choice([0, 100, 100, 64]))
+        steps = int(rng.integers(1, 12)) if not fi else int(fi * rng.integers(1, 3) + rng.integers(0, 20))
+        ks, vs = [("channel", "cst"), ("cst", "cst"), ("channel", "token"), ("token", "cst")][int(rng.integers(4))]
+        bh, bl = [(4, 2), (4, 2), (8, 4), (2, 2), (4, 4), (8, 2)][int(rng.integers(6))]
+        dt = ["bf16", "fp16", "fp32"][int(rng.integers(3))]
+        w = scaled(base, bits_hi=bh, bits_lo=bl, dtype=dt, B=B, Hq=Hkv * G, Hkv=Hkv, L=L, decode_steps=steps,
+                   index=base.index + 100 + case, needles=min(base.needles, 4))
+        print(f"case {case}: {base.name} B={B} Hq={Hkv * G} Hkv={Hkv} d={w.d} L={L} steps={steps} flush={fi} "
+              f"{ks}/{vs} bits={bh}/{bl} {dt}", flush=True)
+        run_pipeline_check(w, k_scheme=ks, v_scheme=vs, flush_interval=fi or None)
+
+
 def test_results_are_deterministic():
     w = scaled(WORKLOADS["llama3_8b_4k"], L=900)
     from paper_2405_14256_amd import probes
