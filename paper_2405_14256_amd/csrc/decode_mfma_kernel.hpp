@@ -302,9 +302,11 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // MODE 4 / 2: codes of that width, q' = q cs sm_scale log2(e) times the factor of
   // its operand register, in the channel order the unpacked K words have; MODE 0:
   // the tail, q itself in natural order.
-  // Returns the operand registers and sum(q'), sum(q' cz) over all channels.
+  // Returns the operand registers and sum(q'), sum(q' cz) over all channels, and the same
+  // two sums over the 32 channels of every k-step (what the normalized encoding needs to
+  // keep its accumulators centred, see the segment).
   auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, const float* vcs, const float* vcz,
-                                 u4 (&qB)[KS], float& sumqq, float& sumqqcz) {
+                                 u4 (&qB)[KS], float& sumqq, float& sumqqcz, float (&sum_k)[KS], float (&sumcz_k)[KS]) {
     constexpr int MODE = decltype(mode_c)::value;
     // q and the channel parameters of this lane's elements of every k-step, straight
     // from global memory (issued together with the first blocks' loads by the caller)
@@ -373,6 +375,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     float sq = 0.f, sqz = 0.f;
 #pragma unroll
     for (int ks0 = 0; ks0 < KS; ++ks0) {
+      const float sq_before = sq, sqz_before = sqz;
       uint32_t regs[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -400,6 +403,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         }
       }
       qB[ks0].x = regs[0]; qB[ks0].y = regs[1]; qB[ks0].z = regs[2]; qB[ks0].w = regs[3];
+      if constexpr (!SUBN && MODE != 0) {
+        sum_k[ks0] = grp_sum(sq - sq_before);
+        sumcz_k[ks0] = grp_sum(sqz - sqz_before);
+      } else {
+        sum_k[ks0] = 0.f; sumcz_k[ks0] = 0.f;
+      }
     }
     sumqq = grp_sum(sq);
     sumqqcz = grp_sum(sqz);
@@ -492,7 +501,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     if (kTwoUnits && wlo + 1 < whi) load_unit(wlo + 1, bf1);
     u4 qB[KS];
     float dummy0, dummy1;
-    build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, nullptr, nullptr, qB, dummy0, dummy1);
+    float dummy_k[KS], dummy_kz[KS];
+    build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, nullptr, nullptr, qB, dummy0, dummy1, dummy_k, dummy_kz);
     float Ot[MG][8];
 #pragma unroll
     for (int gg = 0; gg < MG; ++gg)
@@ -683,9 +693,23 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     for (int i = 0; i < kStages - 1; ++i) issue(ring_lds + i * kStageBytes, bl_lo + i, bl_lo + i < bl_hi);
 
     u4 qB[KS];
-    float Aq, sumqcz;
-    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz);
-    const float kconst = SUBN ? -sumqcz : -(SC * Aq + sumqcz);   // normalized codes: the "1" terms add SC sum(q')
+    float Aq, sumqcz, Aq_k[KS], sumqcz_k[KS];
+    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz, Aq_k, sumqcz_k);
+    // Subnormal codes: the logit is ts (dot - tz sum(q') - sum(q' cz)), the two sums taken off
+    // after the matrix instructions.  Normalized codes (fp32 tensors) add SC sum(q') to the
+    // accumulator on top; there everything that is taken off is taken off k-step by k-step,
+    // between the matrix instructions, so that the accumulator never holds more than one
+    // k-step's worth of what cancels: with fp64 as the yardstick a quarter of the rounding
+    // error when sum(q') is large (queries with a common component, a large token scale).
+    //   corr_c[ks] + tz corr_s[ks], in accumulator units; value column only (the residual
+    //   column is added to it afterwards)
+    const float kconst = SUBN ? -sumqcz : 0.f;
+    float corr_c[KS], corr_s[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      corr_c[ks] = (SUBN || part) ? 0.f : -(SC * Aq_k[ks] + sumqcz_k[ks]) * (1.f / UNSCALE);
+      corr_s[ks] = (SUBN || part) ? 0.f : -Aq_k[ks] * (1.f / UNSCALE);
+    }
     // factor of operand register v of the weights.  When the weights are not split,
     // the second row of a head carries p instead of w = p ts: its product with the
     // constants below is the sum of p (the softmax denominator), at no VALU cost
@@ -747,17 +771,23 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       float lg[2][4], vts[2][4], vtz[2][4];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        f4 sacc = f4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (BITS == 4) {
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack4<SUBN>(bf.kw[jj][ks]), qB[ks], sacc);
-        } else {
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) sacc = mfma16(unpack2<SUBN>(bf.kw[jj][ks >> 1], ks & 1), qB[ks], sacc);
-        }
-        const float own[4] = {sacc.x, sacc.y, sacc.z, sacc.w};
         const float kts[4] = {__uint_as_float(bf.kts[jj].x), __uint_as_float(bf.kts[jj].y), __uint_as_float(bf.kts[jj].z), __uint_as_float(bf.kts[jj].w)};
         const float ktz[4] = {__uint_as_float(bf.ktz[jj].x), __uint_as_float(bf.ktz[jj].y), __uint_as_float(bf.ktz[jj].z), __uint_as_float(bf.ktz[jj].w)};
+        f4 sacc = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          if constexpr (BITS == 4) sacc = mfma16(unpack4<SUBN>(bf.kw[jj][ks]), qB[ks], sacc);
+          else sacc = mfma16(unpack2<SUBN>(bf.kw[jj][ks >> 1], ks & 1), qB[ks], sacc);
+          if constexpr (!SUBN) {
+            if constexpr (KTOK) {
+              sacc.x += fmaf(ktz[0], corr_s[ks], corr_c[ks]); sacc.y += fmaf(ktz[1], corr_s[ks], corr_c[ks]);
+              sacc.z += fmaf(ktz[2], corr_s[ks], corr_c[ks]); sacc.w += fmaf(ktz[3], corr_s[ks], corr_c[ks]);
+            } else {
+              sacc.x += corr_c[ks]; sacc.y += corr_c[ks]; sacc.z += corr_c[ks]; sacc.w += corr_c[ks];
+            }
+          }
+        }
+        const float own[4] = {sacc.x, sacc.y, sacc.z, sacc.w};
         vts[jj][0] = __uint_as_float(bf.vts[jj].x); vts[jj][1] = __uint_as_float(bf.vts[jj].y);
         vts[jj][2] = __uint_as_float(bf.vts[jj].z); vts[jj][3] = __uint_as_float(bf.vts[jj].w);
         vtz[jj][0] = __uint_as_float(bf.vtz[jj].x); vtz[jj][1] = __uint_as_float(bf.vtz[jj].y);
@@ -766,7 +796,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         for (int v = 0; v < 4; ++v) {
           float x;
           const float dot = QSPLIT ? own[v] + xor1(own[v]) : own[v];     // value + residual column
-          if constexpr (KTOK) x = fmaf(kts[v], fmaf(-ktz[v], Aq, fmaf(dot, UNSCALE, kconst)), lshift[v]);
+          if constexpr (KTOK && !SUBN) x = fmaf(kts[v], dot * UNSCALE, lshift[v]);        // already centred
+          else if constexpr (KTOK) x = fmaf(kts[v], fmaf(-ktz[v], Aq, fmaf(dot, UNSCALE, kconst)), lshift[v]);
           else x = fmaf(dot, UNSCALE, kshift[v]);
           lg[jj][v] = x;
         }
