@@ -387,6 +387,51 @@ def test_decode_many_chunks_and_tails(B, Hq, Hkv, d, dtype, L0, bsel):
             assert err <= atol and lerr <= max(atol, 1e-3) * 0.5, (c + 1, T, err, lerr)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_decode_more_chunks_than_travel_in_the_arguments(dtype):
+    """Up to twelve chunk-table rows travel in the kernel arguments; a cache of 15 chunks
+    makes the kernel read the table from device memory instead."""
+    from tests.pipeline_check import packed_to_chunks
+    B, Hq, Hkv, d, L0 = 2, 8, 4, 128, 230
+    g = torch.Generator().manual_seed(77)
+    sizes = [L0] + [int(torch.randint(5, 70, (1,), generator=g)) for _ in range(14)]
+    T_max = 40
+    L_all = sum(sizes) + T_max
+    K = torch.randn(B, Hkv, L_all, d, generator=g).to(dtype)
+    V = torch.randn(B, Hkv, L_all, d, generator=g).to(dtype)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    lib = zb.load()
+    ks = [int(0.4 * n) for n in sizes]
+    cap_hi = lib.zc_arena_slots(sum(ks), len(sizes))
+    cap_lo = lib.zc_arena_slots(sum(sizes) - sum(ks), len(sizes))
+    Kp = zb.PackedTensor(B, Hkv, d, cap_hi, cap_lo, 4, 2, "channel", zb.ZC_LAYOUT_ROW, max_chunks=len(sizes), device=DEV)
+    Vp = zb.PackedTensor(B, Hkv, d, cap_hi, cap_lo, 4, 2, "cst", zb.ZC_LAYOUT_TGROUP, max_chunks=len(sizes), device=DEV)
+    atol = 1e-4 if dtype == torch.float32 else 2e-2
+    n_packed = 0
+    bsel = [0, 1]
+    for c, (n_new, k_new) in enumerate(zip(sizes, ks)):
+        sal, reg = zb.zc_select_salient(torch.rand(B, n_new, generator=g).to(DEV), k_new)
+        sl = slice(n_packed, n_packed + n_new)
+        zb.zc_quantize_pack(Kd[:, :, sl], sal, reg, Kp, pos_offset=n_packed)
+        zb.zc_quantize_pack(Vd[:, :, sl], sal, reg, Vp, pos_offset=n_packed)
+        n_packed += n_new
+        if c + 1 not in (12, 13, 15):                 # the last inline table, the first and a longer one in memory
+            continue
+        chunks_k, chunks_v = packed_to_chunks(Kp, bsel), packed_to_chunks(Vp, bsel)
+        for T in (0, 23):
+            q = torch.randn(B, Hq, d, generator=g).to(dtype)
+            lse = torch.empty(B, Hq, dtype=torch.float32, device=DEV)
+            tk, tv = Kd[:, :, n_packed:n_packed + T_max], Vd[:, :, n_packed:n_packed + T_max]
+            out = zb.zc_decode_attention(q.to(DEV), Kp, Vp, tk if T else None, tv if T else None, T, lse_out=lse)
+            tko = K[:, :, n_packed:n_packed + T].double().numpy() if T else None
+            tvo = V[:, :, n_packed:n_packed + T].double().numpy() if T else None
+            Kc, Vc = zo.cache_matrices(chunks_k, chunks_v, Hkv, tko, tvo)
+            ref, lse_o, _ = zo.decode_attention(q.double().numpy(), Kc, Vc)
+            err = np.abs(out.cpu().double().numpy() - ref).max()
+            lerr = np.abs(lse.cpu().numpy() - lse_o).max()
+            assert err <= atol and lerr <= max(atol, 1e-3) * 0.5, (c + 1, T, err, lerr)
+
+
 def test_decode_randomized_shapes():
     """Thirty seeded draws of (batch, heads, group size, head_dim, dtype, bit widths, K scheme,
     prefill length, number and size of flushed chunks, tail length): the decode entry
