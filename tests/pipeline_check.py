@@ -94,15 +94,26 @@ def compare_subset(g: zo.QuantSubset, o: zo.QuantSubset, what: str) -> Dict[str,
         zg, zo_ = g.tok_zero[:, :, None], o.tok_zero[:, :, None]
     else:
         zg, zo_ = g.chan_zero[:, None, :], o.chan_zero[:, None, :]
+    # Eq. 5 defines x_hat = (code - z) s: a row (or channel) whose zero point came out one
+    # step apart on the two sides, with every code shifted along, is the same quantization.
+    # What is unique is the level code - z: mismatches are counted on levels, and a differing
+    # zero point must sit at its own rounding boundary, z = -round(min / s) with min / s
+    # within 1e-3 of n + 1/2 (fp32 on one side, fp64 on the other).
     zdiff = np.broadcast_to(zg != zo_, g.codes.shape)
     assert np.all(np.abs(zg - zo_) <= 1), f"{what}: zero-point differs by more than one step"
-    mism = g.codes != o.codes
+    if np.any(zg != zo_):
+        zpre = -o.pre_round.min(axis=2 if tokwise else 1)            # -min / s of every row / channel
+        zpre = zpre[:, :, None] if tokwise else zpre[:, None, :]
+        zfrac = np.abs(zpre - np.floor(zpre) - 0.5)
+        assert np.all(zfrac[zg != zo_] < 1e-3), f"{what}: a zero point differs away from its rounding boundary"
+    mism = (g.codes - zg) != (o.codes - zo_)
     rep["n_mismatch"] = int(mism.sum())
     rep["n_zero_mismatch"] = int((zg != zo_).sum())
     if rep["n_mismatch"]:
-        d = np.abs(g.codes - o.codes)[mism]
-        assert np.all(d == 1), f"{what}: a code differs by more than one step"
+        d = np.abs((g.codes - zg) - (o.codes - zo_))[mism]
+        assert np.all(d == 1), f"{what}: a level differs by more than one step"
         frac = np.abs(o.pre_round[mism] - np.floor(o.pre_round[mism]) - 0.5)
+        # (where the zero points differ, the clipped ends of the code range move by one level)
         at_boundary = (frac < 1e-3) | zdiff[mism]
         assert np.all(at_boundary), f"{what}: {int((~at_boundary).sum())} mismatches away from a rounding boundary"
     return rep

@@ -113,3 +113,52 @@ def test_packfmt_bit_positions_follow_the_header():
     codes = np.zeros((1, 1, 64, 64), np.int64); codes[0, 0, 32 + 4 * 1 + 3, 7] = 0x3     # tile 2, kg=1, v=3 -> e=4*1+3
     w = packfmt.encode_tgroup(codes, 2).view(np.uint32).reshape(1, 4, 64)
     assert w[0, 1, 7] == 0x3 << 14 and w.sum() == 0x3 << 14
+
+
+def test_parity_rule_counts_levels_and_polices_zero_point_differences():
+    """The code comparison of the GPU tests, exercised on the CPU with planted differences in
+    copies of the oracle's own result: a zero point one step apart with every code shifted
+    along is the same quantization (Eq. 5: x_hat = (code - z) s) if and only if -min / s sat
+    at a rounding boundary; anywhere else it must be rejected, and so must a shifted level."""
+    import copy
+    import pytest
+    from oracle import zipcache_oracle as zo
+    from tests.pipeline_check import compare_subset
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((1, 40, 64))
+    # plant a near-tie in row 3: make -min/s = n + 1/2 + 1e-6 by moving the row's minimum
+    ref = zo.quantize_rows(X, 4, "token")
+    row = X[0, 3].copy()
+    hi, j = row.max(), int(row.argmin())
+    # min / s = 15 min / (hi - min) = -(n + 0.5) - eps  =>  min = -(n + .5 + eps) hi / (15 - (n + .5 + eps))
+    n = 6
+    t = n + 0.5 + 1e-6
+    row[j] = -t * hi / (15 - t)
+    row[np.arange(64) != j] = np.maximum(row[np.arange(64) != j], row[j] * 0.99)
+    X[0, 3] = row
+    ref = zo.quantize_rows(X, 4, "token")
+    assert abs(-ref.pre_round[0, 3].min() - (n + 0.5)) < 1e-5
+    same = compare_subset(copy.deepcopy(ref), ref, "identical")
+    assert same["n_mismatch"] == 0 and same["n_zero_mismatch"] == 0
+    # the other side rounded that zero point the other way: all codes of the row shift, the clipped end moves a level
+    other = copy.deepcopy(ref)
+    dz = -1.0 if ref.tok_zero[0, 3] == np.round(t) else 1.0
+    other.tok_zero[0, 3] += dz
+    other.codes[0, 3] = np.clip(ref.codes[0, 3] + dz, 0, 15)
+    rep = compare_subset(other, ref, "zero point at its boundary")
+    assert rep["n_zero_mismatch"] == 1 and rep["n_mismatch"] <= 2          # only clipped ends differ in level
+    # the same shift in a row that is nowhere near a boundary is an error
+    r2 = next(r for r in range(40) if r != 3 and abs((-ref.pre_round[0, r].min()) % 1 - 0.5) > 0.1)
+    bad = copy.deepcopy(ref)
+    bad.tok_zero[0, r2] += 1.0
+    bad.codes[0, r2] = np.clip(ref.codes[0, r2] + 1.0, 0, 15)
+    with pytest.raises(AssertionError, match="zero point differs away"):
+        compare_subset(bad, ref, "zero point off")
+    # and so is a level that differs away from a rounding boundary of its element
+    r3, c3 = next((r, c) for r in range(40) for c in range(64)
+                  if abs(ref.pre_round[0, r, c] % 1 - 0.5) > 0.2 and 1 <= ref.codes[0, r, c] <= 14)
+    bad = copy.deepcopy(ref)
+    bad.codes[0, r3, c3] += 1.0
+    with pytest.raises(AssertionError, match="away from a rounding boundary"):
+        compare_subset(bad, ref, "level off")
+
