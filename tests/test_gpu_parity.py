@@ -560,6 +560,47 @@ def test_pipeline_randomized_configurations():
         run_pipeline_check(w, k_scheme=ks, v_scheme=vs, flush_interval=fi or None)
 
 
+def test_graph_replays_reproduce_the_eager_step():
+    """bench.py times replayed HIP graphs: the step of a scaled workload with a streaming
+    flush, captured stage by stage as the benchmark does, must leave exactly what the eager
+    step leaves - scores, index lists, every packed array, all decode outputs and the flush's
+    scores - on each of three replays, with eager work and synchronizations in between."""
+    import bench
+    w = scaled(WORKLOADS["llama2_13b_4k_b16"], B=2, Hq=8, Hkv=8, L=520, decode_steps=130)
+    hp = bench.HotPath(w)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        parts = [hp.scores, hp.sal, hp.reg, hp.out, hp.tail_scores, hp.sal_t, hp.reg_t]
+        for P in (hp.Kp, hp.Vp):
+            parts += [P.codes_hi, P.codes_lo, P.tok_scale_hi, P.tok_zero_hi, P.tok_scale_lo, P.tok_zero_lo,
+                      P.chan_scale, P.chan_zero, P.chunk_table]
+        return [t.clone() for t in parts], (hp.Kp.chunks, hp.Vp.chunks)
+
+    hp.step()
+    want, want_chunks = snapshot()
+    hp.step()                                            # eager again: the step is repeatable
+    again, _ = snapshot()
+    assert all(torch.equal(a, b) for a, b in zip(want, again))
+    stages = hp.stages()
+    graphs = []
+    for _, fn, _, _ in stages:                           # captured in execution order
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        graphs.append(g)
+    assert (hp.Kp.chunks, hp.Vp.chunks) == want_chunks   # capture advanced the host bookkeeping like a step
+    for rep in range(3):
+        for t in (hp.scores, hp.out, hp.tail_scores, hp.Kp.codes_lo, hp.Vp.codes_hi):
+            t.zero_()                                    # eager work between the replays
+        torch.cuda.synchronize()
+        for g in graphs:
+            g.replay()
+        got, _ = snapshot()
+        for i, (a, b) in enumerate(zip(want, got)):
+            assert torch.equal(a, b), f"replay {rep}: array {i} differs from the eager step"
+
+
 def test_results_are_deterministic():
     w = scaled(WORKLOADS["llama3_8b_4k"], L=900)
     from paper_2405_14256_amd import probes
