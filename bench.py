@@ -34,11 +34,23 @@ from paper_2405_14256_amd import probes                 # noqa: E402
 from paper_2405_14256_amd.workloads import WORKLOADS, make_decode_step, make_prefill, to_f64  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per decode call from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by
-# what the same counter reads for a plain 256 MiB copy); the summary of those runs and their
-# commands are in profiles/decode_traffic_llama3_8b_4k.txt.  Not measurable from inside this script.
-MEASURED_DECODE_TRAFFIC = {"llama3_8b_4k": 4963231.0}
 FLUSH_INTERVAL = 100
+
+
+def measured_decode_traffic(workload: str):
+    """HBM bytes per decode call from rocprofv3 counter runs of this script (FETCH_SIZE, then
+    WRITE_SIZE, each scaled by what the same counter reads for a plain 256 MiB copy): not
+    measurable from inside a run, so it is read from the summary of those runs,
+    profiles/decode_traffic_<workload>.txt (its last line, "# decode entry point ...: N bytes").
+    None when no summary exists for the workload."""
+    path = os.path.join(ROOT, "profiles", f"decode_traffic_{workload}.txt")
+    try:
+        for line in reversed(open(path).read().splitlines()):
+            if line.startswith("# decode entry point"):
+                return {"bytes_per_launch": float(line.split(":")[1].split()[0]), "source": os.path.relpath(path, ROOT)}
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
 
 
 class HotPath:
@@ -78,9 +90,11 @@ class HotPath:
         self.out = torch.empty(S, w.B, w.Hq, w.d, dtype=w.torch_dtype, device=dev)
         self.probe_off_np = probes.decode_probe_offsets(FLUSH_INTERVAL, seed=w.seed)
         self.probe_off = torch.from_numpy(self.probe_off_np).to(dev)
-        self.tail_scores = torch.empty(w.B, FLUSH_INTERVAL, **f32)
-        self.sal_t = torch.empty(w.B, self.k_tail, **i32)
-        self.reg_t = torch.empty(w.B, FLUSH_INTERVAL - self.k_tail, **i32)
+        # every flush keeps its window's scores and index lists (a few KB each), so that a
+        # whole step can be checked against the oracle after the fact
+        self.tail_scores = [torch.empty(w.B, FLUSH_INTERVAL, **f32) for _ in range(self.n_flush)]
+        self.sal_t = [torch.empty(w.B, self.k_tail, **i32) for _ in range(self.n_flush)]
+        self.reg_t = [torch.empty(w.B, FLUSH_INTERVAL - self.k_tail, **i32) for _ in range(self.n_flush)]
         self.lse_p = torch.empty(w.B, w.Hq, len(self.probe_off_np), **f32)
         # the log-sum-exp of a probe step goes straight to its row of lse_probe[f] (the other
         # steps do not ask for it): the flush then needs one transposing copy, no gather
@@ -163,11 +177,11 @@ class HotPath:
                 tk = self.tail_k[:, :, base:base + FLUSH_INTERVAL]
                 tv = self.tail_v[:, :, base:base + FLUSH_INTERVAL]
                 zb.zc_probe_saliency(self.q_all, tk, self.probe_off, probe_rows=rows, lse_ext=self.lse_p,
-                                     scores=self.tail_scores)
-                zb.zc_select_salient(self.tail_scores, self.k_tail, self.sal_t, self.reg_t)
+                                     scores=self.tail_scores[f])
+                zb.zc_select_salient(self.tail_scores[f], self.k_tail, self.sal_t[f], self.reg_t[f])
                 n_packed = self.w.L + base
-                zb.zc_quantize_pack(tk, self.sal_t, self.reg_t, self.Kp, pos_offset=n_packed)
-                zb.zc_quantize_pack(tv, self.sal_t, self.reg_t, self.Vp, pos_offset=n_packed)
+                zb.zc_quantize_pack(tk, self.sal_t[f], self.reg_t[f], self.Kp, pos_offset=n_packed)
+                zb.zc_quantize_pack(tv, self.sal_t[f], self.reg_t[f], self.Vp, pos_offset=n_packed)
             return fn
 
         j = 0
@@ -183,35 +197,131 @@ class HotPath:
         for _, fn, _, _ in self.stages():
             fn()
 
+    def launch_units(self, stages, graph: bool = True):
+        """The launch units of the timed region - the three compression stages of the prefill
+        as one unit, every decode range and every flush a unit of its own (so that HIP events
+        can bracket exactly the decode launches) - and, for the split of the first unit, one
+        unit per stage.  With `graph` every unit is captured into a HIP graph and the
+        callables replay it.  Returns (units, their names, per-stage units)."""
+        groups = []
+        for i, (name, _, _, _) in enumerate(stages):
+            if name in ("select", "quantize") and groups and stages[groups[-1][-1]][0] in ("probe", "select"):
+                groups[-1].append(i)
+            else:
+                groups.append([i])
+        group_name = ["compress" if len(gr) > 1 else stages[gr[0]][0] for gr in groups]
+        if not graph:
+            def run_unit(unit):
+                return lambda: [stages[i][1]() for i in unit]
+            self.step()
+            return [run_unit(gr) for gr in groups], group_name, [fn for _, fn, _, _ in stages]
+
+        def capture(units):
+            out = []
+            for unit in units:                      # captured in execution order: the host-side
+                g = torch.cuda.CUDAGraph()          # cache bookkeeping advances as in a real step
+                with torch.cuda.graph(g):
+                    for i in unit:
+                        stages[i][1]()
+                out.append(g.replay)
+            torch.cuda.synchronize()
+            for r in out:
+                r()
+            torch.cuda.synchronize()
+            return out
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return capture(groups), group_name, capture([[i] for i in range(len(stages))])
+
+    def decode_cold(self, reps: int):
+        """Decode calls on the cache as the step leaves it, rotating through copies of it
+        that together exceed 512 MiB, so that no call finds its lines in the last-level
+        cache: microseconds per call (mean / median / min over `reps` replays of a graph
+        that holds one call per copy) and the algorithmic bytes of such a call."""
+        w = self.w
+        hi = sum(c[1] for c in self.Kp.chunks); lo = sum(c[3] for c in self.Kp.chunks)
+        base = self.n_flush * FLUSH_INTERVAL
+        T = self.S - base
+        nbytes = self.decode_bytes(hi, lo, self.Kp.c.n_chunks, T)
+        copies = int(min(max(4, -(-(512 << 20) // int(nbytes))), 192))
+        caches = [(self.Kp.clone(), self.Vp.clone(), self.tail_k[:, :, base:].clone(), self.tail_v[:, :, base:].clone())
+                  for _ in range(copies)]
+        q = self.q_all[:, :, self.S - 1:self.S]
+        out = torch.empty_like(self.out[0])
+        for Kp, Vp, tk, tv in caches[:2]:
+            zb.zc_decode_attention(q, Kp, Vp, tk, tv, T, out=out)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for Kp, Vp, tk, tv in caches:
+                zb.zc_decode_attention(q, Kp, Vp, tk, tv, T, out=out)
+        gr.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); gr.replay(); e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / copies)
+        ts.sort()
+        assert torch.equal(out, self.out[self.S - 1]), "a copy of the cache decodes differently"
+        return {"mean": round(sum(ts) / len(ts), 3), "median": round(ts[len(ts) // 2], 3), "min": round(ts[0], 3),
+                "copies": copies, "bytes_per_launch": nbytes, "tail_len": T}
+
 
 def cpu_baseline(hp: HotPath, decode_sample: int = 4):
-    """The oracle, as it stands, on the host cores: the whole prefill part of
-    one step plus `decode_sample` decode steps, extrapolated to the step's
-    decode count."""
+    """The oracle, as it stands, on the host cores: the whole prefill part of one step
+    plus `decode_sample` decode steps, stage by stage, extrapolated to the step's decode
+    count; once with the thread count numpy's BLAS chooses by itself and once limited to
+    one thread (batch elements are independent: one is timed and the result scaled)."""
     from oracle import zipcache_oracle as zo
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
+        threadpool_limits = None
         cores = os.cpu_count() or 1
     w = hp.w
-    nb = 1 if w.B > 1 else w.B          # batch elements are independent: time one, scale by B
+    nb = 1
     Q, K, V = (to_f64(hp.cpu_inputs[n][:nb]) for n in ("Q", "K", "V"))
-    t0 = time.perf_counter()
-    scores, _ = zo.saliency_scores(Q, K, hp.pos_np)
-    ck, cv, sal, reg = zo.compress_prefill(K, V, scores, hp.k, w.bits_hi, w.bits_lo)
-    t1 = time.perf_counter()
-    cache = zo.StreamingCache(Hkv=w.Hkv, chunks_K=[ck], chunks_V=[cv], n_packed=w.L)
     n = min(decode_sample, hp.S)
-    for j in range(n):
-        d = hp.cpu_decode[j]
-        cache.step(to_f64(d["q"][:nb]), to_f64(d["k_new"][:nb]), to_f64(d["v_new"][:nb]), False)
-    t2 = time.perf_counter()
-    t_step = ((t1 - t0) + (t2 - t1) / n * hp.S) * (w.B / nb)
-    return {"value": w.B * hp.S / t_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"float64 numpy oracle on {nb} of {w.B} batch elements: probe scores + split + quantize of the "
-                      f"{w.name} prefill ({t1 - t0:.2f} s) and {n} of {hp.S} decode steps ({(t2 - t1) / n:.3f} s each), "
-                      f"extrapolated to one whole step of the whole batch"}, sal
+
+    def one_pass():
+        t = [time.perf_counter()]
+        scores, _ = zo.saliency_scores(Q, K, hp.pos_np)
+        t.append(time.perf_counter())
+        sal, reg = zip(*(zo.select_salient(scores[b], hp.k) for b in range(nb)))
+        sal, reg = np.stack(sal), np.stack(reg)
+        t.append(time.perf_counter())
+        ck = zo.compress_tensor(K, sal, reg, w.bits_hi, w.bits_lo, "channel")
+        cv = zo.compress_tensor(V, sal, reg, w.bits_hi, w.bits_lo, "cst")
+        t.append(time.perf_counter())
+        cache = zo.StreamingCache(Hkv=w.Hkv, chunks_K=[ck], chunks_V=[cv], n_packed=w.L)
+        for j in range(n):
+            d = hp.cpu_decode[j]
+            cache.step(to_f64(d["q"][:nb]), to_f64(d["k_new"][:nb]), to_f64(d["v_new"][:nb]), False)
+        t.append(time.perf_counter())
+        st = {"probe_s": t[1] - t[0], "select_s": t[2] - t[1], "quantize_s": t[3] - t[2], "decode_step_s": (t[4] - t[3]) / n}
+        st["step_s"] = (st["probe_s"] + st["select_s"] + st["quantize_s"] + st["decode_step_s"] * hp.S) * (w.B / nb)
+        return st
+
+    multi = one_pass()
+    single = None
+    if threadpool_limits is not None and multi["step_s"] * nb / w.B < 40.0:
+        with threadpool_limits(limits=1):
+            single = one_pass()
+    out = {"value": w.B * hp.S / multi["step_s"], "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"float64 numpy oracle on {nb} of {w.B} batch elements: probe scores, split and quantize of the "
+                     f"{w.name} prefill and {n} of {hp.S} decode steps, extrapolated to one whole step of the whole batch",
+           "stages_s": {k: round(v, 4) for k, v in multi.items()}}
+    if single is not None:
+        out["single_thread"] = {"value": w.B * hp.S / single["step_s"], "stages_s": {k: round(v, 4) for k, v in single.items()}}
+    return out
 
 
 def machine_peaks(args):
@@ -339,6 +449,7 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_4k")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache decode pass after the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain copies of 256 MiB (a kernel of known traffic, "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -370,46 +481,7 @@ def main():
         hp.step()
     torch.cuda.synchronize()
     stages = hp.stages()
-    # Launch units of the timed region: the three compression stages of the prefill as one
-    # graph, every decode range and every flush as a graph of its own (so that HIP events
-    # can bracket exactly the decode launches).
-    groups = []
-    for i, (name, _, _, _) in enumerate(stages):
-        if name in ("select", "quantize") and groups and stages[groups[-1][-1]][0] in ("probe", "select"):
-            groups[-1].append(i)
-        else:
-            groups.append([i])
-    group_name = ["compress" if len(gr) > 1 else stages[gr[0]][0] for gr in groups]
-
-    def capture(units):
-        out = []
-        for unit in units:                      # captured in execution order: the host-side
-            g = torch.cuda.CUDAGraph()          # cache bookkeeping advances as in a real step
-            with torch.cuda.graph(g):
-                for i in unit:
-                    stages[i][1]()
-            out.append(g.replay)
-        torch.cuda.synchronize()
-        for r in out:
-            r()
-        torch.cuda.synchronize()
-        return out
-
-    if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            hp.step()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        runners = capture(groups)
-        stage_runners = capture([[i] for i in range(len(stages))])
-    else:
-        def run_unit(unit):
-            return lambda: [stages[i][1]() for i in unit]
-        runners = [run_unit(gr) for gr in groups]
-        stage_runners = [fn for _, fn, _, _ in stages]
-        hp.step()
+    runners, group_name, stage_runners = hp.launch_units(stages, graph=not args.no_graph)
     dec_bytes_step = sum(getattr(fn, "nbytes", 0.0) for name, fn, _, _ in stages if name == "decode")
     n_dec = sum(nc for name, _, nc, _ in stages if name == "decode")
 
@@ -425,27 +497,35 @@ def main():
                 ev[k][i + 1].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        ms = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)) / args.steps for i in range(len(rs))]
-        return dt, ms
+        # [step][unit] milliseconds
+        return dt, [[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(len(rs))] for k in range(args.steps)]
+
+    def stats(xs):
+        xs = sorted(xs)
+        return {"mean": sum(xs) / len(xs), "median": xs[len(xs) // 2], "min": xs[0]}
+
+    def per_step(ms, names, key):
+        """One value per timed step: the sum of the units called `key` in that step."""
+        return [sum(v for n, v in zip(names, row) if n == key) for row in ms]
 
     dt, unit_ms = timed(runners)
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = w.B * hp.S * args.steps / dt
-    stage_ms = {}
-    for n, v in zip(group_name, unit_ms):
-        stage_ms[n] = stage_ms.get(n, 0.0) + v
+    st_ms = {n: stats(per_step(unit_ms, group_name, n)) for n in dict.fromkeys(group_name)}
     # the split of the compression graph into its stages: a second pass over the same step,
     # one graph per stage (outside the timed region; `value` does not depend on it)
-    _, per_stage = timed(stage_runners)
-    for (name, _, _, _), v in zip(stages, per_stage):
-        if name in ("probe", "select", "quantize"):
-            stage_ms[name] = stage_ms.get(name, 0.0) + v
-    dec_avg_ms = stage_ms["decode"] / n_dec
+    _, stage_ms = timed(stage_runners)
+    names = [name for name, _, _, _ in stages]
+    for n in ("probe", "select", "quantize"):
+        st_ms[n] = stats(per_step(stage_ms, names, n))
+    st_ms.setdefault("flush", {"mean": 0.0, "median": 0.0, "min": 0.0})
+    dec_us = {k: v / n_dec * 1e3 for k, v in st_ms["decode"].items()}      # per launch, the step's average
     dec_avg_bytes = dec_bytes_step / n_dec
-    achieved = dec_avg_bytes / (dec_avg_ms * 1e-3) / 1e9
-    quant_gbps = hp.quant_bytes() / (stage_ms["quantize"] * 1e-3) / 1e9
-    probe_tflops = hp.probe_flops() / (stage_ms["probe"] * 1e-3) / 1e12
-    graph = None if args.no_graph else True
+    achieved = dec_avg_bytes / (dec_us["mean"] * 1e-6) / 1e9
+    quant_gbps = hp.quant_bytes() / (st_ms["quantize"]["mean"] * 1e-3) / 1e9
+    probe_tflops = hp.probe_flops() / (st_ms["probe"]["mean"] * 1e-3) / 1e12
+    cold = None if args.no_cold else hp.decode_cold(max(args.steps, 5))
+    traffic = measured_decode_traffic(w.name)
 
     result = {
         "metric": "KV quantize-pack GB/s + packed decode-attn tokens/s, LLaMA3-8B shape @4k",
@@ -456,20 +536,31 @@ def main():
                    "seq_len": w.L, "probe_rows": int(len(hp.pos_np)), "salient_tokens": hp.k,
                    "bits": f"{w.bits_hi}/{w.bits_lo}", "decode_steps": hp.S, "flush_interval": FLUSH_INTERVAL,
                    "k_scheme": "channel", "v_scheme": "cst",
-                   "launch": "eager" if graph is None else "hipgraph replay: one graph for probe + select + quantize, one per decode range, one per flush"},
+                   "launch": "eager" if args.no_graph else "hipgraph replay: one graph for probe + select + quantize, one per decode range, one per flush"},
         "components": {
-            "quantize_pack_GBps": quant_gbps, "quantize_pack_ms": stage_ms["quantize"],
-            "decode_attention_tokens_per_s": w.B / (dec_avg_ms * 1e-3), "decode_attention_us_per_launch": dec_avg_ms * 1e3,
-            "probe_saliency_TFLOPs": probe_tflops, "probe_saliency_ms": stage_ms["probe"],
-            "select_ms": stage_ms["select"], "flush_ms": stage_ms.get("flush", 0.0),
-            "compress_ms": stage_ms.get("compress", 0.0),
+            "quantize_pack_GBps": quant_gbps, "quantize_pack_ms": st_ms["quantize"]["mean"],
+            "decode_attention_tokens_per_s": w.B / (dec_us["mean"] * 1e-6), "decode_attention_us_per_launch": dec_us["mean"],
+            "probe_saliency_TFLOPs": probe_tflops, "probe_saliency_ms": st_ms["probe"]["mean"],
+            "select_ms": st_ms["select"]["mean"], "flush_ms": st_ms["flush"]["mean"],
+            "compress_ms": st_ms.get("compress", {"mean": 0.0})["mean"],
+            "per_step_ms": {n: {k: round(v, 5) for k, v in d.items()} for n, d in st_ms.items()},
+            "decode_us_per_launch": {"warm": {k: round(v, 3) for k, v in dec_us.items()}, "cold": cold},
             "timing": "HIP events between the graphs inside the timed region (decode, flush, compress = probe + select + "
-                      "quantize as one graph); probe / select / quantize alone from a second pass with one graph per stage"},
+                      "quantize as one graph), mean / median / min over the timed steps; probe / select / quantize alone "
+                      "from a second pass with one graph per stage; decode 'warm' is the timed region itself (one layer: "
+                      "every call re-reads the cache the previous call read, so it is served from the last-level "
+                      "cache), 'cold' a separate pass in which the calls rotate through copies of the final cache that "
+                      "together exceed 512 MiB (every call reads HBM)"},
         "roofline": {"bound": "hbm", "kernel": "zc_decode_attention (k_decode_mfma + k_decode_reduce)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "bytes_per_launch": dec_avg_bytes, "avg_launch_us": dec_avg_ms * 1e3,
-                     "traffic": MEASURED_DECODE_TRAFFIC.get(w.name)},
+                     "bytes_per_launch": dec_avg_bytes, "avg_launch_us": dec_us["mean"],
+                     "cache_state": "warm (timed region)",
+                     "traffic": traffic["bytes_per_launch"] if traffic else None,
+                     "traffic_source": traffic["source"] if traffic else None},
     }
+    if cold:
+        result["roofline"]["cold"] = {"achieved": cold["bytes_per_launch"] / (cold["mean"] * 1e-6) / 1e9,
+                                      "frac": cold["bytes_per_launch"] / (cold["mean"] * 1e-6) / 1e9 / HBM_PEAK_GBPS}
     if w.name != "llama3_8b_4k":
         result["metric"] += f" (supplementary workload {w.name})"
     if args.calibrate_copy:
@@ -479,7 +570,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"], _ = cpu_baseline(hp)
+        result["cpu_baseline"] = cpu_baseline(hp)
     print(json.dumps(result))
 
 

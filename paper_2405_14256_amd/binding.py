@@ -172,6 +172,20 @@ class PackedTensor:
         self.c.n_hi = self.c.n_lo = 0
         self.c.n_chunks = 0
 
+    def clone(self) -> "PackedTensor":
+        """A copy with arrays of its own (same contents, same chunks)."""
+        o = PackedTensor(self.B, self.H, self.D, self.c.cap_hi, self.c.cap_lo, self.c.bits_hi, self.c.bits_lo,
+                         self.scheme, self.layout, max_chunks=self.c.max_chunks, device=self.chan_scale.device,
+                         store_pos=self.pos_hi is not None)
+        for name in ("codes_hi", "codes_lo", "tok_scale_hi", "tok_zero_hi", "tok_scale_lo", "tok_zero_lo",
+                     "pos_hi", "pos_lo", "chan_scale", "chan_zero", "chunk_table"):
+            src = getattr(self, name)
+            if src is not None:
+                getattr(o, name).copy_(src)
+        o.chunk_table_host[:] = self.chunk_table_host
+        o.c.n_hi, o.c.n_lo, o.c.n_chunks = self.c.n_hi, self.c.n_lo, self.c.n_chunks
+        return o
+
     @property
     def chunks(self):
         return [tuple(int(v) for v in self.chunk_table_host[i]) for i in range(self.c.n_chunks)]
@@ -268,3 +282,4 @@ def zc_decode_attention(q: torch.Tensor, Kp: PackedTensor, Vp: PackedTensor,
                                    tail_len, float(sm_scale), out.data_ptr(), _ptr(lse_out),
                                    ws.data_ptr(), ws.numel(), _stream()))
     return out
+

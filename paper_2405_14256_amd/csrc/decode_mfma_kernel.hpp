@@ -662,7 +662,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const auto rs_vtz = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(VTOK ? v_tz + tokbase : nullptr), 0, VTOK ? tok_bytes : 0, kRsrcFlags);
     // Staging: block bi of the segment is D * 16 contiguous bytes of K codes and as
     // many of V codes; each goes to LDS with KCH 1 KB transfers.  (Token parameters:
-    // 64 floats per array, of which a 4-bit block uses the first 32.)
+    // 64 floats per array, of which a 4-bit block uses - and requests - the first 32.)
     constexpr int KCH = D / 64;                           // 1 KB transfers per code array and block
     constexpr int L_STAGE = 2 * KCH + (VTOK ? 2 : 0) + (KTOK ? 2 : 0);   // transfers per block
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)&ring[wave][0];
@@ -670,11 +670,16 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const int bl_lo = hlo / NH, bl_hi = hlo < hhi ? (hhi - 1) / NH + 1 : hlo / NH;    // this wave's blocks
     // (live == false: the same number of transfers, all out of range -- they move
     // zeros and touch no memory -- so that the wait counts below are constants)
+    // (A token-parameter transfer is 64 floats, a 4-bit block 32 slots: lanes past the block
+    // ask out of range too.  The block's offset travels in the scalar offset, which the
+    // range check does not see, so for the last block of an arena that is full to its
+    // capacity those lanes would otherwise read past the end of the array.)
+    const int tok_lane = (4 * lane) | ((TB < 64 && lane >= TB) ? (int)0xFFFFF000u : 0);
     auto issue = [&](uint32_t dst, int bi, bool live) {
       const int ko = (int)((uint32_t)(begin + bi * TB) * (uint32_t)ROWB);          // = block index * D * 16
       const int to = (int)((uint32_t)(begin + bi * TB) * 4u);
       const int oob = live ? 0 : (int)0xFFFFF000u;     // per-lane offsets beyond any buffer the host admits
-      const int v16 = (16 * lane) | oob, v4 = (4 * lane) | oob;
+      const int v16 = (16 * lane) | oob, v4 = tok_lane | oob;
       dma16<0>(dst, rs_k, v16, ko);
       if constexpr (KCH == 2) dma16<1024>(dst, rs_k, v16, ko);
       dma16<0>(dst + kCodeBytes, rs_v, v16, ko);

@@ -7,7 +7,7 @@ import torch
 from oracle import zipcache_oracle as zo
 from paper_2405_14256_amd import binding as zb
 from paper_2405_14256_amd.workloads import WORKLOADS, scaled
-from tests.pipeline_check import run_pipeline_check
+from tests.pipeline_check import record_of_hot_path, run_pipeline_check, verify_record
 
 pytestmark = pytest.mark.gpu
 
@@ -45,8 +45,33 @@ def test_llama3_shape_ragged():
     run_pipeline_check(w, verbose=True)
 
 
-def test_llama3_4k_full():
-    run_pipeline_check(WORKLOADS["llama3_8b_4k"], decode_steps=16, verbose=True)
+def _timed_step_against_oracle(name, bsel, graphs=True):
+    """The benchmark's own object and launch sequence (bench.HotPath: every buffer, view and
+    call of the step bench.py times, replayed from its HIP graphs), at the workload's full
+    size and full number of decode steps, flushes included; afterwards everything the step
+    left behind - prefill scores and split, every chunk of the packed cache, the output of
+    every decode step, the log-sum-exp of every probe step, every flush window's scores and
+    split - is compared with the oracle on the batch elements `bsel`."""
+    import bench
+    w = WORKLOADS[name]
+    hp = bench.HotPath(w)
+    hp.step()
+    if graphs:
+        runners, _, _ = hp.launch_units(hp.stages(), graph=True)
+        for t in [hp.scores, hp.out, hp.Kp.codes_hi, hp.Kp.codes_lo, hp.Vp.codes_hi, hp.Vp.codes_lo] + hp.tail_scores:
+            t.zero_()                                # what the check reads was written by the replay
+        torch.cuda.synchronize()
+        for r in runners:
+            r()
+    torch.cuda.synchronize()
+    rep = verify_record(record_of_hot_path(hp), bsel, verbose=True)
+    assert rep["decode_steps_checked"] == w.decode_steps
+    return rep
+
+
+def test_timed_step_llama3_8b_4k_all_128_steps_and_the_flush():
+    rep = _timed_step_against_oracle("llama3_8b_4k", [0])
+    assert "flush_score_max_rel" in rep and rep["codes_checked"] == 2 * 1024 * (4096 + 100)
 
 
 def test_mha_fp16_with_streaming_flush():
@@ -68,21 +93,49 @@ def test_needles_are_selected():
     assert rep["salient_overlap"] > 0.99
 
 
-# ---- the other configurations at their full sizes -------------------------------------
-# The GPU runs the whole batch in the launch configuration the benchmark times; the
-# oracle checks one batch element (every stage, element by element) and a few decode steps.
+# ---- the other configurations at their full sizes and lengths ----------------------------
+# The GPU runs the whole batch in the launch configuration the benchmark times, all decode
+# steps with the cache growing through its flushes; the oracle checks one batch element:
+# every stage, element by element, every decode step.
 
-def test_full_size_mistral_7b_8k_b8():
-    run_pipeline_check(WORKLOADS["mistral_7b_8k_b8"], decode_steps=3, bsel=[5], verbose=True)
+@pytest.mark.timeout(600)
+def test_timed_step_mistral_7b_8k_b8_all_256_steps_two_flushes():
+    rep = _timed_step_against_oracle("mistral_7b_8k_b8", [5])
+    assert rep["codes_checked"] == 2 * 1024 * (8192 + 200)
 
 
-def test_full_size_llama2_13b_4k_b16():
-    run_pipeline_check(WORKLOADS["llama2_13b_4k_b16"], decode_steps=3, bsel=[11], verbose=True)
+@pytest.mark.timeout(900)
+def test_timed_step_llama2_13b_4k_b16_all_512_steps_five_flushes():
+    rep = _timed_step_against_oracle("llama2_13b_4k_b16", [11])
+    assert rep["codes_checked"] == 2 * 5120 * (4096 + 500)
 
 
-def test_full_size_llama3_8b_32k():
-    rep = run_pipeline_check(WORKLOADS["llama3_8b_32k"], decode_steps=3, verbose=True)
+@pytest.mark.timeout(600)
+def test_timed_step_llama3_8b_32k_all_64_steps():
+    rep = _timed_step_against_oracle("llama3_8b_32k", [0])
     assert rep["salient_overlap"] > 0.99
+
+
+def test_timed_step_tiny():
+    _timed_step_against_oracle("tiny", [0])
+
+
+def test_softmax_scale_override_and_no_position_arrays():
+    """sm_scale != 0 on the probe, accumulated-score and decode entry points (the oracle takes
+    the same override), with a streaming flush so that the decode-time probes use it too; the
+    packed tensors carry no position arrays (pos_hi = pos_lo = NULL)."""
+    w = scaled(WORKLOADS["llama3_8b_4k"], L=777, decode_steps=110, Hq=8, Hkv=2, B=2)
+    rep = run_pipeline_check(w, flush_interval=100, sm_scale=0.05, store_pos=False, verbose=True)
+    assert "flush_score_max_rel" in rep
+    w = scaled(WORKLOADS["tiny"], decode_steps=4)
+    run_pipeline_check(w, sm_scale=0.2, store_pos=False, k_scheme="cst", verbose=True)
+    from paper_2405_14256_amd import probes
+    from paper_2405_14256_amd.workloads import make_prefill
+    inp = make_prefill(w)
+    pos = probes.probe_positions(w.L, w.probe_ratio, 3)
+    got = zb.zc_probe_accumulated(inp["Q"].to(DEV), inp["K"].to(DEV), torch.from_numpy(pos).to(DEV), sm_scale=0.2)
+    ref, _ = zo.saliency_scores(inp["Q"].double().numpy(), inp["K"].double().numpy(), pos, sm_scale=0.2, normalized=False)
+    assert np.abs(got.cpu().double().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
 
 
 # ---- edge cases ---------------------------------------------------------------------
@@ -432,6 +485,32 @@ def test_decode_more_chunks_than_travel_in_the_arguments(dtype):
             assert err <= atol and lerr <= max(atol, 1e-3) * 0.5, (c + 1, T, err, lerr)
 
 
+def test_decode_arena_full_to_its_capacity():
+    """Arenas with no slack: the salient arena holds 100 tokens in 128 slots and the regular
+    one 228 in 256, so the last 4-bit block ends exactly where the (batch) row of every
+    per-slot array ends - the kernel must not depend on anything past it."""
+    from tests.pipeline_check import packed_to_chunks
+    B, Hq, Hkv, d, L, k = 3, 8, 4, 128, 328, 100
+    g = torch.Generator().manual_seed(99)
+    K = torch.randn(B, Hkv, L, d, generator=g).to(torch.float16)
+    V = torch.randn(B, Hkv, L, d, generator=g).to(torch.float16)
+    q = torch.randn(B, Hq, d, generator=g).to(torch.float16)
+    sal, reg = zb.zc_select_salient(torch.rand(B, L, generator=g).to(DEV), k)
+    for k_scheme in ("cst", "channel"):
+        Kp = zb.PackedTensor(B, Hkv, d, 128, 256, 4, 2, k_scheme, zb.ZC_LAYOUT_ROW, max_chunks=1, device=DEV)
+        Vp = zb.PackedTensor(B, Hkv, d, 128, 256, 4, 2, "cst", zb.ZC_LAYOUT_TGROUP, max_chunks=1, device=DEV)
+        assert Kp.c.cap_hi == 128 and Kp.tok_scale_hi.numel() == B * 128
+        zb.zc_quantize_pack(K.to(DEV), sal, reg, Kp)
+        zb.zc_quantize_pack(V.to(DEV), sal, reg, Vp)
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=DEV)
+        out = zb.zc_decode_attention(q.to(DEV), Kp, Vp, lse_out=lse)
+        bsel = [0, 1, 2]
+        Kc, Vc = zo.cache_matrices(packed_to_chunks(Kp, bsel), packed_to_chunks(Vp, bsel), Hkv)
+        ref, lse_o, _ = zo.decode_attention(q.double().numpy(), Kc, Vc)
+        assert np.abs(out.cpu().double().numpy() - ref).max() <= 2e-2
+        assert np.abs(lse.cpu().numpy() - lse_o).max() <= 1e-3
+
+
 def test_decode_randomized_shapes():
     """Thirty seeded draws of (batch, heads, group size, head_dim, dtype, bit widths, K scheme,
     prefill length, number and size of flushed chunks, tail length): the decode entry
@@ -571,7 +650,7 @@ def test_graph_replays_reproduce_the_eager_step():
 
     def snapshot():
         torch.cuda.synchronize()
-        parts = [hp.scores, hp.sal, hp.reg, hp.out, hp.tail_scores, hp.sal_t, hp.reg_t]
+        parts = [hp.scores, hp.sal, hp.reg, hp.out] + hp.tail_scores + hp.sal_t + hp.reg_t
         for P in (hp.Kp, hp.Vp):
             parts += [P.codes_hi, P.codes_lo, P.tok_scale_hi, P.tok_zero_hi, P.tok_scale_lo, P.tok_zero_lo,
                       P.chan_scale, P.chan_zero, P.chunk_table]
@@ -591,7 +670,7 @@ def test_graph_replays_reproduce_the_eager_step():
         graphs.append(g)
     assert (hp.Kp.chunks, hp.Vp.chunks) == want_chunks   # capture advanced the host bookkeeping like a step
     for rep in range(3):
-        for t in (hp.scores, hp.out, hp.tail_scores, hp.Kp.codes_lo, hp.Vp.codes_hi):
+        for t in [hp.scores, hp.out, hp.Kp.codes_lo, hp.Vp.codes_hi] + hp.tail_scores:
             t.zero_()                                    # eager work between the replays
         torch.cuda.synchronize()
         for g in graphs:

@@ -161,4 +161,26 @@ def test_parity_rule_counts_levels_and_polices_zero_point_differences():
     bad.codes[0, r3, c3] += 1.0
     with pytest.raises(AssertionError, match="away from a rounding boundary"):
         compare_subset(bad, ref, "level off")
-
+    # inside the row whose zero point legitimately differs, only the clipped ends may move:
+    # a level off by one in the middle of the code range, away from its own tie, is an error
+    c4 = next(c for c in range(64) if abs(ref.pre_round[0, 3, c] % 1 - 0.5) > 0.2 and 2 <= other.codes[0, 3, c] <= 13)
+    bad = copy.deepcopy(other)
+    bad.codes[0, 3, c4] += 1.0
+    with pytest.raises(AssertionError, match="away from a rounding boundary"):
+        compare_subset(bad, ref, "level off inside a shifted row")
+    # budgets over a pass: raw identical codes, levels, zero points
+    from tests.pipeline_check import CODE_COUNTS, assert_code_budgets
+    tot = {k: rep[k] for k in CODE_COUNTS}
+    assert rep["n_raw_mismatch"] >= 60 and rep["n_raw_unshifted"] == 0          # the whole shifted row differs as stored
+    assert tot["n_mismatch"] == 1                                               # the clipped end of that row: 1 level in 2560,
+    tot["n_codes"] *= 10                                                        # within budget in a case ten times the size
+    out = assert_code_budgets(tot, "one tie in a small case")                   # 40 rows: one tie is tolerated
+    assert out["raw_identical_frac"] < 0.999
+    big = dict(tot, n_groups=20000, n_codes=20000 * 64)                         # a whole workload: budgets are fractions
+    assert_code_budgets(big, "one tie in 20000 rows")
+    with pytest.raises(AssertionError, match="zero points differ"):
+        assert_code_budgets(dict(big, n_zero_mismatch=3), "three ties in 20000 rows")
+    with pytest.raises(AssertionError, match="stored codes are identical"):
+        assert_code_budgets(dict(big, n_raw_mismatch=200), "too many stored codes differ")
+    with pytest.raises(AssertionError, match="levels differ"):
+        assert_code_budgets(dict(big, n_mismatch=200, n_raw_mismatch=100), "too many levels differ")
