@@ -19,7 +19,8 @@
  *   - Every pointer marked "device" is GPU memory owned by the caller; every
  *     other pointer is host memory.  The library allocates nothing, keeps no
  *     pointer after a call returns and has no global mutable state (apart from
- *     a cached copy of the device's compute-unit count).
+ *     a cached copy of the device's compute-unit count and, for
+ *     zc_decode_attention_static, its per-device scratch buffer).
  *   - All work is enqueued on the given HIP stream (`stream` is a hipStream_t
  *     passed as void*; NULL is the default stream).  Calls never synchronise
  *     with the host and never read results back.
@@ -55,7 +56,8 @@ typedef enum {
   ZC_ERR_UNSUPPORTED = -2, /* dtype, head dim, bit width, scheme, size limit  */
   ZC_ERR_WORKSPACE = -3,   /* workspace smaller than the *_workspace() size  */
   ZC_ERR_CAPACITY = -4,    /* arena or chunk table of a zc_packed is full    */
-  ZC_ERR_HIP = -5          /* the HIP runtime refused a launch               */
+  ZC_ERR_HIP = -5,         /* the HIP runtime refused a launch               */
+  ZC_ERR_STATIC_LIMIT = -6 /* needs more scratch than ZC_STATIC_SCRATCH_BYTES */
 } zc_status;
 
 typedef enum { ZC_F32 = 0, ZC_F16 = 1, ZC_BF16 = 2 } zc_dtype;
@@ -206,6 +208,23 @@ int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packe
                         const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
                         float sm_scale, void* out, float* lse_out,
                         void* ws, size_t ws_bytes, void* stream);
+
+/* ---- zc_decode_attention for callers that cannot allocate ----------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid
+ * hipMalloc: the same operation, arguments, kernels and results as zc_decode_attention,
+ * without a workspace argument.  The partial results of the split-K workgroups go to a
+ * buffer of ZC_STATIC_SCRATCH_BYTES that lives in the library's own device image (one
+ * copy per GPU, held until the process ends); the call allocates and frees nothing.
+ * Limit: zc_decode_attention_workspace(B, Hq, D) must not exceed ZC_STATIC_SCRATCH_BYTES
+ * (B*Hq <= 1790 query heads at D = 128 is always within it), else the call returns
+ * ZC_ERR_STATIC_LIMIT and launches nothing.  All calls on one GPU share that buffer: two
+ * calls that may overlap on the same GPU (different streams) race; calls on one stream,
+ * or ordered by events, are safe.  Nothing in the buffer has to start at zero: every
+ * partial a call reads was written by that call. */
+#define ZC_STATIC_SCRATCH_BYTES (8u << 20)
+int zc_decode_attention_static(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
+                               const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
+                               float sm_scale, void* out, float* lse_out, void* stream);
 
 /* ---- helpers ------------------------------------------------------------------ */
 /* Bytes of one code arena of `cap` slots. */

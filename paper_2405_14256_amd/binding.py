@@ -84,6 +84,8 @@ def load() -> C.CDLL:
     lib.zc_decode_attention_workspace.argtypes = [I64, I64, I64]
     lib.zc_decode_attention.restype = C.c_int
     lib.zc_decode_attention.argtypes = [T4, PK, PK, T4, T4, I64, F, P, P, P, SZ, P]
+    lib.zc_decode_attention_static.restype = C.c_int
+    lib.zc_decode_attention_static.argtypes = [T4, PK, PK, T4, T4, I64, F, P, P, P]
     lib.zc_unpack.restype = C.c_int
     lib.zc_unpack.argtypes = [PK, I32, I32, P, P, P]
     lib.zc_arena_bytes.restype = SZ
@@ -283,3 +285,21 @@ def zc_decode_attention(q: torch.Tensor, Kp: PackedTensor, Vp: PackedTensor,
                                    ws.data_ptr(), ws.numel(), _stream()))
     return out
 
+
+def zc_decode_attention_static(q: torch.Tensor, Kp: PackedTensor, Vp: PackedTensor,
+                               tail_k: Optional[torch.Tensor] = None, tail_v: Optional[torch.Tensor] = None,
+                               tail_len: int = 0, sm_scale: float = 0.0, *, out: torch.Tensor,
+                               lse_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """zc_decode_attention on the library's own scratch buffer: nothing is allocated, here
+    or in the library (`out` must be given)."""
+    lib = load()
+    if q.dim() == 3:
+        q = q.unsqueeze(2)
+    tq = tensor4(q)
+    ttk = tensor4(tail_k) if tail_len else None
+    ttv = tensor4(tail_v) if tail_len else None
+    _check("zc_decode_attention_static",
+           lib.zc_decode_attention_static(C.byref(tq), C.byref(Kp.c), C.byref(Vp.c),
+                                          C.byref(ttk) if tail_len else None, C.byref(ttv) if tail_len else None,
+                                          tail_len, float(sm_scale), out.data_ptr(), _ptr(lse_out), _stream()))
+    return out

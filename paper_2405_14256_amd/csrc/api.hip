@@ -61,6 +61,7 @@ extern "C" const char* zc_status_string(int status) {
     case ZC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case ZC_ERR_CAPACITY: return "packed cache arena or chunk table is full";
     case ZC_ERR_HIP: return "HIP launch failed";
+    case ZC_ERR_STATIC_LIMIT: return "problem needs more scratch memory than the library's static buffer holds";
     default: return "unknown status";
   }
 }

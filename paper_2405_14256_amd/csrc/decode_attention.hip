@@ -15,6 +15,8 @@
 // q'[c] = q[c] * cs[c] * sm_scale * log2(e), and the output is
 //   o[c] = cs[c] * ( sum_t w[t] code[t,c] - sum_t w[t] tz[t] - cz[c] * sum_t w[t] ),  w[t] = p[t] * ts[t],
 // accumulated per chunk and subset (each has its own channel parameters).
+#include <atomic>
+
 #include "decode_args.hpp"
 
 namespace zc {
@@ -348,10 +350,31 @@ extern "C" size_t zc_decode_attention_workspace(int64_t B, int64_t Hq, int64_t D
   return (size_t)B * Hq * (split_cap(B, Hq) + kTailSplits) * (D + 2) * sizeof(float);
 }
 
-extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
-                                   const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
-                                   float sm_scale, void* out, float* lse_out,
-                                   void* ws, size_t ws_bytes, void* stream) {
+// ---- the library's own scratch buffer, for callers that cannot allocate -----------------
+// zc_decode_attention_static keeps the partial (m, Z, o) of the split-K workgroups in
+// this array instead of a caller's workspace.  Every GPU the library runs on holds its
+// own copy at its own address; the name below is only a host-side handle, the address
+// on the current device comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[ZC_STATIC_SCRATCH_BYTES];
+
+static int static_scratch_of_current_device(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> of_device[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ZC_ERR_HIP;
+  void* p = of_device[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ZC_ERR_HIP;
+    of_device[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return ZC_OK;
+}
+
+static int decode_entry(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
+                        const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
+                        float sm_scale, void* out, float* lse_out,
+                        void* ws, size_t ws_bytes, bool static_ws, void* stream) {
   int rc = zc_validate_tensor(q);
   if (rc) return rc;
   if (q->L != 1) return ZC_ERR_INVALID_ARG;
@@ -387,7 +410,13 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
       Kp->cap_hi * 4 >= kPartLimit || Kp->cap_lo * 4 >= kPartLimit)
     return ZC_ERR_UNSUPPORTED;
   const size_t need = zc_decode_attention_workspace(q->B, q->H, q->D);
-  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
+  if (static_ws) {
+    if (need > (size_t)ZC_STATIC_SCRATCH_BYTES) return ZC_ERR_STATIC_LIMIT;
+    rc = static_scratch_of_current_device(&ws);
+    if (rc) return rc;
+  } else if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) {
+    return ZC_ERR_WORKSPACE;
+  }
 
   // the chunk tables must agree; count the work units
   const bool mfma_path = (Kp->bits_hi == 2 || Kp->bits_hi == 4) && (Kp->bits_lo == 2 || Kp->bits_lo == 4);
@@ -525,4 +554,17 @@ extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, con
   if (q->dtype == ZC_F16) return ZC_DEC(ZC_F16);
   return ZC_DEC(ZC_BF16);
 #undef ZC_DEC
+}
+
+extern "C" int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
+                                   const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
+                                   float sm_scale, void* out, float* lse_out,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  return decode_entry(q, Kp, Vp, tail_k, tail_v, tail_len, sm_scale, out, lse_out, ws, ws_bytes, false, stream);
+}
+
+extern "C" int zc_decode_attention_static(const zc_tensor4* q, const zc_packed* Kp, const zc_packed* Vp,
+                                          const zc_tensor4* tail_k, const zc_tensor4* tail_v, int64_t tail_len,
+                                          float sm_scale, void* out, float* lse_out, void* stream) {
+  return decode_entry(q, Kp, Vp, tail_k, tail_v, tail_len, sm_scale, out, lse_out, nullptr, 0, true, stream);
 }

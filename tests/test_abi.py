@@ -175,3 +175,19 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(zb, "LIB_PATH", "/nonexistent/libzipcache.so")
     with pytest.raises(ImportError):
         zb.load()
+
+
+def test_static_scratch_entry_point_refuses_oversize_problems_on_the_host():
+    """zc_decode_attention_static: a problem whose split-K partials exceed the library's
+    static buffer is refused before anything touches the GPU (so this runs without one)."""
+    lib = zb.load()
+    B, Hq, Hkv, D = 64, 32, 8, 128
+    assert lib.zc_decode_attention_workspace(B, Hq, D) > (8 << 20)
+    host = np.zeros((1, 4), np.int32)
+    def packed(layout, scheme):
+        return zb.zc_packed(layout, scheme, 4, 2, B, Hkv, D, 64, 64, 0, 0, 0x10000, 0x20000, 0x30000, 0x40000, 0x50000,
+                            0x60000, None, None, 0x70000, 0x80000, 0x90000, host.ctypes.data, 0, 1)
+    q = zb.zc_tensor4(0x1000, zb.ZC_BF16, 0, B, Hq, 1, D, Hq * D, D, D)
+    kp, vp = packed(zb.ZC_LAYOUT_ROW, zb.ZC_SCHEME_CHANNEL), packed(zb.ZC_LAYOUT_TGROUP, zb.ZC_SCHEME_CST)
+    rc = lib.zc_decode_attention_static(C.byref(q), C.byref(kp), C.byref(vp), None, None, 0, 0.0, 0x2000, None, None)
+    assert rc == -6 and b"static" in lib.zc_status_string(rc)
