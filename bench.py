@@ -372,6 +372,84 @@ def machine_peaks(args):
         }}))
 
 
+def latency_floor(args):
+    """What a launch costs on this GPU before it does any work - the terms a latency-bound call
+    (one decode step at batch 1 moves 3 MB: 0.4 us at the HBM peak) is made of.  Each line is
+    the median and minimum over `--steps` repetitions, HIP events around each repetition:
+      empty_eager        an empty kernel of 256 workgroups, 200 launches back to back, per launch
+      empty_graph_node   the same 200 launches as nodes of one HIP graph, per node
+      touch_graph_node   nodes that each make one trip to cold memory per workgroup and store a word
+      dependent_pair     two such kernels, the second reading what the first stored (a producer
+                         and its reduction), per pair, inside a graph
+      memory_trip        one wave chasing dependent loads through a 1 GiB table: microseconds per hop"""
+    import ctypes as C
+    lib = C.CDLL(os.path.join(ROOT, "paper_2405_14256_amd", "libzc_peaks.so"))
+    V, SZ, U32 = C.c_void_p, C.c_size_t, C.c_uint32
+    lib.zc_peak_empty.argtypes = [C.c_int, V]
+    lib.zc_peak_touch.argtypes = [V, SZ, SZ, C.c_int, U32, V, V]
+    lib.zc_peak_chase.argtypes = [V, SZ, U32, C.c_int, V, V]
+    dev = torch.device("cuda")
+    st = lambda: torch.cuda.current_stream().cuda_stream
+    WG, N = 256, 200
+    big = torch.randint(0, 2 ** 31 - 1, ((1 << 30) // 4,), dtype=torch.int32, device=dev)     # 1 GiB: beyond the last-level cache
+    nbytes = big.numel() * 4
+    d1 = torch.zeros(4096, dtype=torch.int32, device=dev)
+    d2 = torch.zeros(4096, dtype=torch.int32, device=dev)
+    # a permutation whose successor is always far away: i -> (i + 1 + 2^22 + odd offset) mod n is one cycle
+    n_tab = big.numel()
+    step = (1 << 22) + 12345
+    table = ((torch.arange(n_tab, dtype=torch.int64, device=dev) + step) % n_tab).to(torch.int32)
+    reps = max(args.steps, 5)
+
+    def graph_of(fn):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        torch.cuda.synchronize()
+        return g.replay
+
+    def timed(run, per):
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); run(); b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / per)
+        ts.sort()
+        return {"median_us": round(ts[len(ts) // 2], 3), "min_us": round(ts[0], 3)}
+
+    salt = [0]
+
+    def empties():
+        for _ in range(N):
+            assert lib.zc_peak_empty(WG, st()) == 0
+
+    def touches():
+        for i in range(N):      # every node reads lines no earlier node of this replay has read
+            assert lib.zc_peak_touch(big.data_ptr() + (i * 4096 * WG) % (nbytes // 2), nbytes // 2, 4096, WG, i, d1.data_ptr(), st()) == 0
+
+    def pairs():
+        for i in range(N // 2):
+            assert lib.zc_peak_touch(big.data_ptr() + (i * 4096 * WG) % (nbytes // 2), nbytes // 2, 4096, WG, i, d1.data_ptr(), st()) == 0
+            assert lib.zc_peak_touch(d1.data_ptr(), 4096 * 4, 16, 32, i, d2.data_ptr(), st()) == 0
+
+    out = {"empty_eager": timed(empties, N), "empty_graph_node": timed(graph_of(empties), N),
+           "touch_graph_node": timed(graph_of(touches), N), "dependent_pair": timed(graph_of(pairs), N // 2)}
+    hop = {}
+    for hops in (1, 33):
+        def chase(h=hops):
+            salt[0] = (salt[0] + 7919) % n_tab
+            assert lib.zc_peak_chase(table.data_ptr(), n_tab, salt[0], h, d2.data_ptr(), st()) == 0
+        hop[hops] = timed(chase, 1)
+    out["memory_trip"] = {"median_us": round((hop[33]["median_us"] - hop[1]["median_us"]) / 32, 3),
+                          "min_us": round((hop[33]["min_us"] - hop[1]["min_us"]) / 32, 3),
+                          "kernel_with_1_hop_us": hop[1], "kernel_with_33_hops_us": hop[33]}
+    print(json.dumps({"latency_floor": out, "workgroups_per_kernel": WG, "launches_per_repetition": N, "repetitions": reps}))
+
+
 def decode_sweep(args):
     """Decode entry point alone at the metric's layer shape, batch 1 -> 64: each size is
     timed "warm" (the same packed cache every call: it stays in the last-level cache) and
@@ -456,6 +534,9 @@ def main():
     ap.add_argument("--peaks", action="store_true",
                     help="instead of the step: time the machine-peak probes (streaming read, streaming copy, a loop "
                          "of matrix instructions) and print what this GPU attains as one JSON line")
+    ap.add_argument("--latency-floor", action="store_true",
+                    help="instead of the step: time what a launch costs before it does any work (empty kernels, "
+                         "graph nodes, a dependent pair, one trip to memory) and print it as one JSON line")
     ap.add_argument("--decode-sweep", action="store_true",
                     help="instead of the step: time the decode entry point alone at batch 1..64 of the "
                          "workload's layer shape, cold and warm caches, and print that table as one JSON line")
@@ -469,6 +550,9 @@ def main():
     zb.load()
     if args.peaks:
         machine_peaks(args)
+        return
+    if args.latency_floor:
+        latency_floor(args)
         return
     if args.decode_sweep:
         decode_sweep(args)

@@ -31,6 +31,25 @@ int zc_peak_copy(void* dst, const void* src, size_t bytes, void* stream);
  * (>= 4 bytes) receives a word only if an accumulator ends as NaN. */
 int zc_peak_mfma(int dtype, int workgroups, int iters, float* sink, void* stream);
 
+/* ---- latency probes: what a launch costs before it does any work -------------------
+ * An empty kernel of `workgroups` x 256 threads (every wave ends at once). */
+int zc_peak_empty(int workgroups, void* stream);
+
+/* One trip to memory and one store per workgroup: workgroup i reads the 16 bytes at
+ * src + ((i * stride_bytes) mod bytes) (lane 0 only), adds `salt` and stores the sum to
+ * dst[i].  With stride_bytes >= 4096 and a buffer larger than the last-level cache every
+ * read is a miss.  src 16-byte aligned, bytes a multiple of 16, dst holds `workgroups`
+ * words.  Two launches, the second reading the first one's dst as its src, make a
+ * dependent pair. */
+int zc_peak_touch(const void* src, size_t bytes, size_t stride_bytes, int workgroups, uint32_t salt,
+                  uint32_t* dst, void* stream);
+
+/* One wave follows `hops` dependent loads through `table` (n 32-bit entries, entry i
+ * holding the index of the next entry: the caller builds a permutation with far-apart
+ * successors) starting at entry `start`, and stores the index it ends at in *dst: the
+ * kernel's duration grows by one memory latency per hop. */
+int zc_peak_chase(const uint32_t* table, size_t n, uint32_t start, int hops, uint32_t* dst, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -77,6 +77,24 @@ __global__ __launch_bounds__(kThreads) void k_peak_mfma(int iters, float* sink) 
   if (s != s) *sink = s;
 }
 
+__global__ __launch_bounds__(kThreads) void k_peak_empty() {}
+
+__global__ __launch_bounds__(kThreads) void k_peak_touch(const uint8_t* __restrict__ src, size_t bytes, size_t stride,
+                                                         uint32_t salt, uint32_t* __restrict__ dst) {
+  if (threadIdx.x != 0) return;
+  const size_t off = ((size_t)blockIdx.x * stride) % bytes & ~(size_t)15;
+  const uint4 v = *reinterpret_cast<const uint4*>(src + off);
+  dst[blockIdx.x] = v.x + v.y + v.z + v.w + salt;
+}
+
+__global__ __launch_bounds__(64) void k_peak_chase(const uint32_t* __restrict__ table, size_t n, uint32_t start, int hops,
+                                                   uint32_t* __restrict__ dst) {
+  if (threadIdx.x != 0) return;
+  uint32_t i = start;
+  for (int h = 0; h < hops; ++h) i = __builtin_nontemporal_load(table + (i < n ? i : 0));   // (stays in bounds whatever the table holds)
+  *dst = i;
+}
+
 int grid_for(size_t n16) {
   // enough workgroups to keep every CU's request queues full, few enough that each
   // still loops: 16 per CU
@@ -115,5 +133,27 @@ extern "C" int zc_peak_mfma(int dtype, int workgroups, int iters, float* sink, v
   if (!sink || workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || (dtype != 1 && dtype != 2)) return -1;
   if (dtype == 2) hipLaunchKernelGGL(k_peak_mfma<true>, dim3(workgroups), dim3(kThreads), 0, (hipStream_t)stream, iters, sink);
   else hipLaunchKernelGGL(k_peak_mfma<false>, dim3(workgroups), dim3(kThreads), 0, (hipStream_t)stream, iters, sink);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+extern "C" int zc_peak_empty(int workgroups, void* stream) {
+  if (workgroups <= 0 || workgroups > (1 << 20)) return -1;
+  hipLaunchKernelGGL(k_peak_empty, dim3(workgroups), dim3(kThreads), 0, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+extern "C" int zc_peak_touch(const void* src, size_t bytes, size_t stride_bytes, int workgroups, uint32_t salt,
+                             uint32_t* dst, void* stream) {
+  if (!src || !dst || bytes < 16 || (bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || workgroups <= 0 ||
+      workgroups > (1 << 20))
+    return -1;
+  hipLaunchKernelGGL(k_peak_touch, dim3(workgroups), dim3(kThreads), 0, (hipStream_t)stream,
+                     static_cast<const uint8_t*>(src), bytes, stride_bytes, salt, dst);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+extern "C" int zc_peak_chase(const uint32_t* table, size_t n, uint32_t start, int hops, uint32_t* dst, void* stream) {
+  if (!table || !dst || n == 0 || start >= n || hops < 0 || hops > (1 << 20)) return -1;
+  hipLaunchKernelGGL(k_peak_chase, dim3(1), dim3(64), 0, (hipStream_t)stream, table, n, start, hops, dst);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }

@@ -35,7 +35,7 @@ def test_peak_probe_library_exports_its_header_and_checks_arguments():
     """The machine-peak probes of bench.py --peaks live in a library of their own."""
     src = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "zc_peaks.h")).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(zc_peak_[a-z_]+)\s*\(", src)))
-    assert names == ["zc_peak_copy", "zc_peak_mfma", "zc_peak_read"]
+    assert names == ["zc_peak_chase", "zc_peak_copy", "zc_peak_empty", "zc_peak_mfma", "zc_peak_read", "zc_peak_touch"]
     lib = C.CDLL(os.path.join(ROOT, "paper_2405_14256_amd", "libzc_peaks.so"))
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in zc_peaks.h but not exported"
@@ -51,6 +51,15 @@ def test_peak_probe_library_exports_its_header_and_checks_arguments():
     assert lib.zc_peak_mfma(0, 1, 1, 0x1000, None) == -1
     assert lib.zc_peak_mfma(2, 0, 1, 0x1000, None) == -1
     assert lib.zc_peak_mfma(2, 1, 1, None, None) == -1
+    lib.zc_peak_empty.argtypes = [C.c_int, C.c_void_p]
+    lib.zc_peak_touch.argtypes = [C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p]
+    lib.zc_peak_chase.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_int, C.c_void_p, C.c_void_p]
+    assert lib.zc_peak_empty(0, None) == -1
+    assert lib.zc_peak_touch(None, 64, 16, 1, 0, 0x1000, None) == -1
+    assert lib.zc_peak_touch(0x1000, 24, 16, 1, 0, 0x2000, None) == -1
+    assert lib.zc_peak_touch(0x1000, 64, 16, 0, 0, 0x2000, None) == -1
+    assert lib.zc_peak_chase(0x1000, 16, 16, 1, 0x2000, None) == -1          # start outside the table
+    assert lib.zc_peak_chase(0x1000, 16, 0, -1, 0x2000, None) == -1
 
 
 def test_struct_sizes_match_header_layout():

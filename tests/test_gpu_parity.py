@@ -614,6 +614,23 @@ def test_machine_peak_probes_run_and_copy_exactly():
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
     assert float(sink.abs().sum()) == 0.0
+    # latency probes: the touch kernel adds up the words it read, the chase ends where the table says
+    lib.zc_peak_empty.argtypes = [C.c_int, C.c_void_p]
+    lib.zc_peak_touch.argtypes = [C.c_void_p, C.c_size_t, C.c_size_t, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p]
+    lib.zc_peak_chase.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_int, C.c_void_p, C.c_void_p]
+    assert lib.zc_peak_empty(256, st) == 0
+    words = torch.arange(4096, dtype=torch.int32, device=DEV)
+    got = torch.zeros(8, dtype=torch.int32, device=DEV)
+    assert lib.zc_peak_touch(words.data_ptr(), 4096 * 4, 4096, 8, 5, got.data_ptr(), st) == 0
+    table = ((torch.arange(1000, dtype=torch.int64) * 7 + 3) % 1000).to(torch.int32)
+    end = torch.zeros(1, dtype=torch.int32, device=DEV)
+    assert lib.zc_peak_chase(table.to(DEV).data_ptr(), 1000, 11, 25, end.data_ptr(), st) == 0
+    torch.cuda.synchronize()
+    assert got.tolist() == [4 * (1024 * i % 4096) + 6 + 5 for i in range(8)]
+    i = 11
+    for _ in range(25):
+        i = int(table[i])
+    assert int(end[0]) == i
 
 
 def test_pipeline_randomized_configurations():
