@@ -87,6 +87,34 @@ def probe_attention(q_rows: np.ndarray, pos: np.ndarray, k: np.ndarray,
     return A, lse
 
 
+def prefill_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
+                      sm_scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 2's attention line: the prefill output of every token at once,
+    O = Softmax(Q K^T / sqrt(d)) V with the causal mask (Eq. 2 applied to V), and
+    the log-normaliser of every row (the natural log of its softmax denominator,
+    what a row needs to be re-normalised later: the probe rows of Eq. 9).
+
+    Q: [B, Hq, L, d]; K, V: [B, Hkv, L, d]; query head h reads KV head h // (Hq // Hkv).
+    Returns (O [B, Hq, L, d], lse [B, Hq, L])."""
+    Q = np.asarray(Q, F64)
+    K = np.asarray(K, F64)
+    V = np.asarray(V, F64)
+    B, Hq, L, d = Q.shape
+    G = Hq // K.shape[1]
+    O = np.zeros((B, Hq, L, d), F64)
+    lse = np.zeros((B, Hq, L), F64)
+    row = np.arange(L)[:, None]
+    col = np.arange(L)[None, :]
+    for b in range(B):
+        for h in range(Hq):
+            A = causal_attention(Q[b, h], K[b, h // G], sm_scale)
+            O[b, h] = A @ V[b, h // G]
+            S = np.where(col <= row, (Q[b, h] @ K[b, h // G].T) * _scale(d, sm_scale), -np.inf)
+            m = S.max(axis=1)
+            lse[b, h] = m + np.log(np.exp(S - m[:, None]).sum(axis=1))
+    return O, lse
+
+
 def unmasked_count(pos: np.ndarray, Lk: int) -> np.ndarray:
     """nnz(A[:, i]) of Eq. 8 read structurally: the number of probe rows whose
     causal window contains column i."""

@@ -159,3 +159,40 @@ def test_select_matches_sorted_brute_force(k):
 def test_select_tie_goes_to_lower_index():
     sal, reg = zo.select_salient(np.array([1.0, 3.0, 3.0, 3.0, 0.5]), 2)
     assert list(sal) == [1, 2] and list(reg) == [0, 3, 4]
+
+
+def test_prefill_attention_against_a_scalar_loop_and_library_routines():
+    """Algorithm 2's attention output and row normalisers: a scalar-loop evaluation of
+    o_p = sum_{i<=p} softmax_i(q_p . k_i / sqrt(d)) v_i with the grouped-head mapping,
+    scipy's logsumexp for the normaliser, and the special cases that have closed forms
+    (first row copies v_0; equal values are reproduced; Q = 0 gives running means)."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(12)
+    B, Hq, Hkv, L, d = 2, 4, 2, 9, 8
+    Q = rng.standard_normal((B, Hq, L, d)); K = rng.standard_normal((B, Hkv, L, d)); V = rng.standard_normal((B, Hkv, L, d))
+    O, lse = zo.prefill_attention(Q, K, V)
+    G = Hq // Hkv
+    for b in range(B):
+        for h in range(Hq):
+            for p in range(L):
+                logits = [sum(Q[b, h, p, c] * K[b, h // G, i, c] for c in range(d)) / math.sqrt(d) for i in range(p + 1)]
+                mx = max(logits)
+                w = [math.exp(x - mx) for x in logits]
+                for c in range(d):
+                    want = sum(w[i] * V[b, h // G, i, c] for i in range(p + 1)) / sum(w)
+                    assert abs(O[b, h, p, c] - want) < 1e-12
+                assert abs(lse[b, h, p] - logsumexp(logits)) < 1e-12
+    assert np.allclose(O[:, :, 0], np.repeat(V[:, :, 0], G, axis=1))             # the first token sees only itself
+    assert np.allclose(zo.prefill_attention(Q, K, np.ones_like(V) * 2.5)[0], 2.5)   # a convex combination
+    O0, lse0 = zo.prefill_attention(np.zeros_like(Q), K, V)                      # uniform attention: running means
+    means = np.cumsum(V, axis=2) / np.arange(1, L + 1)[None, None, :, None]
+    assert np.allclose(O0, np.repeat(means, G, axis=1)) and np.allclose(lse0, np.log(np.arange(1, L + 1)))
+    # the probe rows of Eq. 9 are rows of the same matrix: re-normalising with these log-normalisers
+    # reproduces them
+    pos = np.array([2, 5, 8])
+    A_rows, lse_rows = zo.probe_attention(Q[1, 3, pos], pos, K[1, 1])
+    assert np.allclose(lse_rows, lse[1, 3, pos])
+    assert np.allclose(A_rows @ V[1, 1], O[1, 3, pos])
+    # an override of the softmax scale is honoured
+    O2, _ = zo.prefill_attention(Q, K, V, sm_scale=0.3)
+    assert np.allclose(O2[0, 1], zo.causal_attention(Q[0, 1], K[0, 0], 0.3) @ V[0, 0]) and not np.allclose(O2, O)
