@@ -3,7 +3,8 @@
  * data-parallel hot path (arXiv 2405.14256).
  *
  * Four operations, in the order Algorithm 2 (prefill) and Algorithm 3 (decode)
- * use them:
+ * use them (and, beside them, the prefill attention of Algorithm 2 itself,
+ * zc_prefill_attention, whose row normalisers feed the first):
  *
  *   zc_probe_saliency    Eq. 9 + Eq. 8: normalized attention score of every
  *                        key token from a probe subset of query rows.
@@ -167,6 +168,24 @@ int zc_probe_accumulated(const zc_tensor4* q, const zc_tensor4* k,
                          float sm_scale, const float* lse_ext,
                          float* scores, float* scores_per_head,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Algorithm 2, the attention line (Eq. 2 applied to V; Appendix B, prefill) -------
+ * The attention output of all prompt tokens at once, with the causal mask:
+ *   out[b, h, p, :] = sum_{i <= p} softmax_i(q[b,h,p] . k[b,h/G,i] * sm_scale) v[b,h/G,i, :]
+ * q, out [B, Hq, L, D]; k, v [B, Hkv, L, D]; all four of one dtype (out may have strides of
+ * its own); sm_scale == 0 means 1/sqrt(D).  lse (device float [B, Hq, L], optional)
+ * receives the natural-log normaliser of every row.  With P > 0 the normalisers of the
+ * rows probe_pos[0..P) (device int32, values in [0, L)) are also gathered into lse_probe
+ * (device float [B, Hq, P]; needs lse): exactly the lse_ext argument with which
+ * zc_probe_saliency scores the same probe rows in one sweep instead of two.
+ * fp32 tensors are multiplied on the fp32 matrix pipes, never rounded to 16 bits; the
+ * probabilities of 16-bit tensors enter the second product rounded to the tensors' type.
+ * Needs no workspace; enqueued on `stream`.
+ * Errors: ZC_ERR_INVALID_ARG for mismatching shapes or types, ZC_ERR_UNSUPPORTED for a
+ * (batch, head) slab of 4 GiB or more. */
+int zc_prefill_attention(const zc_tensor4* q, const zc_tensor4* k, const zc_tensor4* v, float sm_scale,
+                         const zc_tensor4* out, float* lse,
+                         const int32_t* probe_pos, int32_t P, float* lse_probe, void* stream);
 
 /* ---- Algorithm 2, Split(., p~, r%) ------------------------------------------
  * scores: device float [B, L] (must not contain NaN).  For every batch row

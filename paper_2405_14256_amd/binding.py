@@ -72,6 +72,8 @@ def load() -> C.CDLL:
     lib.zc_probe_saliency.argtypes = [T4, T4, P, P, I32, F, P, P, P, P, SZ, P]
     lib.zc_probe_accumulated.restype = C.c_int
     lib.zc_probe_accumulated.argtypes = [T4, T4, P, P, I32, F, P, P, P, P, SZ, P]
+    lib.zc_prefill_attention.restype = C.c_int
+    lib.zc_prefill_attention.argtypes = [T4, T4, T4, F, T4, P, P, I32, P, P]
     lib.zc_select_salient_workspace.restype = SZ
     lib.zc_select_salient_workspace.argtypes = [I64, I64]
     lib.zc_select_salient.restype = C.c_int
@@ -216,6 +218,26 @@ def zc_probe_saliency(q: torch.Tensor, k: torch.Tensor, probe_pos: torch.Tensor,
 def zc_probe_accumulated(q: torch.Tensor, k: torch.Tensor, probe_pos: torch.Tensor, **kw) -> torch.Tensor:
     """Eq. 7: as zc_probe_saliency, without the division by the unmasked count."""
     return zc_probe_saliency(q, k, probe_pos, _entry="zc_probe_accumulated", **kw)
+
+
+def zc_prefill_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, sm_scale: float = 0.0,
+                         out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                         probe_pos: Optional[torch.Tensor] = None, lse_probe: Optional[torch.Tensor] = None):
+    """(out [B, Hq, L, D], lse [B, Hq, L], lse_probe [B, Hq, P] or None)."""
+    lib = load()
+    B, Hq, L, _ = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty(B, Hq, L, dtype=torch.float32, device=q.device)
+    P = int(probe_pos.numel()) if probe_pos is not None else 0
+    if P and lse_probe is None:
+        lse_probe = torch.empty(B, Hq, P, dtype=torch.float32, device=q.device)
+    tq, tk, tv, to = tensor4(q), tensor4(k), tensor4(v), tensor4(out)
+    _check("zc_prefill_attention",
+           lib.zc_prefill_attention(C.byref(tq), C.byref(tk), C.byref(tv), float(sm_scale), C.byref(to), _ptr(lse),
+                                    _ptr(probe_pos) if P else None, P, _ptr(lse_probe) if P else None, _stream()))
+    return out, lse, lse_probe
 
 
 def zc_select_salient(scores: torch.Tensor, k: int, salient_idx: Optional[torch.Tensor] = None,
