@@ -238,6 +238,38 @@ class HotPath:
         torch.cuda.synchronize()
         return capture(groups), group_name, capture([[i] for i in range(len(stages))])
 
+    def prefill_components(self, reps: int):
+        """Outside the step: the prefill attention of Algorithm 2 on the same inputs
+        (zc_prefill_attention, which also hands the probe rows' log-normalisers over) and the
+        probe stage run on those normalisers (one sweep instead of two); milliseconds, mean /
+        median / min over `reps` launches, HIP events around each."""
+        w = self.w
+        out = torch.empty_like(self.Q)
+        lse = torch.empty(w.B, w.Hq, w.L, dtype=torch.float32, device=self.Q.device)
+        lse_p = torch.empty(w.B, w.Hq, len(self.pos_np), dtype=torch.float32, device=self.Q.device)
+        scores = torch.empty_like(self.scores)
+
+        def timed(fn):
+            fn(); fn()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); fn(); e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            ts.sort()
+            return {"mean": round(sum(ts) / len(ts), 5), "median": round(ts[len(ts) // 2], 5), "min": round(ts[0], 5)}
+
+        pf = timed(lambda: zb.zc_prefill_attention(self.Q, self.K, self.V, out=out, lse=lse, probe_pos=self.pos, lse_probe=lse_p))
+        pr = timed(lambda: zb.zc_probe_saliency(self.Q, self.K, self.pos, lse_ext=lse_p, scores=scores))
+        flops = 4.0 * w.d * (w.L * (w.L + 1) / 2.0) * w.Hq * w.B          # unmasked (row, key) pairs, two products
+        rel = float(((scores - self.scores).abs().max() / self.scores.abs().max()).item())
+        assert rel <= 1e-4, f"one-sweep probe scores differ from the step's by {rel:.2e}"
+        return {"prefill_attention_ms": pf, "prefill_attention_TFLOPs": flops / (pf["mean"] * 1e-3) / 1e12,
+                "probe_saliency_given_prefill_lse_ms": pr,
+                "probe_saliency_given_prefill_lse_TFLOPs": self.probe_flops() / (pr["mean"] * 1e-3) / 1e12}
+
     def decode_cold(self, reps: int):
         """Decode calls on the cache as the step leaves it, rotating through copies of it
         that together exceed 512 MiB, so that no call finds its lines in the last-level
@@ -527,7 +559,8 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_4k")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache decode pass after the timed region")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the passes after the timed region (cold-cache decode, prefill attention and the one-sweep probe)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run three plain copies of 256 MiB (a kernel of known traffic, "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -609,6 +642,7 @@ def main():
     quant_gbps = hp.quant_bytes() / (st_ms["quantize"]["mean"] * 1e-3) / 1e9
     probe_tflops = hp.probe_flops() / (st_ms["probe"]["mean"] * 1e-3) / 1e12
     cold = None if args.no_cold else hp.decode_cold(max(args.steps, 5))
+    prefill = None if args.no_cold else hp.prefill_components(max(args.steps, 5))
     traffic = measured_decode_traffic(w.name)
 
     result = {
@@ -629,6 +663,7 @@ def main():
             "compress_ms": st_ms.get("compress", {"mean": 0.0})["mean"],
             "per_step_ms": {n: {k: round(v, 5) for k, v in d.items()} for n, d in st_ms.items()},
             "decode_us_per_launch": {"warm": {k: round(v, 3) for k, v in dec_us.items()}, "cold": cold},
+            "prefill": prefill,
             "timing": "HIP events between the graphs inside the timed region (decode, flush, compress = probe + select + "
                       "quantize as one graph), mean / median / min over the timed steps; probe / select / quantize alone "
                       "from a second pass with one graph per stage; decode 'warm' is the timed region itself (one layer: "

@@ -20,9 +20,10 @@ throughout (tokens and channels are 0-indexed):
   * A degenerate group with max == min takes s := 1; a channel whose maximum
     magnitude is 0 takes c := 1.
 
-Parity pins live in tests/test_oracle_*.py; the streaming (tail flush) reading
-of Algorithm 3 is pinned only by self-consistency ("parity unpinned" by the
-paper, whose text is ambiguous there).
+Parity pins live in tests/test_oracle_*.py; both readings of Algorithm 3's
+re-compression branch (StreamingCache: chunk-local; LiteralStreamingCache: the
+text taken at its word) are pinned only by self-consistency ("parity unpinned"
+by the paper, whose text is ambiguous there).
 """
 from __future__ import annotations
 
@@ -460,6 +461,133 @@ class StreamingCache:
         self.n_packed += tk.shape[2]
         self.tail_k, self.tail_v = [], []
         self.probe_q, self.probe_lse, self.probe_pos = [], [], []
+        return scores, sal, reg
+
+
+# --------------------------------------------------------------------------
+# Algorithm 3 read literally: explicit attention rows of the probe steps,
+# re-compression of everything but the newest `interval` tokens
+# --------------------------------------------------------------------------
+
+def round_to_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
+    """x rounded to the nearest value of a storage type ("fp32", "fp16", "bf16";
+    ties to even), returned as float64."""
+    x = np.asarray(x, F64)
+    if dtype == "fp32":
+        return x.astype(np.float32).astype(F64)
+    if dtype == "fp16":
+        return x.astype(np.float16).astype(F64)
+    if dtype == "bf16":
+        # 8 significant bits: x = m 2^e with 1/2 <= |m| < 1, so m 2^8 is rounded to an integer
+        # (numpy.rint: ties to even) directly on the float64 value - no detour through fp32,
+        # which would round twice.  (Values below bf16's normal range, 2^-126, do not occur.)
+        m, e = np.frexp(x)
+        return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+    raise ValueError(dtype)
+
+
+def cache_positions(chunks: List[QuantChunk], n_tail: int, tail_pos0: int) -> np.ndarray:
+    """[B, N] original token position of every column of `cache_matrices`
+    (chunk by chunk: salient subset, regular subset; then the tail)."""
+    cols = []
+    for ck in chunks:
+        cols += [ck.hi.idx, ck.lo.idx]
+    B = cols[0].shape[0] if cols else 1
+    cols.append(np.tile(np.arange(tail_pos0, tail_pos0 + n_tail), (B, 1)))
+    return np.concatenate(cols, axis=1).astype(np.int64)
+
+
+def rows_saliency(rows: Sequence[np.ndarray], normalized: bool = True) -> np.ndarray:
+    """Eq. 8 on explicit attention rows: rows[j] is [B, Hq, n_j], the probabilities of
+    probe j over the n_j tokens it could see (token order), n_j non-decreasing.
+    score[b, i] = mean over heads of (sum of rows that see token i) / (their number);
+    a token no row sees scores 0.  Returns [B, n_max]."""
+    n = max(r.shape[2] for r in rows)
+    B, Hq = rows[0].shape[:2]
+    tot = np.zeros((B, Hq, n), F64)
+    cnt = np.zeros(n, F64)
+    for r in rows:
+        tot[:, :, :r.shape[2]] += np.asarray(r, F64)
+        cnt[:r.shape[2]] += 1.0
+    if normalized:
+        tot = np.where(cnt > 0, tot / np.maximum(cnt, 1.0), 0.0)
+    return tot.mean(axis=1)
+
+
+@dataclass
+class LiteralStreamingCache:
+    """Algorithm 3 taken at its word.  Every decode step appends k, v in full precision and
+    attends over the whole cache; a probe step also keeps its attention row a (Eq. 4's
+    probabilities, in token order).  After every `interval` steps, everything except the
+    newest `interval` tokens - "K[:-100]": the tokens compressed earlier, as they now are
+    (de-quantized, rounded to the cache's storage type), and the full-precision tokens
+    older than the window - is compressed again as one whole by Algorithm 2's
+    compression part: normalized scores (Eq. 8) from this window's probe rows, Split at
+    r %, ChannelQuant / CSTQuant per subset.  A token can so move between the salient
+    and the regular subset, and every re-compression quantizes de-quantized values.
+    The probe rows are dropped after each re-compression."""
+    Hkv: int
+    store_dtype: str = "fp32"
+    bits_hi: int = 4
+    bits_lo: int = 2
+    k_scheme: str = "channel"
+    v_scheme: str = "cst"
+    interval: int = 100
+    chunk_K: Optional[QuantChunk] = None        # the compressed part: one chunk, positions 0 .. n_packed-1
+    chunk_V: Optional[QuantChunk] = None
+    n_packed: int = 0
+    fp_k: List[np.ndarray] = field(default_factory=list)    # full-precision tokens, positions n_packed ..
+    fp_v: List[np.ndarray] = field(default_factory=list)
+    rows: List[np.ndarray] = field(default_factory=list)    # probe rows [B, Hq, n_j], token order
+
+    def _matrices(self):
+        tk = np.stack(self.fp_k, axis=2) if self.fp_k else None
+        tv = np.stack(self.fp_v, axis=2) if self.fp_v else None
+        ck = [self.chunk_K] if self.chunk_K is not None else []
+        cv = [self.chunk_V] if self.chunk_V is not None else []
+        Kc, Vc = cache_matrices(ck, cv, self.Hkv, tk, tv)
+        pos = cache_positions(ck, len(self.fp_k), self.n_packed)
+        return Kc, Vc, pos
+
+    def step(self, q, k_new, v_new, is_probe: bool, sm_scale=None):
+        self.fp_k.append(np.asarray(k_new, F64))
+        self.fp_v.append(np.asarray(v_new, F64))
+        Kc, Vc, pos = self._matrices()
+        out, lse, probs = decode_attention(q, Kc, Vc, sm_scale)
+        row = np.zeros_like(probs)
+        for b in range(probs.shape[0]):
+            row[b][:, pos[b]] = probs[b]                      # token order
+        if is_probe:
+            self.rows.append(row)
+        return out, lse, row
+
+    def token_matrices(self):
+        """The cache in token order as it would be compressed again: [B, Hkv, n, d] of
+        de-quantized (and storage-rounded) packed tokens followed by the full-precision ones."""
+        Kc, Vc, pos = self._matrices()
+        B = Kc.shape[0]
+        Kt, Vt = np.zeros_like(Kc), np.zeros_like(Vc)
+        npk = self.n_packed
+        for b in range(B):
+            Kt[b][:, pos[b]] = Kc[b]
+            Vt[b][:, pos[b]] = Vc[b]
+        Kt[:, :, :npk] = round_to_dtype(Kt[:, :, :npk], self.store_dtype)
+        Vt[:, :, :npk] = round_to_dtype(Vt[:, :, :npk], self.store_dtype)
+        return Kt, Vt
+
+    def recompress(self, salient_ratio: float):
+        """The `i == 100` branch.  Returns (scores [B, m], salient, regular) over the
+        m = n - interval tokens that were compressed."""
+        Kt, Vt = self.token_matrices()
+        n = Kt.shape[2]
+        m = n - self.interval
+        scores = rows_saliency(self.rows)[:, :m]
+        k = int(np.floor(salient_ratio * m + 1e-9))
+        ck, cv, sal, reg = compress_prefill(Kt[:, :, :m], Vt[:, :, :m], scores, k, self.bits_hi, self.bits_lo,
+                                            self.k_scheme, self.v_scheme)
+        self.chunk_K, self.chunk_V, self.n_packed = ck, cv, m
+        self.fp_k, self.fp_v = self.fp_k[-self.interval:], self.fp_v[-self.interval:]
+        self.rows = []
         return scores, sal, reg
 
 
