@@ -228,6 +228,37 @@ int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packe
                         float sm_scale, void* out, float* lse_out,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* ---- Algorithm 3 with its re-compression branch taken at its word ----------------------
+ * ("Extract K[:-100] and V[:-100] and adaptively compress them with A_probe": every 100
+ * steps everything but the newest 100 tokens is compressed again as a whole, ranked by the
+ * explicit attention rows of the window's probe steps.)  Three building blocks; together
+ * with zc_select_salient and zc_quantize_pack into a fresh zc_packed they make that branch.
+ *
+ * zc_decode_probs: the attention row a of one decode step (Eq. 4's probabilities; the
+ * "Compute attention scores a of current token" line), in token order:
+ *   probs_out[b, h, pos] = exp(q[b,h] . k_hat[b, h/G, pos] * sm_scale - lse[b, h])
+ * over every token of Kp (at its stored position: Kp needs its pos arrays) and the first
+ * tail_len rows of tail_k (token tail_pos0 + t).  lse (device float [B, Hq]) is the
+ * normaliser zc_decode_attention returned for the same step; probs_out is device float
+ * [B, Hq, N], N >= tail_pos0 + tail_len, and entries of positions the cache does not hold
+ * are left untouched.  Arguments as for zc_decode_attention otherwise.
+ *
+ * zc_rows_saliency: Eq. 8 on explicit rows.  rows is device float [P, B, Hq, row_stride]
+ * (row j valid for tokens i < row_len[j]; row_len device int32 [P]):
+ *   scores[b, i] = mean over heads of sum_{j : row_len[j] > i} rows[j, b, h, i] / #{j : row_len[j] > i}
+ * for i < n_out (scores: device float [B, n_out]; 0 where no row sees the token; without the
+ * division when normalize == 0: Eq. 7).  Deterministic (fixed summation order).
+ *
+ * zc_dequantize_cache: out[b, h, pos, :] = x_hat of every token of p (all chunks), rounded to
+ * out's dtype, at its stored position (p needs its pos arrays; positions >= out->L are
+ * skipped).  out [B, H, L', D] is typically the caller's full-precision token buffer, whose
+ * rows pos >= (tokens in p) already hold the tokens not compressed yet. */
+int zc_decode_probs(const zc_tensor4* q, const zc_packed* Kp, const zc_tensor4* tail_k, int64_t tail_len,
+                    int64_t tail_pos0, float sm_scale, const float* lse, float* probs_out, int64_t N, void* stream);
+int zc_rows_saliency(const float* rows, const int32_t* row_len, int32_t P, int64_t B, int64_t Hq,
+                     int64_t row_stride, int64_t n_out, int32_t normalize, float* scores, void* stream);
+int zc_dequantize_cache(const zc_packed* p, const zc_tensor4* out, void* stream);
+
 /* ---- zc_decode_attention for callers that cannot allocate ----------------------------
  * For code under HIP graph capture, tight serving loops and harnesses that forbid
  * hipMalloc: the same operation, arguments, kernels and results as zc_decode_attention,

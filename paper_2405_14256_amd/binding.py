@@ -88,6 +88,12 @@ def load() -> C.CDLL:
     lib.zc_decode_attention.argtypes = [T4, PK, PK, T4, T4, I64, F, P, P, P, SZ, P]
     lib.zc_decode_attention_static.restype = C.c_int
     lib.zc_decode_attention_static.argtypes = [T4, PK, PK, T4, T4, I64, F, P, P, P]
+    lib.zc_decode_probs.restype = C.c_int
+    lib.zc_decode_probs.argtypes = [T4, PK, T4, I64, I64, F, P, P, I64, P]
+    lib.zc_rows_saliency.restype = C.c_int
+    lib.zc_rows_saliency.argtypes = [P, P, I32, I64, I64, I64, I64, I32, P, P]
+    lib.zc_dequantize_cache.restype = C.c_int
+    lib.zc_dequantize_cache.argtypes = [PK, T4, P]
     lib.zc_unpack.restype = C.c_int
     lib.zc_unpack.argtypes = [PK, I32, I32, P, P, P]
     lib.zc_arena_bytes.restype = SZ
@@ -324,4 +330,41 @@ def zc_decode_attention_static(q: torch.Tensor, Kp: PackedTensor, Vp: PackedTens
            lib.zc_decode_attention_static(C.byref(tq), C.byref(Kp.c), C.byref(Vp.c),
                                           C.byref(ttk) if tail_len else None, C.byref(ttv) if tail_len else None,
                                           tail_len, float(sm_scale), out.data_ptr(), _ptr(lse_out), _stream()))
+    return out
+
+
+def zc_decode_probs(q: torch.Tensor, Kp: PackedTensor, tail_k: Optional[torch.Tensor], tail_len: int, tail_pos0: int,
+                    lse: torch.Tensor, probs_out: torch.Tensor, sm_scale: float = 0.0) -> torch.Tensor:
+    """probs_out [B, Hq, N] (token order) of one decode step; lse from zc_decode_attention."""
+    lib = load()
+    if q.dim() == 3:
+        q = q.unsqueeze(2)
+    assert probs_out.dim() == 3 and probs_out.is_contiguous() and probs_out.dtype == torch.float32
+    tq = tensor4(q)
+    ttk = tensor4(tail_k) if tail_len else None
+    _check("zc_decode_probs",
+           lib.zc_decode_probs(C.byref(tq), C.byref(Kp.c), C.byref(ttk) if tail_len else None, tail_len, tail_pos0,
+                               float(sm_scale), lse.data_ptr(), probs_out.data_ptr(), probs_out.shape[2], _stream()))
+    return probs_out
+
+
+def zc_rows_saliency(rows: torch.Tensor, row_len: torch.Tensor, n_out: int, normalize: bool = True,
+                     scores: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """rows [P, B, Hq, N] float32, row_len int32 [P] -> scores [B, n_out]."""
+    lib = load()
+    P, B, Hq, N = rows.shape
+    assert rows.is_contiguous() and rows.dtype == torch.float32 and row_len.dtype == torch.int32
+    if scores is None:
+        scores = torch.empty(B, n_out, dtype=torch.float32, device=rows.device)
+    _check("zc_rows_saliency",
+           lib.zc_rows_saliency(rows.data_ptr(), row_len.data_ptr(), P, B, Hq, N, n_out, int(normalize),
+                                scores.data_ptr(), _stream()))
+    return scores
+
+
+def zc_dequantize_cache(p: PackedTensor, out: torch.Tensor) -> torch.Tensor:
+    """Scatters x_hat of every token of `p` to out[b, h, position, :]."""
+    lib = load()
+    to = tensor4(out)
+    _check("zc_dequantize_cache", lib.zc_dequantize_cache(C.byref(p.c), C.byref(to), _stream()))
     return out

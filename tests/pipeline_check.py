@@ -147,7 +147,7 @@ def compare_subset(g: zo.QuantSubset, o: zo.QuantSubset, what: str) -> Dict[str,
 CODE_COUNTS = ("n_codes", "n_mismatch", "n_raw_mismatch", "n_raw_unshifted", "n_groups", "n_zero_mismatch")
 
 
-def assert_code_budgets(tot: Dict[str, int], what: str) -> Dict[str, float]:
+def assert_code_budgets(tot: Dict[str, int], what: str, level_budget: float = CODE_MISMATCH_BUDGET) -> Dict[str, float]:
     """The budgets of the code rule over everything `tot` has summed up (CODE_COUNTS).
     At most 1e-4 of the levels differ; at most 1e-4 of the zero points differ (one of
     them when there are fewer than 10^4 groups: a single tie must not fail a small
@@ -158,12 +158,12 @@ def assert_code_budgets(tot: Dict[str, int], what: str) -> Dict[str, float]:
     n = max(tot["n_codes"], 1)
     out = {"raw_identical_frac": 1.0 - tot["n_raw_mismatch"] / n, "code_mismatch_frac": tot["n_mismatch"] / n,
            "zero_mismatch_frac": tot["n_zero_mismatch"] / max(tot["n_groups"], 1)}
-    assert out["code_mismatch_frac"] <= CODE_MISMATCH_BUDGET, f"{what}: {out['code_mismatch_frac']:.3e} of the levels differ"
-    assert tot["n_raw_unshifted"] / n <= CODE_MISMATCH_BUDGET, f"{what}: {tot['n_raw_unshifted']} stored codes differ"
+    assert out["code_mismatch_frac"] <= level_budget, f"{what}: {out['code_mismatch_frac']:.3e} of the levels differ"
+    assert tot["n_raw_unshifted"] / n <= level_budget, f"{what}: {tot['n_raw_unshifted']} stored codes differ"
     assert tot["n_zero_mismatch"] <= max(1, int(np.floor(ZERO_MISMATCH_BUDGET * tot["n_groups"]))), \
         f"{what}: {tot['n_zero_mismatch']} of {tot['n_groups']} zero points differ"
     if tot["n_groups"] >= 1.0 / ZERO_MISMATCH_BUDGET:
-        assert out["raw_identical_frac"] >= 1.0 - CODE_MISMATCH_BUDGET, \
+        assert out["raw_identical_frac"] >= 1.0 - level_budget, \
             f"{what}: only {out['raw_identical_frac']:.6f} of the stored codes are identical"
     return out
 
