@@ -254,15 +254,24 @@ class QuantSubset:
     tok_scale: np.ndarray    # [B, n]
     tok_zero: np.ndarray     # [B, n]
     pre_round: Optional[np.ndarray] = None  # x/s before rounding (diagnostics)
+    grp_scale: Optional[np.ndarray] = None  # groupwise only: [B, n, W / group]
+    grp_zero: Optional[np.ndarray] = None
 
     def dequant(self) -> np.ndarray:
+        if self.scheme == "group":
+            g = self.codes.shape[2] // self.grp_scale.shape[2]
+            return (self.codes - np.repeat(self.grp_zero, g, axis=2)) * np.repeat(self.grp_scale, g, axis=2)
         return (self.chan_scale[:, None, :] * self.tok_scale[:, :, None]
                 * (self.codes - self.tok_zero[:, :, None] - self.chan_zero[:, None, :]))
 
 
-def quantize_rows(X: np.ndarray, bits: int, scheme: str, idx: Optional[np.ndarray] = None) -> QuantSubset:
+def quantize_rows(X: np.ndarray, bits: int, scheme: str, idx: Optional[np.ndarray] = None,
+                  group: int = 32) -> QuantSubset:
     """Quantize token rows X [B, n, W] of one subset.
 
+    scheme "group": groupwise quantization, the fine-grained baseline of Table 1 and
+      Appendix A (Eq. A): every `group` consecutive channels of a token row share one
+      (s, z) of Eq. 5 - 2 l h d / n parameters per tensor.
     scheme "channel": one (s, z) per channel over the subset's tokens (the
       paper's key-cache scheme, Section 4.1).
     scheme "cst": Algorithm 1 - c_i = sqrt(max |X_i|), X_i /= c_i, tokenwise
@@ -280,6 +289,14 @@ def quantize_rows(X: np.ndarray, bits: int, scheme: str, idx: Optional[np.ndarra
     if n == 0:
         return QuantSubset(scheme, bits, idx, np.zeros((B, 0, W)), ones_c, zeros_c, ones_t, zeros_t,
                            np.zeros((B, 0, W)))
+    if scheme == "group":
+        assert W % group == 0
+        Xg = X.reshape(B, n, W // group, group)
+        lo, hi = Xg.min(axis=3), Xg.max(axis=3)                          # [B, n, W / group]
+        s, z = quant_params(lo, hi, bits)
+        codes, pre = quantize(Xg, lo[..., None], hi[..., None], bits)
+        return QuantSubset(scheme, bits, idx, codes.reshape(B, n, W), ones_c, zeros_c, ones_t, zeros_t,
+                           pre.reshape(B, n, W), s, z)
     if scheme == "channel":
         lo, hi = X.min(axis=1), X.max(axis=1)                            # [B, W]
         s, z = quant_params(lo, hi, bits)

@@ -199,3 +199,37 @@ def test_published_mixed_ratios_are_bracketed():
         vals = [zo.compression_ratio("channel+cst", 8, 4096, int(l), 4, 2, float(ratio), subsets=s)
                 for s in (1, 2)]
         assert min(abs(v - float(printed)) for v in vals) <= 0.025, (ratio, l, vals)
+
+
+def test_groupwise_quantization_pins():
+    """Groupwise quantization (Table 1's first row, Appendix A Eq. A): every group of n channels
+    of a token row is Eq. 5 on its own - checked group by group against the scalar quantizer, by
+    the half-step error bound per group, by its two limits (one group per row = tokenwise; the
+    parameter count 2 l h d / n per tensor) and by data already on a group's grid."""
+    rng = np.random.default_rng(8)
+    B, n, W, g = 2, 5, 64, 32
+    X = rng.standard_normal((B, n, W)) * (1 + 9 * (rng.random((1, 1, W)) > 0.9))
+    q = zo.quantize_rows(X, 4, "group", group=g)
+    assert q.grp_scale.shape == (B, n, W // g) and q.codes.min() >= 0 and q.codes.max() <= 15
+    xh = q.dequant()
+    for b in range(B):
+        for t in range(n):
+            for j in range(W // g):
+                grp = X[b, t, j * g:(j + 1) * g]
+                s, z = zo.quant_params(grp.min(), grp.max(), 4)
+                codes, _ = zo.quantize(grp, grp.min(), grp.max(), 4)
+                assert np.array_equal(q.codes[b, t, j * g:(j + 1) * g], codes)
+                assert q.grp_scale[b, t, j] == s and q.grp_zero[b, t, j] == z
+                assert np.all(np.abs(xh[b, t, j * g:(j + 1) * g] - grp) <= s / 2 + 1e-12)
+    # outlier channels only hurt their own group: error of a group without outliers is far below tokenwise
+    tok = zo.quantize_rows(X, 4, "token")
+    assert np.abs(xh - X).mean() < np.abs(tok.dequant() - X).mean()
+    # one group per row is plain tokenwise quantization
+    one = zo.quantize_rows(X, 4, "group", group=W)
+    assert np.array_equal(one.codes, tok.codes) and np.allclose(one.dequant(), tok.dequant())
+    # parameters: 2 (s, z) per group; keys and values together 4 b h d l / n (Table 1)
+    assert 2 * (q.grp_scale.size + q.grp_zero.size) == zo.quant_param_count("groupwise", B, W, n, g)
+    # integers 0..3 in every group round-trip exactly at 2 bits
+    Xi = np.tile(np.arange(4.0), (B, n, W // 4))
+    qi = zo.quantize_rows(Xi, 2, "group", group=8)
+    assert np.array_equal(qi.codes, Xi) and np.all(qi.grp_scale == 1.0) and np.all(qi.grp_zero == 0.0)
