@@ -482,6 +482,109 @@ def latency_floor(args):
     print(json.dumps({"latency_floor": out, "workgroups_per_kernel": WG, "launches_per_repetition": N, "repetitions": reps}))
 
 
+def error_report(workload: str, decode_queries: int = 16, max_batch: int = 2):
+    """Reconstruction and attention error against compression ratio for the quantization
+    granularities of Table 1 (groupwise n = 32, tokenwise, channelwise keys with tokenwise or
+    channel-separable tokenwise values) and for the two saliency metrics (Eq. 7 accumulated,
+    Eq. 8 normalized) on a synthetic workload - what stands in for the paper's accuracy
+    columns, which need datasets and weights.  Everything is computed by the library on the
+    GPU: zc_quantize_pack + zc_unpack (zc_group_quantize for groupwise) for x_hat,
+    zc_decode_attention over the packed cache (over x_hat as a full-precision tail for
+    groupwise) against zc_decode_attention over the unquantized tensors for the attention
+    error; torch only takes norms of differences.  Batch elements beyond `max_batch` are left
+    out (the errors are per-token statistics)."""
+    import dataclasses
+    from oracle import zipcache_oracle as zo          # Appendix A's accounting formulas only
+    w0 = WORKLOADS[workload]
+    w = dataclasses.replace(w0, B=min(w0.B, max_batch))
+    dev = torch.device("cuda")
+    lib = zb.load()
+    inp = make_prefill(w)
+    Q, K, V = (inp[n].to(dev) for n in ("Q", "K", "V"))
+    pos = torch.from_numpy(probes.probe_positions(w.L, w.probe_ratio, w.seed)).to(dev)
+    qs = torch.stack([make_decode_step(w, j)["q"] for j in range(decode_queries)], dim=0).to(dev)    # [n, B, Hq, d]
+    f32 = dict(dtype=torch.float32, device=dev)
+
+    def empty_cache():
+        mk = lambda s, l: zb.PackedTensor(w.B, w.Hkv, w.d, 64, 64, 4, 2, s, l, max_chunks=1, device="cuda")
+        return mk("channel", zb.ZC_LAYOUT_ROW), mk("cst", zb.ZC_LAYOUT_TGROUP)
+
+    def attend_tail(Kt, Vt):
+        Ke, Ve = empty_cache()
+        return torch.stack([zb.zc_decode_attention(qs[j], Ke, Ve, Kt, Vt, w.L).float() for j in range(decode_queries)])
+
+    def attend_packed(Kp, Vp):
+        return torch.stack([zb.zc_decode_attention(qs[j], Kp, Vp).float() for j in range(decode_queries)])
+
+    o_ref = attend_tail(K, V)
+
+    def rel_mse(xh, X):
+        X = X.float()
+        return float(((xh - X) ** 2).sum() / (X ** 2).sum())
+
+    def x_hat(P):
+        """[B, H, L, d] de-quantized tensor of a packed cache (token order)."""
+        out = torch.zeros(w.B, w.Hkv, w.L, w.d, **f32)
+        zb.zc_dequantize_cache(P, out)
+        return out
+
+    def pack(scheme_k, scheme_v, bits_hi, bits_lo, sal, reg):
+        cap_hi, cap_lo = lib.zc_arena_slots(sal.shape[1], 1), lib.zc_arena_slots(reg.shape[1], 1)
+        Kp = zb.PackedTensor(w.B, w.Hkv, w.d, cap_hi, cap_lo, bits_hi, bits_lo, scheme_k, zb.ZC_LAYOUT_ROW, max_chunks=1, device="cuda")
+        Vp = zb.PackedTensor(w.B, w.Hkv, w.d, cap_hi, cap_lo, bits_hi, bits_lo, scheme_v, zb.ZC_LAYOUT_TGROUP, max_chunks=1, device="cuda")
+        zb.zc_quantize_pack(K, sal, reg, Kp)
+        zb.zc_quantize_pack(V, sal, reg, Vp)
+        return Kp, Vp
+
+    def out_err(o):
+        return float((o - o_ref).norm() / o_ref.norm())
+
+    scores = zb.zc_probe_saliency(Q, K, pos)
+    sal, reg = zb.zc_select_salient(scores, w.k_salient)
+    all_idx, none_idx = zb.zc_select_salient(scores, w.L)
+    hd, ratio = w.W, w.salient_ratio
+    rows = []
+    for bits_hi, bits_lo, s_idx, r_idx, label in ((4, 4, all_idx, none_idx, "4/4"), (w.bits_hi, w.bits_lo, sal, reg, f"{w.bits_hi}/{w.bits_lo}")):
+        mixed = label != "4/4"
+        for ks, vs, gran in (("group", "group", "groupwise"), ("token", "token", "tokenwise"),
+                             ("channel", "token", "channel+token"), ("channel", "cst", "channel+cst")):
+            if ks == "group":
+                parts_k, parts_v = torch.zeros(w.B, w.L, w.W, **f32), torch.zeros(w.B, w.L, w.W, **f32)
+                for idx, bits in ((s_idx, bits_hi), (r_idx, bits_lo)):
+                    if idx.shape[1] == 0:
+                        continue
+                    for X, dst in ((K, parts_k), (V, parts_v)):
+                        _, _, _, dq = zb.zc_group_quantize(X, bits, 32, idx, codes=False)
+                        dst.scatter_(1, idx.long()[:, :, None].expand(-1, -1, w.W), dq)
+                Kh = parts_k.view(w.B, w.L, w.Hkv, w.d).permute(0, 2, 1, 3).contiguous()
+                Vh = parts_v.view(w.B, w.L, w.Hkv, w.d).permute(0, 2, 1, 3).contiguous()
+                o = attend_tail(Kh.to(w.torch_dtype), Vh.to(w.torch_dtype))
+            else:
+                Kp, Vp = pack(ks, vs, bits_hi, bits_lo, s_idx, r_idx)
+                Kh, Vh = x_hat(Kp), x_hat(Vp)
+                o = attend_packed(Kp, Vp)
+            cr = zo.compression_ratio(gran, w.B, hd, w.L, bits_hi, bits_lo if mixed else None, ratio if mixed else 1.0,
+                                      subsets=2 if mixed else 1)
+            rows.append({"k_scheme": ks, "v_scheme": vs, "bits": label, "k_rel_mse": rel_mse(Kh, K), "v_rel_mse": rel_mse(Vh, V),
+                         "attn_out_rel_err": out_err(o), "compression_ratio": cr})
+    # Eq. 7 against Eq. 8: which tokens get the high bit width, and what that does to the output
+    sal_rows = []
+    full = torch.arange(w.L, dtype=torch.int32, device=dev)
+    for name, fn in (("normalized (Eq. 8)", zb.zc_probe_saliency), ("accumulated (Eq. 7)", zb.zc_probe_accumulated)):
+        sc = fn(Q, K, pos)
+        s_i, r_i = zb.zc_select_salient(sc, w.k_salient)
+        Kp, Vp = pack("channel", "cst", w.bits_hi, w.bits_lo, s_i, r_i)
+        sc_full = fn(Q, K, full)                        # the same metric from the full attention matrix
+        s_full, _ = zb.zc_select_salient(sc_full, w.k_salient)
+        overlap = float(np.mean([len(set(s_i[b].tolist()) & set(s_full[b].tolist())) / max(w.k_salient, 1) for b in range(w.B)]))
+        sal_rows.append({"metric": name, "attn_out_rel_err": out_err(attend_packed(Kp, Vp)),
+                         "mean_salient_position": float(s_i.float().mean()) / w.L,
+                         "overlap_with_full_matrix_selection": overlap})
+    torch.cuda.synchronize()
+    return {"error_report": workload, "batch_elements": w.B, "seq_len": w.L, "decode_queries": decode_queries,
+            "salient_ratio": ratio, "granularities": rows, "saliency_metrics": sal_rows}
+
+
 def decode_sweep(args):
     """Decode entry point alone at the metric's layer shape, batch 1 -> 64: each size is
     timed "warm" (the same packed cache every call: it stays in the last-level cache) and
@@ -570,6 +673,9 @@ def main():
     ap.add_argument("--latency-floor", action="store_true",
                     help="instead of the step: time what a launch costs before it does any work (empty kernels, "
                          "graph nodes, a dependent pair, one trip to memory) and print it as one JSON line")
+    ap.add_argument("--error-report", action="store_true",
+                    help="instead of the step: reconstruction and attention error against compression ratio for the "
+                         "granularities of Table 1 and the two saliency metrics, one JSON line per workload given")
     ap.add_argument("--decode-sweep", action="store_true",
                     help="instead of the step: time the decode entry point alone at batch 1..64 of the "
                          "workload's layer shape, cold and warm caches, and print that table as one JSON line")
@@ -586,6 +692,9 @@ def main():
         return
     if args.latency_floor:
         latency_floor(args)
+        return
+    if args.error_report:
+        print(json.dumps(error_report(args.workload)))
         return
     if args.decode_sweep:
         decode_sweep(args)

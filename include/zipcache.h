@@ -228,6 +228,17 @@ int zc_decode_attention(const zc_tensor4* q, const zc_packed* Kp, const zc_packe
                         float sm_scale, void* out, float* lse_out,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* ---- groupwise quantization: the baseline granularity of Table 1 / Appendix A (Eq. A) -----
+ * Every `group` (8, 16, 32, 64 or 128; the paper's n = 32) consecutive channels of a token
+ * row w = h*D + c share one (s, z) of Eq. 5 (s := 1 when the group is constant; round half to
+ * even).  x [B, H, L, D]; the n token rows idx[b, 0..n) (device int32, or NULL for rows 0..n-1)
+ * are quantized at `bits` (2, 4 or 8).  A comparator, not a cache format: outputs are
+ * token-major and unpacked, each optional - codes_out device uint8 [B, n, W], scale_out /
+ * zero_out device float [B, n, W / group], dequant_out device float [B, n, W] =
+ * (code - z) * s.  Needs no workspace. */
+int zc_group_quantize(const zc_tensor4* x, const int32_t* idx, int64_t n, int32_t bits, int32_t group,
+                      uint8_t* codes_out, float* scale_out, float* zero_out, float* dequant_out, void* stream);
+
 /* ---- Algorithm 3 with its re-compression branch taken at its word ----------------------
  * ("Extract K[:-100] and V[:-100] and adaptively compress them with A_probe": every 100
  * steps everything but the newest 100 tokens is compressed again as a whole, ranked by the

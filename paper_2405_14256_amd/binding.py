@@ -94,6 +94,8 @@ def load() -> C.CDLL:
     lib.zc_rows_saliency.argtypes = [P, P, I32, I64, I64, I64, I64, I32, P, P]
     lib.zc_dequantize_cache.restype = C.c_int
     lib.zc_dequantize_cache.argtypes = [PK, T4, P]
+    lib.zc_group_quantize.restype = C.c_int
+    lib.zc_group_quantize.argtypes = [T4, P, I64, I32, I32, P, P, P, P, P]
     lib.zc_unpack.restype = C.c_int
     lib.zc_unpack.argtypes = [PK, I32, I32, P, P, P]
     lib.zc_arena_bytes.restype = SZ
@@ -368,3 +370,22 @@ def zc_dequantize_cache(p: PackedTensor, out: torch.Tensor) -> torch.Tensor:
     to = tensor4(out)
     _check("zc_dequantize_cache", lib.zc_dequantize_cache(C.byref(p.c), C.byref(to), _stream()))
     return out
+
+
+def zc_group_quantize(x: torch.Tensor, bits: int, group: int = 32, idx: Optional[torch.Tensor] = None,
+                      codes: bool = True, dequant: bool = True):
+    """Groupwise quantization of the token rows `idx` [B, n] (default: all) of x [B, H, L, D]:
+    (codes uint8 [B, n, W], scale [B, n, W/group], zero, x_hat float32 [B, n, W])."""
+    lib = load()
+    B, H, L, D = x.shape
+    n = int(idx.shape[1]) if idx is not None else L
+    W = H * D
+    dev = x.device
+    co = torch.empty(B, n, W, dtype=torch.uint8, device=dev) if codes else None
+    sc = torch.empty(B, n, W // group, dtype=torch.float32, device=dev)
+    ze = torch.empty(B, n, W // group, dtype=torch.float32, device=dev)
+    dq = torch.empty(B, n, W, dtype=torch.float32, device=dev) if dequant else None
+    tx = tensor4(x)
+    _check("zc_group_quantize", lib.zc_group_quantize(C.byref(tx), _ptr(idx), n, bits, group, _ptr(co), _ptr(sc), _ptr(ze),
+                                                      _ptr(dq), _stream()))
+    return co, sc, ze, dq

@@ -21,7 +21,7 @@
 // Every sweep reads 16 bytes per lane with consecutive lanes on consecutive
 // addresses of a (token, head) row; the second sweep of a tensor that fits the
 // 256 MB Infinity Cache does not reach HBM.
-#include "zc_common.hpp"
+#include "quant_math.hpp"
 
 namespace zc {
 
@@ -118,26 +118,6 @@ __global__ __launch_bounds__(kStatThreads) void k_chan_stats(QPArgs a) {
   o4[1] = make_float4(mn[2], mx[2], mn[3], mx[3]);
   o4[2] = make_float4(mn[4], mx[4], mn[5], mx[5]);
   o4[3] = make_float4(mn[6], mx[6], mn[7], mx[7]);
-}
-
-// N / R from the correctly rounded reciprocal y = 1/R with one residual
-// correction.  When the true quotient is representable (in particular an exact
-// tie n + 1/2, frequent with 16-bit inputs) the result is that quotient, so the
-// round-half-even that follows sees the tie.
-__device__ inline float refined_div(float N, float R, float y) {
-  const float q0 = N * y;
-  const float r = fmaf(-q0, R, N);
-  return fmaf(r, y, q0);
-}
-// x * qmax / R with the rounding error of the product x * qmax carried along, so
-// that ties stay exact for 24-bit x too (e.g. the minimum of a token row whose
-// maximum is its mirror image: exactly -qmax / 2).
-__device__ inline float refined_ratio(float x, float qmax, float R, float y) {
-  const float nh = x * qmax;
-  const float nl = fmaf(x, qmax, -nh);
-  const float q0 = nh * y;
-  const float r = fmaf(-q0, R, nh) + nl;
-  return fmaf(r, y, q0);
 }
 
 // grid (ceil(W / 64), 2 subsets, B), block (64 channels, 4 tile lanes)

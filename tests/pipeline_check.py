@@ -98,6 +98,7 @@ def compare_subset(g: zo.QuantSubset, o: zo.QuantSubset, what: str) -> Dict[str,
         return rep
     assert g.idx is None or np.array_equal(g.idx, o.idx), f"{what}: stored positions differ"
     tokwise = o.scheme != "channel"
+    grouped = o.scheme == "group"
     qmax = float(2 ** o.bits - 1)
 
     def rel(a, b):
@@ -105,13 +106,18 @@ def compare_subset(g: zo.QuantSubset, o: zo.QuantSubset, what: str) -> Dict[str,
     f32 = lambda x: x.astype(np.float32).astype(np.float64)
     rep["chan_scale_rel"] = rel(g.chan_scale, f32(o.chan_scale))
     assert rep["chan_scale_rel"] <= SCALE_RTOL, f"{what}: channel scale off by {rep['chan_scale_rel']:.3e}"
-    if tokwise:
+    if grouped:
+        gsz = o.codes.shape[2] // o.grp_scale.shape[2]
+        rep["tok_scale_rel"] = rel(g.grp_scale, f32(o.grp_scale))
+        assert rep["tok_scale_rel"] <= SCALE_RTOL, f"{what}: group scale off by {rep['tok_scale_rel']:.3e}"
+        zg, zo_ = np.repeat(g.grp_zero, gsz, axis=2), np.repeat(o.grp_zero, gsz, axis=2)
+    elif tokwise:
         rep["tok_scale_rel"] = rel(g.tok_scale, f32(o.tok_scale))
         assert rep["tok_scale_rel"] <= SCALE_RTOL, f"{what}: token scale off by {rep['tok_scale_rel']:.3e}"
         zg, zo_ = g.tok_zero[:, :, None], o.tok_zero[:, :, None]
     else:
         zg, zo_ = g.chan_zero[:, None, :], o.chan_zero[:, None, :]
-    rep["n_groups"] = int(zg.size)
+    rep["n_groups"] = int(o.grp_zero.size) if grouped else int(zg.size)
     rep["n_raw_mismatch"] = int((g.codes != o.codes).sum())
     # Eq. 5 defines x_hat = (code - z) s: a row (or channel) whose zero point came out one
     # step apart on the two sides, with every code shifted along, is the same quantization.
@@ -122,13 +128,17 @@ def compare_subset(g: zo.QuantSubset, o: zo.QuantSubset, what: str) -> Dict[str,
     rep["n_raw_unshifted"] = int(((g.codes != o.codes) & ~zdiff).sum())
     assert np.all(np.abs(zg - zo_) <= 1), f"{what}: zero-point differs by more than one step"
     if np.any(zg != zo_):
-        zpre = -o.pre_round.min(axis=2 if tokwise else 1)            # -min / s of every row / channel
-        zpre = zpre[:, :, None] if tokwise else zpre[:, None, :]
+        if grouped:
+            B_, n_, W_ = o.codes.shape
+            zpre = np.repeat(-o.pre_round.reshape(B_, n_, W_ // gsz, gsz).min(axis=3), gsz, axis=2)
+        else:
+            zpre = -o.pre_round.min(axis=2 if tokwise else 1)        # -min / s of every row / channel
+            zpre = zpre[:, :, None] if tokwise else zpre[:, None, :]
         zfrac = np.abs(zpre - np.floor(zpre) - 0.5)
         assert np.all(zfrac[zg != zo_] < 1e-3), f"{what}: a zero point differs away from its rounding boundary"
     mism = (g.codes - zg) != (o.codes - zo_)
     rep["n_mismatch"] = int(mism.sum())
-    rep["n_zero_mismatch"] = int((zg != zo_).sum())
+    rep["n_zero_mismatch"] = int((g.grp_zero != o.grp_zero).sum()) if grouped else int((zg != zo_).sum())
     if rep["n_mismatch"]:
         d = np.abs((g.codes - zg) - (o.codes - zo_))[mism]
         assert np.all(d == 1), f"{what}: a level differs by more than one step"
