@@ -152,8 +152,7 @@ class HotPath:
             zb.zc_select_salient(self.scores, self.k, self.sal, self.reg)
 
         def quantize():
-            zb.zc_quantize_pack(self.K, self.sal, self.reg, self.Kp)
-            zb.zc_quantize_pack(self.V, self.sal, self.reg, self.Vp)
+            zb.zc_quantize_pack_kv(self.K, self.V, self.sal, self.reg, self.Kp, self.Vp)
 
         out += [("probe", probe, 0, 0.0), ("select", select, 0, 0.0), ("quantize", quantize, 0, 0.0)]
 
@@ -180,8 +179,7 @@ class HotPath:
                                      scores=self.tail_scores[f])
                 zb.zc_select_salient(self.tail_scores[f], self.k_tail, self.sal_t[f], self.reg_t[f])
                 n_packed = self.w.L + base
-                zb.zc_quantize_pack(tk, self.sal_t[f], self.reg_t[f], self.Kp, pos_offset=n_packed)
-                zb.zc_quantize_pack(tv, self.sal_t[f], self.reg_t[f], self.Vp, pos_offset=n_packed)
+                zb.zc_quantize_pack_kv(tk, tv, self.sal_t[f], self.reg_t[f], self.Kp, self.Vp, pos_offset=n_packed)
             return fn
 
         j = 0

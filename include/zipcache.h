@@ -213,6 +213,19 @@ int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
                      const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
                      zc_packed* out, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- the four quantizer calls of Algorithm 2 at once ------------------------------------
+ * Keys and values of one cache compressed by the same launches: exactly what two
+ * zc_quantize_pack calls (xk into outK, then xv into outV, same index lists and offset)
+ * leave behind, bit for bit, in half the launches (three, when outK is CHANNEL / ROW, outV is
+ * CST / TGROUP and a token row has at most 2048 channels; four or five otherwise).  xk and xv
+ * must agree in shape and dtype; outK and outV are two different descriptors.  Workspace:
+ * zc_quantize_pack_kv_workspace(B, H, k + n_reg, D).  Errors as for zc_quantize_pack; when
+ * one is returned neither descriptor has been changed. */
+size_t zc_quantize_pack_kv_workspace(int64_t B, int64_t H, int64_t L, int64_t D);
+int zc_quantize_pack_kv(const zc_tensor4* xk, const zc_tensor4* xv, const int32_t* salient_idx, int64_t k,
+                        const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
+                        zc_packed* outK, zc_packed* outV, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- Eq. 4 over the packed cache (Algorithm 3, attention line) -------------------
  * q [B, Hq, 1, D]; Kp (ROW layout) and Vp (TGROUP layout) hold the same
  * chunks; tail_k / tail_v [B, Hkv, >=tail_len, D] are the full-precision

@@ -82,6 +82,10 @@ def load() -> C.CDLL:
     lib.zc_quantize_pack_workspace.argtypes = [I64, I64, I64, I64]
     lib.zc_quantize_pack.restype = C.c_int
     lib.zc_quantize_pack.argtypes = [T4, P, I64, P, I64, I64, PK, P, SZ, P]
+    lib.zc_quantize_pack_kv_workspace.restype = SZ
+    lib.zc_quantize_pack_kv_workspace.argtypes = [I64, I64, I64, I64]
+    lib.zc_quantize_pack_kv.restype = C.c_int
+    lib.zc_quantize_pack_kv.argtypes = [T4, T4, P, I64, P, I64, I64, PK, PK, P, SZ, P]
     lib.zc_decode_attention_workspace.restype = SZ
     lib.zc_decode_attention_workspace.argtypes = [I64, I64, I64]
     lib.zc_decode_attention.restype = C.c_int
@@ -276,6 +280,22 @@ def zc_quantize_pack(x: torch.Tensor, salient_idx: torch.Tensor, regular_idx: to
            lib.zc_quantize_pack(C.byref(tx), _ptr(salient_idx) if k else None, k,
                                 _ptr(regular_idx) if n_reg else None, n_reg, pos_offset,
                                 C.byref(out.c), ws.data_ptr(), ws.numel(), _stream()))
+
+
+def zc_quantize_pack_kv(xk: torch.Tensor, xv: torch.Tensor, salient_idx: torch.Tensor, regular_idx: torch.Tensor,
+                        outK: PackedTensor, outV: PackedTensor, pos_offset: int = 0) -> None:
+    """Keys and values of one cache in the same launches (the four quantizer calls of Algorithm 2)."""
+    lib = load()
+    B, H, _, D = xk.shape
+    k = int(salient_idx.shape[1]) if salient_idx is not None else 0
+    n_reg = int(regular_idx.shape[1]) if regular_idx is not None else 0
+    need = lib.zc_quantize_pack_kv_workspace(B, H, k + n_reg, D)
+    ws = _workspace(need, xk.device, "quantize_kv")
+    tk, tv = tensor4(xk), tensor4(xv)
+    _check("zc_quantize_pack_kv",
+           lib.zc_quantize_pack_kv(C.byref(tk), C.byref(tv), _ptr(salient_idx) if k else None, k,
+                                   _ptr(regular_idx) if n_reg else None, n_reg, pos_offset,
+                                   C.byref(outK.c), C.byref(outV.c), ws.data_ptr(), ws.numel(), _stream()))
 
 
 def zc_unpack(p: PackedTensor, which: int, chunk: int, codes: bool = True, dequant: bool = True):

@@ -60,17 +60,17 @@ __host__ __device__ inline int stats_tile_tokens(int64_t total_tokens) {
 
 // grid (tiles, B, ceil(NV / 256)): a workgroup reduces 256 channel vectors over a
 // tile of tokens of one subset; a thread owns one vector (8 channels).
+struct QPPair { QPArgs t[2]; };   // keys and values of one cache, compressed by the same launches
+
 template <int DT>
-__global__ __launch_bounds__(kStatThreads) void k_chan_stats(QPArgs a) {
+__device__ inline void chan_stats_body(const QPArgs& a, int tile, int b, int zchunk) {
   constexpr int RAW = (DT == ZC_F32) ? 2 : 1;        // 16-byte loads per channel vector
-  const int b = blockIdx.y;
-  int tile = blockIdx.x;
   const int sub = tile >= a.tiles[0] ? 1 : 0;
   const int gtile = tile;
   if (sub) tile -= a.tiles[0];
   const int t0 = tile * a.TT;
   const int t1 = min(t0 + a.TT, a.n[sub]);
-  const int v = blockIdx.z * kStatThreads + threadIdx.x;
+  const int v = zchunk * kStatThreads + threadIdx.x;
   if (v >= a.NV) return;
   const int32_t* idx = a.idx[sub] + (int64_t)b * a.n[sub];
   const int w = v * 8, h = w / a.D, c = w % a.D;
@@ -120,11 +120,24 @@ __global__ __launch_bounds__(kStatThreads) void k_chan_stats(QPArgs a) {
   o4[3] = make_float4(mn[6], mx[6], mn[7], mx[7]);
 }
 
+template <int DT>
+__global__ __launch_bounds__(kStatThreads) void k_chan_stats(QPArgs a) {
+  chan_stats_body<DT>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+// both tensors of a cache: grid.x = tiles of the first + tiles of the second
+template <int DT>
+__global__ __launch_bounds__(kStatThreads) void k_chan_stats_kv(QPPair p) {
+  const int nt = p.t[0].tiles[0] + p.t[0].tiles[1];
+  const int which = (int)blockIdx.x >= nt ? 1 : 0;
+  const QPArgs& a = which ? p.t[1] : p.t[0];
+  if (a.scheme == ZC_SCHEME_TOKEN) return;           // plain tokenwise: no channel statistics
+  chan_stats_body<DT>(a, blockIdx.x - which * nt, blockIdx.y, blockIdx.z);
+}
+
 // grid (ceil(W / 64), 2 subsets, B), block (64 channels, 4 tile lanes)
-__global__ __launch_bounds__(256) void k_chan_finalize(QPArgs a) {
-  __shared__ float smn[4][64], smx[4][64];
+__device__ inline void chan_finalize_body(const QPArgs& a, int sub, float (*smn)[64], float (*smx)[64]) {
   const int cx = threadIdx.x, ty = threadIdx.y;
-  const int w = blockIdx.x * 64 + cx, sub = blockIdx.y, b = blockIdx.z;
+  const int w = blockIdx.x * 64 + cx, b = blockIdx.z;
   const int n = a.n[sub];
   const float qmax = (float)((1 << a.bits[sub]) - 1);
   float lo = INFINITY, hi = -INFINITY;
@@ -165,6 +178,16 @@ __global__ __launch_bounds__(256) void k_chan_finalize(QPArgs a) {
     a.chunk_row[0] = a.begin[0]; a.chunk_row[1] = a.n[0];
     a.chunk_row[2] = a.begin[1]; a.chunk_row[3] = a.n[1];
   }
+}
+__global__ __launch_bounds__(256) void k_chan_finalize(QPArgs a) {
+  __shared__ float smn[4][64], smx[4][64];
+  chan_finalize_body(a, blockIdx.y, smn, smx);
+}
+// both tensors of a cache: grid.y = 2 subsets of the first, then of the second
+__global__ __launch_bounds__(256) void k_chan_finalize_kv(QPPair p) {
+  __shared__ float smn[4][64], smx[4][64];
+  const int which = blockIdx.y >> 1;
+  chan_finalize_body(which ? p.t[1] : p.t[0], blockIdx.y & 1, smn, smx);
 }
 
 // ---- minima of N values over a wave at once -----------------------------------------
@@ -520,6 +543,34 @@ __global__ __launch_bounds__(MAXT) void k_quant_pack(QPArgs a) {
   else quant_units<DT, 8, LAYOUT, TOKWISE, EXACT, PIPE>(a, sub, g0, ng, b, red, sidx);
 }
 
+// Keys (channelwise, ROW layout) and values (channel-separable tokenwise, TGROUP layout) of one
+// cache in one launch, for token rows of at most 256 channel vectors (one workgroup width serves
+// both): grid.x = workgroups of the keys, then of the values.
+template <int DT>
+__global__ __launch_bounds__(256) void k_quant_pack_kv(QPPair p) {
+  constexpr bool PIPE = (DT != ZC_F32);
+  __shared__ float red[2][16][16];
+  __shared__ int32_t sidx[64];
+  const int b = blockIdx.y;
+  const int nk = p.t[0].wgs[0] + p.t[0].wgs[1];
+  const int which = (int)blockIdx.x >= nk ? 1 : 0;
+  const QPArgs& a = which ? p.t[1] : p.t[0];
+  int wg = blockIdx.x - which * nk;
+  const int sub = wg >= a.wgs[0] ? 1 : 0;
+  if (sub) wg -= a.wgs[0];
+  const int g0 = wg * a.upw, ng = a.upw;
+  const int bits = a.bits[sub];
+  if (which == 0) {
+    if (bits == 4) quant_units<DT, 4, ZC_LAYOUT_ROW, false, false, PIPE>(a, sub, g0, ng, b, red, sidx);
+    else if (bits == 2) quant_units<DT, 2, ZC_LAYOUT_ROW, false, false, PIPE>(a, sub, g0, ng, b, red, sidx);
+    else quant_units<DT, 8, ZC_LAYOUT_ROW, false, false, PIPE>(a, sub, g0, ng, b, red, sidx);
+  } else {
+    if (bits == 4) quant_units<DT, 4, ZC_LAYOUT_TGROUP, true, false, PIPE>(a, sub, g0, ng, b, red, sidx);
+    else if (bits == 2) quant_units<DT, 2, ZC_LAYOUT_TGROUP, true, false, PIPE>(a, sub, g0, ng, b, red, sidx);
+    else quant_units<DT, 8, ZC_LAYOUT_TGROUP, true, false, PIPE>(a, sub, g0, ng, b, red, sidx);
+  }
+}
+
 template <int DT, int LAYOUT, int MAXT>
 static void launch_qp_l(const QPArgs& a, bool tokwise, dim3 grid, dim3 block, hipStream_t st) {
   if (!tokwise) hipLaunchKernelGGL((k_quant_pack<DT, LAYOUT, false, false, MAXT>), grid, block, 0, st, a);
@@ -556,9 +607,9 @@ extern "C" size_t zc_quantize_pack_workspace(int64_t B, int64_t H, int64_t L, in
   return params + partial;
 }
 
-extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
-                                const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
-                                zc_packed* out, void* ws, size_t ws_bytes, void* stream) {
+// Validation and kernel arguments of one tensor's compression call.
+static int qp_prepare(const zc_tensor4* x, const int32_t* salient_idx, int64_t k, const int32_t* regular_idx, int64_t n_reg,
+                      int64_t pos_offset, const zc_packed* out, void* ws, size_t ws_bytes, QPArgs& a) {
   int rc = zc_validate_tensor(x);
   if (rc) return rc;
   rc = zc_validate_packed(out, true);
@@ -576,8 +627,6 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   const size_t need = zc_quantize_pack_workspace(x->B, x->H, k + n_reg, x->D);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
 
-  hipStream_t st = (hipStream_t)stream;
-  QPArgs a;
   a.x = x->ptr; a.sB = x->sB; a.sH = x->sH; a.sL = x->sL;
   a.B = (int)x->B; a.H = (int)x->H; a.D = (int)x->D; a.W = (int)W; a.NV = (int)(W / 8);
   a.idx[0] = salient_idx; a.idx[1] = regular_idx;
@@ -605,20 +654,6 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
   // word groups of 32 / bits tokens; a TGROUP block holds 4 of them
   a.units[0] = (int)ceil_div64(k, 4 * (32 / out->bits_hi)) * 4;
   a.units[1] = (int)ceil_div64(n_reg, 4 * (32 / out->bits_lo)) * 4;
-
-  // ---- sweep 1: channel statistics (partials) -----------------------------------
-  if (out->scheme != ZC_SCHEME_TOKEN && a.tiles[0] + a.tiles[1] > 0) {
-    const int TX = a.NV >= kStatThreads ? kStatThreads : (int)align_up64(a.NV, 64);
-    dim3 grid((unsigned)(a.tiles[0] + a.tiles[1]), (unsigned)x->B, (unsigned)ceil_div64(a.NV, kStatThreads)), block(TX);
-    if (x->dtype == ZC_F32) hipLaunchKernelGGL(k_chan_stats<ZC_F32>, grid, block, 0, st, a);
-    else if (x->dtype == ZC_F16) hipLaunchKernelGGL(k_chan_stats<ZC_F16>, grid, block, 0, st, a);
-    else hipLaunchKernelGGL(k_chan_stats<ZC_BF16>, grid, block, 0, st, a);
-    ZC_LAUNCH_CHECK();
-  }
-  // ---- parameters (also for empty subsets and the tokenwise scheme: defaults) ------
-  hipLaunchKernelGGL(k_chan_finalize, dim3((unsigned)ceil_div64(W, 64), 2, (unsigned)x->B), dim3(64, 4), 0, st, a);
-  ZC_LAUNCH_CHECK();
-  // ---- sweep 2: quantize + pack ---------------------------------------------------
   // word groups per workgroup: one while the launch is small (latency), up to a whole
   // block of consecutive slots when there is enough work to fill the chip anyway
   {
@@ -629,22 +664,108 @@ extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx,
     a.wgs[0] = a.units[0] / upw;
     a.wgs[1] = a.units[1] / upw;
   }
-  if (a.units[0] + a.units[1] > 0) {
-    const bool tokwise = out->scheme != ZC_SCHEME_CHANNEL;
-    int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
-    int zchunks = 1;
-    if (!tokwise && TXq > 256) { zchunks = (int)ceil_div64(a.NV, 256); TXq = 256; }
-    dim3 grid((unsigned)(a.wgs[0] + a.wgs[1]), (unsigned)x->B, (unsigned)zchunks), block(TXq);
-    if (x->dtype == ZC_F32) launch_qp<ZC_F32>(a, out->layout, tokwise, grid, block, st);
-    else if (x->dtype == ZC_F16) launch_qp<ZC_F16>(a, out->layout, tokwise, grid, block, st);
-    else launch_qp<ZC_BF16>(a, out->layout, tokwise, grid, block, st);
-    ZC_LAUNCH_CHECK();
-  }
+  return ZC_OK;
+}
 
+// Host bookkeeping of an appended chunk.
+static void qp_commit(zc_packed* out, int64_t k, int64_t n_reg) {
   int32_t* row = out->chunk_table_host + 4 * out->n_chunks;
   row[0] = (int32_t)out->n_hi; row[1] = (int32_t)k; row[2] = (int32_t)out->n_lo; row[3] = (int32_t)n_reg;
-  out->n_hi = end_hi;
-  out->n_lo = end_lo;
+  out->n_hi = align_up64(out->n_hi + k, ZC_SLOT_ALIGN);
+  out->n_lo = align_up64(out->n_lo + n_reg, ZC_SLOT_ALIGN);
   out->n_chunks += 1;
+}
+
+static int qp_launch_pack(const QPArgs& a, int dtype, int layout, hipStream_t st) {
+  if (a.units[0] + a.units[1] == 0) return ZC_OK;
+  const bool tokwise = a.scheme != ZC_SCHEME_CHANNEL;
+  int TXq = (int)align_up64(ceil_div64(a.NV, kVPT), 64);
+  int zchunks = 1;
+  if (!tokwise && TXq > 256) { zchunks = (int)ceil_div64(a.NV, 256); TXq = 256; }
+  dim3 grid((unsigned)(a.wgs[0] + a.wgs[1]), (unsigned)a.B, (unsigned)zchunks), block(TXq);
+  if (dtype == ZC_F32) launch_qp<ZC_F32>(a, layout, tokwise, grid, block, st);
+  else if (dtype == ZC_F16) launch_qp<ZC_F16>(a, layout, tokwise, grid, block, st);
+  else launch_qp<ZC_BF16>(a, layout, tokwise, grid, block, st);
+  ZC_LAUNCH_CHECK();
+  return ZC_OK;
+}
+
+extern "C" int zc_quantize_pack(const zc_tensor4* x, const int32_t* salient_idx, int64_t k,
+                                const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
+                                zc_packed* out, void* ws, size_t ws_bytes, void* stream) {
+  QPArgs a;
+  int rc = qp_prepare(x, salient_idx, k, regular_idx, n_reg, pos_offset, out, ws, ws_bytes, a);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  // ---- sweep 1: channel statistics (partials) -----------------------------------
+  if (out->scheme != ZC_SCHEME_TOKEN && a.tiles[0] + a.tiles[1] > 0) {
+    const int TX = a.NV >= kStatThreads ? kStatThreads : (int)align_up64(a.NV, 64);
+    dim3 grid((unsigned)(a.tiles[0] + a.tiles[1]), (unsigned)x->B, (unsigned)ceil_div64(a.NV, kStatThreads)), block(TX);
+    if (x->dtype == ZC_F32) hipLaunchKernelGGL(k_chan_stats<ZC_F32>, grid, block, 0, st, a);
+    else if (x->dtype == ZC_F16) hipLaunchKernelGGL(k_chan_stats<ZC_F16>, grid, block, 0, st, a);
+    else hipLaunchKernelGGL(k_chan_stats<ZC_BF16>, grid, block, 0, st, a);
+    ZC_LAUNCH_CHECK();
+  }
+  // ---- parameters (also for empty subsets and the tokenwise scheme: defaults) ------
+  hipLaunchKernelGGL(k_chan_finalize, dim3((unsigned)ceil_div64(a.W, 64), 2, (unsigned)x->B), dim3(64, 4), 0, st, a);
+  ZC_LAUNCH_CHECK();
+  // ---- sweep 2: quantize + pack ---------------------------------------------------
+  rc = qp_launch_pack(a, x->dtype, out->layout, st);
+  if (rc) return rc;
+  qp_commit(out, k, n_reg);
+  return ZC_OK;
+}
+
+extern "C" size_t zc_quantize_pack_kv_workspace(int64_t B, int64_t H, int64_t L, int64_t D) {
+  return 2 * (size_t)align_up64((int64_t)zc_quantize_pack_workspace(B, H, L, D), 256);
+}
+
+extern "C" int zc_quantize_pack_kv(const zc_tensor4* xk, const zc_tensor4* xv, const int32_t* salient_idx, int64_t k,
+                                   const int32_t* regular_idx, int64_t n_reg, int64_t pos_offset,
+                                   zc_packed* outK, zc_packed* outV, void* ws, size_t ws_bytes, void* stream) {
+  if (!xk || !xv || !outK || !outV || outK == outV) return ZC_ERR_INVALID_ARG;
+  if (xk->dtype != xv->dtype || xk->B != xv->B || xk->H != xv->H || xk->D != xv->D || xk->L != xv->L) return ZC_ERR_INVALID_ARG;
+  const size_t half = (size_t)align_up64((int64_t)zc_quantize_pack_workspace(xk->B, xk->H, k + n_reg, xk->D), 256);
+  if (!ws || ws_bytes < 2 * half || (reinterpret_cast<uintptr_t>(ws) & 15)) return ZC_ERR_WORKSPACE;
+  QPPair p;
+  int rc = qp_prepare(xk, salient_idx, k, regular_idx, n_reg, pos_offset, outK, ws, half, p.t[0]);
+  if (rc) return rc;
+  rc = qp_prepare(xv, salient_idx, k, regular_idx, n_reg, pos_offset, outV, reinterpret_cast<uint8_t*>(ws) + half, half, p.t[1]);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const QPArgs& a = p.t[0];
+  const int dt = xk->dtype;
+  const int nt = a.tiles[0] + a.tiles[1];
+  // ---- sweep 1 of both tensors --------------------------------------------------------
+  if (nt > 0 && (outK->scheme != ZC_SCHEME_TOKEN || outV->scheme != ZC_SCHEME_TOKEN)) {
+    const int TX = a.NV >= kStatThreads ? kStatThreads : (int)align_up64(a.NV, 64);
+    dim3 grid((unsigned)(2 * nt), (unsigned)a.B, (unsigned)ceil_div64(a.NV, kStatThreads)), block(TX);
+    if (dt == ZC_F32) hipLaunchKernelGGL(k_chan_stats_kv<ZC_F32>, grid, block, 0, st, p);
+    else if (dt == ZC_F16) hipLaunchKernelGGL(k_chan_stats_kv<ZC_F16>, grid, block, 0, st, p);
+    else hipLaunchKernelGGL(k_chan_stats_kv<ZC_BF16>, grid, block, 0, st, p);
+    ZC_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_chan_finalize_kv, dim3((unsigned)ceil_div64(a.W, 64), 4, (unsigned)a.B), dim3(64, 4), 0, st, p);
+  ZC_LAUNCH_CHECK();
+  // ---- sweep 2: one launch for both tensors in the paper's configuration (channelwise keys in
+  //      ROW layout, channel-separable tokenwise values in TGROUP layout) when a token row fits
+  //      one workgroup of 256 threads; else a launch per tensor ------------------------------
+  const bool paper_cfg = outK->scheme == ZC_SCHEME_CHANNEL && outK->layout == ZC_LAYOUT_ROW &&
+                         outV->scheme == ZC_SCHEME_CST && outV->layout == ZC_LAYOUT_TGROUP;
+  const int nwg = a.wgs[0] + a.wgs[1] + p.t[1].wgs[0] + p.t[1].wgs[1];
+  if (paper_cfg && a.NV <= 256 && nwg > 0) {
+    dim3 grid((unsigned)nwg, (unsigned)a.B), block((unsigned)align_up64(a.NV, 64));
+    if (dt == ZC_F32) hipLaunchKernelGGL(k_quant_pack_kv<ZC_F32>, grid, block, 0, st, p);
+    else if (dt == ZC_F16) hipLaunchKernelGGL(k_quant_pack_kv<ZC_F16>, grid, block, 0, st, p);
+    else hipLaunchKernelGGL(k_quant_pack_kv<ZC_BF16>, grid, block, 0, st, p);
+    ZC_LAUNCH_CHECK();
+  } else {
+    rc = qp_launch_pack(p.t[0], dt, outK->layout, st);
+    if (rc) return rc;
+    rc = qp_launch_pack(p.t[1], dt, outV->layout, st);
+    if (rc) return rc;
+  }
+  qp_commit(outK, k, n_reg);
+  qp_commit(outV, k, n_reg);
   return ZC_OK;
 }

@@ -315,6 +315,42 @@ def test_quantize_randomized_shapes():
     assert mism <= 1e-4 * total, (mism, total)
 
 
+def test_quantize_pack_kv_equals_two_calls():
+    """zc_quantize_pack_kv leaves exactly what two zc_quantize_pack calls leave: every array of
+    both packed tensors, bit for bit - the merged launches of the paper's configuration and the
+    per-tensor fallbacks (other schemes / layouts, rows wider than one workgroup), two chunks."""
+    rng = np.random.default_rng(5150)
+    cases = [("channel", zb.ZC_LAYOUT_ROW, "cst", zb.ZC_LAYOUT_TGROUP, 8, 128, torch.bfloat16),      # merged
+             ("channel", zb.ZC_LAYOUT_ROW, "cst", zb.ZC_LAYOUT_TGROUP, 3, 64, torch.float32),        # merged, ragged wave
+             ("channel", zb.ZC_LAYOUT_ROW, "cst", zb.ZC_LAYOUT_TGROUP, 40, 128, torch.float16),      # wide rows: per-tensor packs
+             ("cst", zb.ZC_LAYOUT_ROW, "cst", zb.ZC_LAYOUT_TGROUP, 4, 128, torch.bfloat16),
+             ("token", zb.ZC_LAYOUT_ROW, "token", zb.ZC_LAYOUT_TGROUP, 2, 64, torch.float16),
+             ("channel", zb.ZC_LAYOUT_ROW, "channel", zb.ZC_LAYOUT_TGROUP, 5, 64, torch.float32)]
+    for ks, kl, vs, vl, H, D, dtype in cases:
+        B = 2
+        g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+        sizes = [int(rng.integers(1, 400)), int(rng.integers(1, 120))]
+        caps = zb.load().zc_arena_slots(sum(sizes), 2)
+        packs = [[zb.PackedTensor(B, H, D, caps, caps, 4, 2, s_, l_, max_chunks=2, device=DEV) for s_, l_ in ((ks, kl), (vs, vl))]
+                 for _ in range(2)]
+        n0 = 0
+        for n in sizes:
+            K = torch.randn(B, H, n, D, generator=g).to(dtype).to(DEV)
+            V = torch.randn(B, H, n, D, generator=g).to(dtype).to(DEV)
+            kk = int(rng.integers(0, n + 1))
+            sal, reg = zb.zc_select_salient(torch.rand(B, n, generator=g).to(DEV), kk)
+            zb.zc_quantize_pack(K, sal, reg, packs[0][0], pos_offset=n0)
+            zb.zc_quantize_pack(V, sal, reg, packs[0][1], pos_offset=n0)
+            zb.zc_quantize_pack_kv(K, V, sal, reg, packs[1][0], packs[1][1], pos_offset=n0)
+            n0 += n
+        torch.cuda.synchronize()
+        for a, b in zip(packs[0], packs[1]):
+            assert a.chunks == b.chunks and (a.c.n_hi, a.c.n_lo, a.c.n_chunks) == (b.c.n_hi, b.c.n_lo, b.c.n_chunks)
+            for name in ("codes_hi", "codes_lo", "tok_scale_hi", "tok_zero_hi", "tok_scale_lo", "tok_zero_lo", "pos_hi", "pos_lo",
+                         "chan_scale", "chan_zero", "chunk_table"):
+                assert torch.equal(getattr(a, name), getattr(b, name)), (ks, vs, H, D, dtype, name)
+
+
 def test_plain_tokenwise_codes_are_tie_exact():
     """Without channel normalization (scheme "token", c = 1) 16-bit inputs sit on a grid where
     x / s lands on n + 1/2 exactly about once in 10^4 elements: the codes must still be the
