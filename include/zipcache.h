@@ -33,6 +33,13 @@
  *     elements.
  *   - Supported: head dimension D in {64, 128}; dtypes f32, f16, bf16;
  *     code widths in {2, 4, 8}; Hq a multiple of Hkv with Hq/Hkv <= 8.
+ *   - Value ranges (not checked: the data lives on the device).  All inputs must be
+ *     finite - no NaN, no infinity (the quantizer takes minima and maxima without
+ *     regard to NaN).  zc_decode_attention feeds the matrix cores fp16 operands:
+ *     every |q[c] * chan_scale[c] * sm_scale| of the keys' channel scales must stay
+ *     below 700 and every token scale of the values below 1000 (an fp16 overflow
+ *     there turns the output into NaN); activations of the models the paper
+ *     compresses are orders of magnitude inside these bounds.
  *   - Size limits (beyond them a call returns ZC_ERR_UNSUPPORTED and launches
  *     nothing): B <= 65535 and heads <= 65535; a token row of a cache tensor at
  *     most 8192 channels (W = H*D) in zc_quantize_pack; the kernels address one
