@@ -33,6 +33,15 @@
  *     elements.
  *   - Supported: head dimension D in {64, 128}; dtypes f32, f16, bf16;
  *     code widths in {2, 4, 8}; Hq a multiple of Hkv with Hq/Hkv <= 8.
+ *   - HIP graph capture.  Every call may be captured (nothing synchronises or
+ *     allocates).  The state of a zc_packed on the host - slots in use, number of
+ *     chunks, the mirror of the chunk table - is read when a call is *issued* and
+ *     travels in the kernel arguments: a captured zc_decode_attention replays over the
+ *     chunks the cache had at capture time, a captured zc_quantize_pack appends at the
+ *     slots it was captured for.  A graph therefore has to be captured in the order its
+ *     calls will run and replayed as a whole sequence from the same starting state
+ *     (after the host fields have been reset to what they were when capture began);
+ *     the library cannot check this.
  *   - Value ranges (not checked: the data lives on the device).  All inputs must be
  *     finite - no NaN, no infinity (the quantizer takes minima and maxima without
  *     regard to NaN).  zc_decode_attention feeds the matrix cores fp16 operands:
