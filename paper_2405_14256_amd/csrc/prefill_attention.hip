@@ -17,6 +17,8 @@
 // written to LDS in the order the logit accumulators imply.
 // K tiles go global -> LDS directly; V tiles pass through registers, where four
 // consecutive keys of eight (four) channels are transposed before they are stored.
+#include <type_traits>
+
 #include "mfma_tiles.hpp"
 
 namespace zc {
@@ -185,14 +187,15 @@ __global__ __launch_bounds__(256, (DT == ZC_F32) ? 1 : 2) void k_prefill_attenti
     for (int i = 0; i < 16; ++i) oacc[ct][i] = 0.f;
   float m = -INFINITY, l = 0.f;       // running maximum (log2 units) and this half-wave's share of the sum
 
-  for (int t = 0; t < ntiles; ++t) {
+  auto tile = [&](auto masked_c, int t) {
+    constexpr bool MASKED = decltype(masked_c)::value;
     const int cur = t & 1;
     wait_all_loads();                 // K tile t (this wave's transfers) and V tile t (registers) have landed
     v_store(cur, vr);
     __syncthreads();                  // tile t is complete in LDS; nobody still reads the other buffers
     if (t + 1 < ntiles) { k_issue(t + 1, cur ^ 1); v_issue(t + 1, vr); }
     const int key0 = t * kPfKeys;
-    if (key0 > wq0 + 31) continue;    // none of this tile's keys is visible to the wave's rows
+    if (key0 > wq0 + 31) return;      // none of this tile's keys is visible to the wave's rows
 
     // ---- logits of 64 keys x 32 rows ----
     v16f sacc[2];
@@ -207,20 +210,22 @@ __global__ __launch_bounds__(256, (DT == ZC_F32) ? 1 : 2) void k_prefill_attenti
       }
     }
     // ---- online softmax: a lane owns one row and 32 of the tile's keys ----
-    float s[2][16];
-    const bool need_mask = key0 + kPfKeys - 1 > wq0;
+    // (the maximum is taken over the raw products - the scale is positive - and the scale
+    // enters with the subtraction of the reference: one fused multiply-add per logit)
     float tmax = -INFINITY;
+    if constexpr (MASKED) {
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (key0 + 32 * jt + acc_row(v, kh) > qpos) sacc[jt][v] = -INFINITY;
+    }
 #pragma unroll
     for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x = sacc[jt][v] * a.scale_log2;
-        if (need_mask && key0 + 32 * jt + acc_row(v, kh) > qpos) x = -INFINITY;
-        s[jt][v] = x;
-        tmax = fmaxf(tmax, x);
-      }
+      for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[jt][v]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m, tmax);
+    const float m_new = fmaxf(m, tmax * a.scale_log2);
     if (__builtin_amdgcn_ballot_w64(m_new > m)) {
       const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - m_new);
       l *= alpha;
@@ -230,12 +235,13 @@ __global__ __launch_bounds__(256, (DT == ZC_F32) ? 1 : 2) void k_prefill_attenti
         for (int i = 0; i < 16; ++i) oacc[ct][i] *= alpha;
       m = m_new;
     }
+    float s[2][16];
     float psum = 0.f;
 #pragma unroll
     for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        s[jt][v] = __builtin_amdgcn_exp2f(s[jt][v] - m);      // (m is finite: key 0 is visible to every row)
+        s[jt][v] = __builtin_amdgcn_exp2f(fmaf(sacc[jt][v], a.scale_log2, -m));   // (m is finite: key 0 is visible to every row)
         psum += s[jt][v];
       }
     l += psum;
@@ -259,7 +265,13 @@ __global__ __launch_bounds__(256, (DT == ZC_F32) ? 1 : 2) void k_prefill_attenti
           mma_chunk<DT>(oacc[ct], vf, pb);
         }
       }
-  }
+  };
+  // Tiles all of whose keys every row of this wave sees need no mask: they run a copy of the
+  // tile code without the position compares (the waves of a workgroup reach their diagonal at
+  // different tiles, but every wave passes one barrier per tile either way).
+  const int t_full = min(ntiles, (wq0 + 1) / kPfKeys);
+  for (int t = 0; t < t_full; ++t) tile(std::false_type{}, t);
+  for (int t = t_full; t < ntiles; ++t) tile(std::true_type{}, t);
 
   // ---- normalise and store: lane = row, accumulator v of tile ct = channel 32 ct + acc_row(v, kh) ----
   const float l_tot = l + __shfl_xor(l, 32);
