@@ -243,6 +243,44 @@ def test_select_edges(L, k):
         assert np.array_equal(sal[b].cpu().numpy(), s_o) and np.array_equal(reg[b].cpu().numpy(), r_o)
 
 
+def test_select_value_distributions_and_row_alignments():
+    """The cached select kernel starts its radix passes at the first bit in which two keys of the
+    row differ, loads rows with 16-byte words when they are aligned and writes the mask a word
+    at a time when it can: rows of mixed sign (no common bit), of one value (no undecided bit),
+    of two adjacent floats (one undecided bit), of one octave, of many octaves, with ties across
+    the k-th place; row lengths around the piece sizes (4, 256, a wave's run) and the largest
+    cached row, with B > 1 so that odd lengths leave rows and mask rows misaligned."""
+    rng = np.random.default_rng(77)
+    def rows(kind, B, L):
+        if kind == "mixed":
+            x = rng.standard_normal((B, L)).astype(np.float32)
+        elif kind == "const":
+            x = np.full((B, L), 0.375, np.float32)
+        elif kind == "adjacent":
+            x = np.where(rng.random((B, L)) < 0.5, np.float32(1.0), np.nextafter(np.float32(1.0), np.float32(2.0))).astype(np.float32)
+        elif kind == "octave":
+            x = (1.0 + rng.random((B, L))).astype(np.float32) / np.float32(L)
+        elif kind == "wide":
+            x = np.exp(rng.uniform(-30, 3, (B, L))).astype(np.float32)
+        else:                                       # ties: few distinct values
+            x = rng.integers(0, 5, (B, L)).astype(np.float32) * np.float32(0.25)
+        return x
+    cases = [(1, 1), (3, 2), (3, 5), (2, 255), (2, 256), (3, 257), (2, 4095), (1, 4096), (2, 4100), (3, 12289),
+             (1, 34816), (2, 34815), (1, 34817)]
+    for B, L in cases:
+        for kind in ("mixed", "const", "adjacent", "octave", "wide", "ties"):
+            x = rows(kind, B, L)
+            for k in sorted({0, 1, L // 3, L - 1, L} & set(range(L + 1))):
+                mask = torch.full((B, L), 7, dtype=torch.uint8, device=DEV)
+                sal, reg = zb.zc_select_salient(torch.from_numpy(x).to(DEV), k, mask=mask)
+                sal, reg, mk = sal.cpu().numpy(), reg.cpu().numpy(), mask.cpu().numpy()
+                for b in range(B):
+                    s_o, r_o = zo.select_salient(x[b].astype(np.float64), k)
+                    assert np.array_equal(sal[b], s_o) and np.array_equal(reg[b], r_o), (kind, B, L, k, b)
+                    m_o = np.zeros(L, np.uint8); m_o[s_o] = 1
+                    assert np.array_equal(mk[b], m_o), (kind, B, L, k, b)
+
+
 def test_select_negative_and_mask():
     sc = torch.tensor([[-1.0, -0.0, 0.0, 3.0, -7.5, 3.0, 1e-30, -1e-30]])
     mask = torch.zeros(1, 8, dtype=torch.uint8, device=DEV)
