@@ -262,13 +262,16 @@ def test_select_value_distributions_and_row_alignments():
             x = (1.0 + rng.random((B, L))).astype(np.float32) / np.float32(L)
         elif kind == "wide":
             x = np.exp(rng.uniform(-30, 3, (B, L))).astype(np.float32)
+        elif kind == "special":                     # infinities of both signs (-inf has the lowest key of all) and subnormals
+            x = rng.random((B, L), dtype=np.float32)
+            x[:, ::7] = np.inf; x[:, 1::11] = -np.inf; x[:, 2::13] = 1e-42
         else:                                       # ties: few distinct values
             x = rng.integers(0, 5, (B, L)).astype(np.float32) * np.float32(0.25)
         return x
     cases = [(1, 1), (3, 2), (3, 5), (2, 255), (2, 256), (3, 257), (2, 4095), (1, 4096), (2, 4100), (3, 12289),
              (1, 34816), (2, 34815), (1, 34817)]
     for B, L in cases:
-        for kind in ("mixed", "const", "adjacent", "octave", "wide", "ties"):
+        for kind in ("mixed", "const", "adjacent", "octave", "wide", "ties", "special"):
             x = rows(kind, B, L)
             for k in sorted({0, 1, L // 3, L - 1, L} & set(range(L + 1))):
                 mask = torch.full((B, L), 7, dtype=torch.uint8, device=DEV)
