@@ -969,31 +969,38 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   write_result();
 }
 
-// Reduces the partial (m, Z, o) of the workgroups of one query head.
+// Reduces the partial (m, Z, o) of the workgroups of one query head.  The call's latency is
+// this kernel's too, so nothing here branches: lane ss of every wave fetches (m, Z) of split
+// ss with one load each (lanes past the last split repeat the last one and count as empty),
+// the 32 possible output partials of this thread's channel are requested back to back (splits
+// past the last one repeat it, with weight 0), and the weights 2^(m - M) come from one
+// exponential over the lanes, handed round as scalars.  (With a branch per split - which
+// loads exist depends on S - the loads took 1.6 us to issue and land, against 0.8 us here.)
 template <int DT, int D>
 __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ part_m, const float* __restrict__ part_z,
                                                       const float* __restrict__ part_o, int S,
                                                       void* __restrict__ out, float* __restrict__ lse_out) {
+  static_assert(kCombineMax <= 64, "one lane per split");
   const int64_t hq = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
-  const int c = threadIdx.x;
-  // all partials are requested before any is used
-  float pm[kCombineMax], pz[kCombineMax], po[kCombineMax];
+  const int c = threadIdx.x, lane = c & 63;
+  const int last = S - 1;
+  const int64_t row = hq * S;
+  float pmv = part_m[row + min(lane, last)], pzv = part_z[row + min(lane, last)];
+  float po[kCombineMax];
 #pragma unroll
-  for (int ss = 0; ss < kCombineMax; ++ss) {
-    const bool in = ss < S;
-    pm[ss] = in ? part_m[hq * S + ss] : -INFINITY;
-    pz[ss] = in ? part_z[hq * S + ss] : 0.f;
-    po[ss] = in ? part_o[(hq * S + ss) * D + c] : 0.f;
-  }
-  float M = -INFINITY;
+  for (int ss = 0; ss < kCombineMax; ++ss) po[ss] = part_o[(row + min(ss, last)) * D + c];
+  if (lane > last) { pmv = -INFINITY; pzv = 0.f; }
+  float M = pmv;
 #pragma unroll
-  for (int ss = 0; ss < kCombineMax; ++ss) M = fmaxf(M, pm[ss]);
+  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  const float fv = (pmv > -INFINITY) ? fast_exp2(pmv - M) : 0.f;
   float o = 0.f, z = 0.f;
 #pragma unroll
   for (int ss = 0; ss < kCombineMax; ++ss) {
-    const float f = (pm[ss] > -INFINITY) ? fast_exp2(pm[ss] - M) : 0.f;
+    const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fv), ss));
+    const float pz = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pzv), ss));
     o = fmaf(po[ss], f, o);
-    z = fmaf(pz[ss], f, z);
+    z = fmaf(pz, f, z);
   }
   store1<DT>(out, hq * D + c, z > 0.f ? o / z : 0.f);
   if (lse_out && c == 0) lse_out[hq] = (M + log2f(z)) * kLn2;
