@@ -152,13 +152,30 @@ __device__ inline float half_hi_to_float(uint32_t w) {
 __device__ inline float xor1(float x) {   // value of the neighbouring lane (lane ^ 1)
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));
 }
-__device__ inline float grp_max(float x) {  // over the four 16-lane groups
-  x = fmaxf(x, __shfl_xor(x, 16));
-  return fmaxf(x, __shfl_xor(x, 32));
+// Reductions over the four 16-lane rows of a wave with the register-pair swaps of this part
+// (vector instructions; a shuffle through the LDS crossbar costs a wave that runs alone on its
+// SIMD a round trip each).  v_permlane16_swap exchanges the odd rows of its first operand with
+// the even rows of its second, v_permlane32_swap the upper half of the first with the lower
+// half of the second.
+//   rows16(a, b): rows 0, 2 hold a summed over the row pair, rows 1, 3 hold b;
+//   halves32(a, b): lanes 0-31 hold a summed over the two halves, lanes 32-63 hold b.
+__device__ inline float rows16(float a, float b) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
-__device__ inline float grp_sum(float x) {
-  x += __shfl_xor(x, 16);
-  return x + __shfl_xor(x, 32);
+__device__ inline float halves32(float a, float b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ inline float grp_max(float x) {  // over the four 16-lane groups, in every lane
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float grp_sum(float x) {  // (row r + row r^1) + (the other pair), as the shuffles gave it
+  x = rows16(x, x);
+  return halves32(x, x);
 }
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -189,7 +206,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   constexpr int KS = D / 32;     // k-steps of the logit product
   constexpr int NR = D / 64;     // 16-byte V loads per lane and block
   constexpr int MG = ZC_MAX_GROUP;
-  __shared__ __align__(16) float svc[4][2][D];   // per wave: channel scale and zero of V for its current segment
+  __shared__ __align__(16) float svc[4][256];    // per wave: channel scales [0, D) and zeros [D, 2 D) of V for its current segment (one 1 KB transfer)
   // Per wave a ring of kStages staging buffers for one block of the packed cache
   // each: K codes (D * 16 bytes), V codes (D * 16 bytes), then 256 bytes each of
   // V token scale, V token zero, K token scale, K token zero.  After its last block a
@@ -305,13 +322,14 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // Returns the operand registers and sum(q'), sum(q' cz) over all channels, and the same
   // two sums over the 32 channels of every k-step (what the normalized encoding needs to
   // keep its accumulators centred, see the segment).
-  auto build_query_operand = [&](auto mode_c, const float* kcs, const float* kcz, const float* vcs, const float* vcz,
+  // qsrc + qoff (elements): the query row of this lane's head; kcs, kcz: the K channel
+  // parameters of the segment.  The tail reads q from global memory; a packed segment has
+  // had the rows and the parameters brought to LDS (see the segment).
+  auto build_query_operand = [&](auto mode_c, const void* qsrc, int64_t qoff, const float* kcs, const float* kcz,
                                  u4 (&qB)[KS], float& sumqq, float& sumqqcz, float (&sum_k)[KS], float (&sumcz_k)[KS]) {
     constexpr int MODE = decltype(mode_c)::value;
-    // q and the channel parameters of this lane's elements of every k-step, straight
-    // from global memory (issued together with the first blocks' loads by the caller)
+    // q and the channel parameters of this lane's elements of every k-step
     float q8[KS][8], cs8[KS][8], cz8[KS][8];
-    const int64_t qoff = (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH;
 #pragma unroll
     for (int ks0 = 0; ks0 < KS; ++ks0) {
 #pragma unroll
@@ -320,8 +338,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         // slots (i, half) are channels base + 4 (ks0 & 1) + i + 8 half of a 16-channel word
         const int base = grp * (D / 4) + 16 * (ks0 >> 1) + 4 * (ks0 & 1);
         float qa[8], qb[8];
-        load8<DT>(a.q, qoff + base - 4 * (ks0 & 1), qa);
-        load8<DT>(a.q, qoff + base - 4 * (ks0 & 1) + 8, qb);
+        load8<DT>(qsrc, qoff + base - 4 * (ks0 & 1), qa);
+        load8<DT>(qsrc, qoff + base - 4 * (ks0 & 1) + 8, qb);
         const float4 ca = *reinterpret_cast<const float4*>(kcs + base);
         const float4 cb = *reinterpret_cast<const float4*>(kcs + base + 8);
         const float4 za = *reinterpret_cast<const float4*>(kcz + base);
@@ -338,7 +356,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         // MODE 4: slots (i, half) are channels base + i + 4 half; MODE 0: base + 2 i + half
         const int base = (MODE == 4) ? grp * (D / 4) + 8 * ks0 : 32 * ks0 + 8 * grp;
         float qa[8];
-        load8<DT>(a.q, qoff + base, qa);
+        load8<DT>(qsrc, qoff + base, qa);
         float ca[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f}, za[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if constexpr (MODE == 4) {
           const float4 c0 = *reinterpret_cast<const float4*>(kcs + base), c1 = *reinterpret_cast<const float4*>(kcs + base + 4);
@@ -353,15 +371,6 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
             const int e = (MODE == 4) ? i + 4 * half : 2 * i + half;
             q8[ks0][2 * i + half] = qa[e]; cs8[ks0][2 * i + half] = ca[e]; cz8[ks0][2 * i + half] = za[e];
           }
-      }
-    }
-    // the V channel parameters wait in this wave's part of LDS until the segment is folded
-    if constexpr (MODE != 0) {
-      if (lane < D / 2) {
-        const bool zero_half = lane >= D / 4;
-        const int c4 = 4 * (zero_half ? lane - D / 4 : lane);
-        const float4 t = *reinterpret_cast<const float4*>((zero_half ? vcz : vcs) + c4);
-        *reinterpret_cast<float4*>(&svc[wave][zero_half ? 1 : 0][c4]) = t;
       }
     }
     // Value and residual columns: the residual of the query operand is NOT scaled, so its
@@ -502,7 +511,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     u4 qB[KS];
     float dummy0, dummy1;
     float dummy_k[KS], dummy_kz[KS];
-    build_query_operand(std::integral_constant<int, 0>{}, nullptr, nullptr, nullptr, nullptr, qB, dummy0, dummy1, dummy_k, dummy_kz);
+    build_query_operand(std::integral_constant<int, 0>{}, a.q, (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH,
+                        nullptr, nullptr, qB, dummy0, dummy1, dummy_k, dummy_kz);
     float Ot[MG][8];
 #pragma unroll
     for (int gg = 0; gg < MG; ++gg)
@@ -608,18 +618,24 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         tail_unit(tu, bf0);
       }
     }
-    // merge: sum the token sub-rows, then the four waves through LDS
+    // merge: sum the token sub-rows, then the four waves through LDS.  Four values at a
+    // time are summed over the four rows with three swaps and three additions, after which
+    // row r holds the sum of value r - and writes it.
     const float z_tot = grp_sum(z_part);
     if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
 #pragma unroll
     for (int gg = 0; gg < MG; ++gg) {
       if (gg < G) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          float x = Ot[gg][e];
+        for (int h = 0; h < 2; ++h) {
+          float x[4];
 #pragma unroll
-          for (int o = LPT; o < 64; o <<= 1) x += __shfl_xor(x, o);
-          if (lane < LPT) mO(wave, gg, vch + e) = x;
+          for (int e = 0; e < 4; ++e) {
+            x[e] = Ot[gg][4 * h + e];
+            if constexpr (LPT == 8) x[e] += __shfl_xor(x[e], 8);      // (D = 64: two tokens per row)
+          }
+          const float sum = halves32(rows16(x[0], x[1]), rows16(x[2], x[3]));
+          if ((lane & 15) < LPT) mO(wave, gg, vch + 4 * h + grp) = sum;
         }
       }
     }
@@ -693,13 +709,40 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         dma4(dst + 2 * kCodeBytes + 768, rs_ktz, v4, to);
       }
     };
+    // What the query operand is built from goes to LDS by three or four transfers of its own
+    // (with a load per lane and k-step - some thirty of them, each with its address arithmetic
+    // - a wave needed 0.8 us just to issue them): the K channel scales and zeros (1 KB: lanes
+    // pick their 16-byte piece of either array) and the query rows of the KV head's G heads go
+    // to the ring's last stage, which is free until the block loop's first request; the V
+    // channel scales and zeros go to svc, where they wait until the segment is folded.
+    constexpr int ESZ = (DT == ZC_F32) ? 4 : 2;
+    constexpr int PA = D / 4;                           // 16-byte pieces of a parameter row
+    constexpr int PR = D * ESZ / 16, RP = 64 / PR;      // 16-byte pieces of a query row; rows per transfer
+    constexpr int NQ = (MG + RP - 1) / RP;
+    static_assert(1024 + NQ * 1024 <= kStageBytes, "the parameters fit a stage of the ring");
+    const uint32_t par_lds = ring_lds + (kStages - 1) * kStageBytes;
+    const uint8_t* par = ring_gen + (kStages - 1) * kStageBytes;
+    {
+      const int piece = lane % PA;
+      const bool zeros = (lane / PA) & 1;
+      gdma16(par_lds, (zeros ? a.k_cz : a.k_cs) + chan_off + 4 * piece);
+      gdma16((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)&svc[wave][0],
+             (zeros ? a.v_cz : a.v_cs) + chan_off + 4 * piece);
+      const uint8_t* qrows = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hk * G * a.q_sH) * ESZ + 16 * (lane % PR);
+#pragma unroll
+      for (int t = 0; t < NQ; ++t)
+        if (t * RP < G)                                 // (wave-uniform; rows past the last head repeat it)
+          gdma16(par_lds + 1024 + t * 1024, qrows + (int64_t)min(t * RP + lane / PR, G - 1) * a.q_sH * ESZ);
+    }
     // the first blocks are in flight while the operand is built
 #pragma unroll
     for (int i = 0; i < kStages - 1; ++i) issue(ring_lds + i * kStageBytes, bl_lo + i, bl_lo + i < bl_hi);
 
     u4 qB[KS];
     float Aq, sumqcz, Aq_k[KS], sumqcz_k[KS];
-    build_query_operand(std::integral_constant<int, BITS>{}, a.k_cs + chan_off, a.k_cz + chan_off, a.v_cs + chan_off, a.v_cz + chan_off, qB, Aq, sumqcz, Aq_k, sumqcz_k);
+    wait_vmem<(kStages - 1) * L_STAGE>();               // the parameters have landed (the blocks need not have)
+    build_query_operand(std::integral_constant<int, BITS>{}, par + 1024, (int64_t)(nvalid ? g : 0) * D,
+                        reinterpret_cast<const float*>(par), reinterpret_cast<const float*>(par) + D, qB, Aq, sumqcz, Aq_k, sumqcz_k);
     // Subnormal codes: the logit is ts (dot - tz sum(q') - sum(q' cz)), the two sums taken off
     // after the matrix instructions.  Normalized codes (fp32 tensors) add SC sum(q') to the
     // accumulator on top; there everything that is taken off is taken off k-step by k-step,
@@ -903,8 +946,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-      const float4 vcs4 = *reinterpret_cast<const float4*>(&svc[wave][0][4 * (n + 16 * r)]);
-      const float4 vcz4 = *reinterpret_cast<const float4*>(&svc[wave][1][4 * (n + 16 * r)]);
+      const float4 vcs4 = *reinterpret_cast<const float4*>(&svc[wave][4 * (n + 16 * r)]);
+      const float4 vcz4 = *reinterpret_cast<const float4*>(&svc[wave][D + 4 * (n + 16 * r)]);
       const float cs[4] = {vcs4.x, vcs4.y, vcs4.z, vcs4.w}, cz[4] = {vcz4.x, vcz4.y, vcz4.z, vcz4.w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {

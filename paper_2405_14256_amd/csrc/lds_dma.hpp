@@ -21,6 +21,10 @@ __device__ inline void dma4(uint32_t lds_addr, __amdgpu_buffer_rsrc_t rs, int vo
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                :: "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff) : "memory");
 }
+// The same with an address of its own per lane (no buffer descriptor, no range check).
+__device__ inline void gdma16(uint32_t lds_addr, const void* lane_src) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds_addr), "v"(lane_src) : "memory");
+}
 template <int N>
 __device__ inline void wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ inline void dma_reuse_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
