@@ -425,19 +425,33 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 
   // Combines the (m, Z, o) the four waves left in LDS and writes the workgroup's
   // result: the output itself when it is the only workgroup of its KV head.
+  // (Everything is read from LDS before anything is computed, and a wave without tokens -
+  // m = -inf; its sums are zeros - takes part with weight 0 instead of being branched
+  // around: this is the end of the call's critical path, and with a branch per wave the
+  // reads went out one dependent round trip after the other.)
   auto write_result = [&]() {
     const bool direct = a.S == 1;
-    for (int i = tid; i < G * D; i += 256) {
+    constexpr int NIT = MG * D / 256;               // most elements per thread
+    float pm[NIT][4], pz[NIT][4], po[NIT][4];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if (256 * it >= G * D) break;                 // (wave-uniform)
+      const int i = min(tid + 256 * it, G * D - 1), gg = i / D, c = i % D;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) { pm[it][w] = mM[w][gg]; pz[it][w] = mZ[w][gg]; po[it][w] = mO(w, gg, c); }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int i = tid + 256 * it;
+      if (i >= G * D) break;
       const int gg = i / D, c = i % D;
-      float M = fmaxf(fmaxf(mM[0][gg], mM[1][gg]), fmaxf(mM[2][gg], mM[3][gg]));
+      const float M = fmaxf(fmaxf(pm[it][0], pm[it][1]), fmaxf(pm[it][2], pm[it][3]));
       float o = 0.f, z = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        if (mM[w][gg] > -INFINITY) {
-          const float f = fast_exp2(mM[w][gg] - M);
-          o = fmaf(mO(w, gg, c), f, o);
-          z = fmaf(mZ[w][gg], f, z);
-        }
+        const float f = (pm[it][w] > -INFINITY) ? fast_exp2(pm[it][w] - M) : 0.f;
+        o = fmaf(po[it][w], f, o);
+        z = fmaf(pz[it][w], f, z);
       }
       const int64_t hq = (int64_t)b * a.Hq + hk * G + gg;
       if (direct) {
@@ -1033,9 +1047,16 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
 #pragma unroll
   for (int ss = 0; ss < kCombineMax; ++ss) po[ss] = part_o[(row + min(ss, last)) * D + c];
   if (lane > last) { pmv = -INFINITY; pzv = 0.f; }
+  // maximum over the lanes: inside the rows of 16, then row to row into lane 63 (vector
+  // instructions with lane permutation; no round trips through the LDS crossbar)
   float M = pmv;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x111, 0xF, 0xF, false)));   // row_shr:1
+  M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x112, 0xF, 0xF, false)));   // row_shr:2
+  M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x114, 0xF, 0xF, false)));   // row_shr:4
+  M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x118, 0xF, 0xF, false)));   // row_shr:8
+  M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x142, 0xA, 0xF, false)));   // row_bcast:15
+  M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x143, 0xC, 0xF, false)));   // row_bcast:31
+  M = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(M), 63));
   const float fv = (pmv > -INFINITY) ? fast_exp2(pmv - M) : 0.f;
   float o = 0.f, z = 0.f;
 #pragma unroll
