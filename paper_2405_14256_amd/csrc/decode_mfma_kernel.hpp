@@ -974,8 +974,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   };
 
   if (!tail_wave) {
-    for (int ci = 0; ci < a.n_chunks; ++ci) {
+    for (int ci = 0; ci < a.n_chunks && cursor < u1; ++ci) {
       for (int sub = 0; sub < 2; ++sub) {
+        if (cursor >= u1) break;                   // the wave's run ends before this segment: nothing left to do
         // The row of the chunk table: from the kernel arguments (a scalar load) when the
         // table travels there, else from memory.  The empty asm statements pin each
         // source's values in scalar registers, so that the two loads are not merged
