@@ -272,6 +272,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
                  "s"(p7), "s"(p8), "s"(p9), "s"(p10), "s"(p11), "s"(p12), "s"(p13));
   }
 
+  // The chunk table that travels in the kernel arguments, one entry per lane: fetched once,
+  // here, with the other arguments; the chunk loop then takes its rows from the lanes (a
+  // scalar load per row would be a dependent round trip per segment the wave looks at).
+  int rows_v = 0;
+  if (a.chunks_inline) rows_v = a.chunk_rows[min(lane, 4 * kInlineChunks - 1)];
+
   // The waves of the workgroups of one (batch, KV head) are workers of their own:
   // n_tw of them take the full-precision tail, the other n_pw share the cost line of
   // the packed cache (half-blocks + kSegCost per segment start, a contiguous run each).
@@ -977,14 +983,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     for (int ci = 0; ci < a.n_chunks && cursor < u1; ++ci) {
       for (int sub = 0; sub < 2; ++sub) {
         if (cursor >= u1) break;                   // the wave's run ends before this segment: nothing left to do
-        // The row of the chunk table: from the kernel arguments (a scalar load) when the
-        // table travels there, else from memory.  The empty asm statements pin each
-        // source's values in scalar registers, so that the two loads are not merged
-        // into one load through a selected (then generic) pointer.
+        // The row of the chunk table: from the lanes of rows_v when the table travels in the
+        // kernel arguments, else from memory.
         int begin, len;
         if (a.chunks_inline) {
-          begin = a.chunk_rows[4 * ci + 2 * sub]; len = a.chunk_rows[4 * ci + 2 * sub + 1];
-          asm volatile("" : "+s"(begin), "+s"(len));
+          begin = __builtin_amdgcn_readlane(rows_v, 4 * ci + 2 * sub);
+          len = __builtin_amdgcn_readlane(rows_v, 4 * ci + 2 * sub + 1);
         } else {
           begin = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub]);
           len = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub + 1]);
