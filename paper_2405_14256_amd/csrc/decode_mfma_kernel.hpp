@@ -277,6 +277,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // scalar load per row would be a dependent round trip per segment the wave looks at).
   int rows_v = 0;
   if (a.chunks_inline) rows_v = a.chunk_rows[min(lane, 4 * kInlineChunks - 1)];
+  // What the packed waves need again at their chunk loop: held in scalar registers from here
+  // on (as outputs of an empty asm statement they cannot be fetched again where they are used,
+  // which the compiler otherwise does - two more dependent round trips before the loop).
+  int p_n_chunks = a.n_chunks, p_inline = a.chunks_inline, p_B = a.B, p_Hkv = a.Hkv;
+  float p_scale = a.scale_log2;
+  asm volatile("" : "+s"(p_n_chunks), "+s"(p_inline), "+s"(p_B), "+s"(p_Hkv), "+s"(p_scale));
 
   // The waves of the workgroups of one (batch, KV head) are workers of their own:
   // n_tw of them take the full-precision tail, the other n_pw share the cost line of
@@ -386,7 +392,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     // Unused columns get q' = 0.  For 16-bit tensors the sums take q' itself rather than
     // the value the two fp16 columns represent (they differ by 2^-22 relative: nothing
     // next to the rounding of a 16-bit output); fp32 tensors take the represented value.
-    const float lane_scale = nvalid ? a.scale_log2 : 0.f;
+    const float lane_scale = nvalid ? p_scale : 0.f;
     float sq = 0.f, sqz = 0.f;
 #pragma unroll
     for (int ks0 = 0; ks0 < KS; ++ks0) {
@@ -670,14 +676,14 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     constexpr int ROWB = D * BITS / 8;                  // bytes of one K row
     constexpr float UNSCALE = code_unscale<BITS, SUBN>();
     constexpr float SC = (BITS == 4) ? 16.f : 4.f;     // normalized encoding: 1 + code / SC
-    const int64_t chan_off = ((int64_t)(ci * 2 + sub) * a.B + b) * (a.Hkv * D) + hk * D;
+    const int64_t chan_off = ((int64_t)(ci * 2 + sub) * p_B + b) * (p_Hkv * D) + hk * D;
     // lo, hi: this wave's range of the segment in half-blocks (not empty)
     const int hlo = lo, hhi = hi;
 
     // Buffer resources over this (batch, KV head)'s part of each array: the
     // per-lane offset is fixed, the half-block adds a scalar offset, reads past
     // the end return zeros.  (The host checks that each part is below 4 GiB.)
-    const int64_t bh = (int64_t)b * a.Hkv + hk;
+    const int64_t bh = (int64_t)b * p_Hkv + hk;
     // (selects between the two subsets' kernel arguments, which are in registers already:
     // an index would be another scalar load and another wait)
     const int64_t cap = sub ? a.cap[1] : a.cap[0];
@@ -980,13 +986,13 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   };
 
   if (!tail_wave) {
-    for (int ci = 0; ci < a.n_chunks && cursor < u1; ++ci) {
+    for (int ci = 0; ci < p_n_chunks && cursor < u1; ++ci) {
       for (int sub = 0; sub < 2; ++sub) {
         if (cursor >= u1) break;                   // the wave's run ends before this segment: nothing left to do
         // The row of the chunk table: from the lanes of rows_v when the table travels in the
         // kernel arguments, else from memory.
         int begin, len;
-        if (a.chunks_inline) {
+        if (p_inline) {
           begin = __builtin_amdgcn_readlane(rows_v, 4 * ci + 2 * sub);
           len = __builtin_amdgcn_readlane(rows_v, 4 * ci + 2 * sub + 1);
         } else {
