@@ -1044,19 +1044,21 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 // past the last one repeat it, with weight 0), and the weights 2^(m - M) come from one
 // exponential over the lanes, handed round as scalars.  (With a branch per split - which
 // loads exist depends on S - the loads took 1.6 us to issue and land, against 0.8 us here.)
-template <int DT, int D>
+// NMAX: the most splits this instance handles (8 for launches that fill the chip, whose heads
+// have few splits each; kCombineMax otherwise).
+template <int DT, int D, int NMAX>
 __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ part_m, const float* __restrict__ part_z,
                                                       const float* __restrict__ part_o, int S,
                                                       void* __restrict__ out, float* __restrict__ lse_out) {
-  static_assert(kCombineMax <= 64, "one lane per split");
+  static_assert(NMAX <= kCombineMax && kCombineMax <= 64, "one lane per split");
   const int64_t hq = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
   const int c = threadIdx.x, lane = c & 63;
   const int last = S - 1;
   const int64_t row = hq * S;
   float pmv = part_m[row + min(lane, last)], pzv = part_z[row + min(lane, last)];
-  float po[kCombineMax];
+  float po[NMAX];
 #pragma unroll
-  for (int ss = 0; ss < kCombineMax; ++ss) po[ss] = part_o[(row + min(ss, last)) * D + c];
+  for (int ss = 0; ss < NMAX; ++ss) po[ss] = part_o[(row + min(ss, last)) * D + c];
   if (lane > last) { pmv = -INFINITY; pzv = 0.f; }
   // maximum over the lanes: inside the rows of 16, then row to row into lane 63 (vector
   // instructions with lane permutation; no round trips through the LDS crossbar)
@@ -1071,7 +1073,7 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
   const float fv = (pmv > -INFINITY) ? fast_exp2(pmv - M) : 0.f;
   float o = 0.f, z = 0.f;
 #pragma unroll
-  for (int ss = 0; ss < kCombineMax; ++ss) {
+  for (int ss = 0; ss < NMAX; ++ss) {
     const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fv), ss));
     const float pz = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pzv), ss));
     o = fmaf(po[ss], f, o);
@@ -1102,8 +1104,10 @@ static int launch_decode_mfma_dt(const DecArgs& a, hipStream_t st) {
 #undef ZC_L
   ZC_LAUNCH_CHECK();
   if (a.S > 1) {
-    if (a.D == 128) hipLaunchKernelGGL((k_decode_reduce<DT, 128>), dim3(a.Hq, a.B), dim3(128), 0, st, a.part_m, a.part_z, a.part_o, a.S, a.out, a.lse_out);
-    else hipLaunchKernelGGL((k_decode_reduce<DT, 64>), dim3(a.Hq, a.B), dim3(64), 0, st, a.part_m, a.part_z, a.part_o, a.S, a.out, a.lse_out);
+#define ZC_R(DD, NM) hipLaunchKernelGGL((k_decode_reduce<DT, DD, NM>), dim3(a.Hq, a.B), dim3(DD), 0, st, a.part_m, a.part_z, a.part_o, a.S, a.out, a.lse_out)
+    if (a.D == 128) { if (a.S <= 8) ZC_R(128, 8); else ZC_R(128, kCombineMax); }
+    else { if (a.S <= 8) ZC_R(64, 8); else ZC_R(64, kCombineMax); }
+#undef ZC_R
     ZC_LAUNCH_CHECK();
   }
   return ZC_OK;
