@@ -335,8 +335,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // two sums over the 32 channels of every k-step (what the normalized encoding needs to
   // keep its accumulators centred, see the segment).
   // qsrc + qoff (elements): the query row of this lane's head; kcs, kcz: the K channel
-  // parameters of the segment.  The tail reads q from global memory; a packed segment has
-  // had the rows and the parameters brought to LDS (see the segment).
+  // parameters of the segment.  In global memory, or in LDS when a packed segment has had
+  // the rows and the parameters brought there (see the segment).
   auto build_query_operand = [&](auto mode_c, const void* qsrc, int64_t qoff, const float* kcs, const float* kcz,
                                  u4 (&qB)[KS], float& sumqq, float& sumqqcz, float (&sum_k)[KS], float (&sumcz_k)[KS]) {
     constexpr int MODE = decltype(mode_c)::value;
@@ -735,12 +735,16 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         dma4(dst + 2 * kCodeBytes + 768, rs_ktz, v4, to);
       }
     };
-    // What the query operand is built from goes to LDS by three or four transfers of its own
-    // (with a load per lane and k-step - some thirty of them, each with its address arithmetic
-    // - a wave needed 0.8 us just to issue them): the K channel scales and zeros (1 KB: lanes
-    // pick their 16-byte piece of either array) and the query rows of the KV head's G heads go
-    // to the ring's last stage, which is free until the block loop's first request; the V
-    // channel scales and zeros go to svc, where they wait until the segment is folded.
+    // Launches of at most one workgroup per CU, where only latency counts (MINB == 1): what the
+    // query operand is built from goes to LDS by three or four transfers of its own (with a
+    // load per lane and k-step - some thirty of them, each with its address arithmetic - a wave
+    // needed 0.8 us just to issue them): the K channel scales and zeros (1 KB: lanes pick their
+    // 16-byte piece of either array) and the query rows of the KV head's G heads go to the
+    // ring's last stage, which is free until the block loop's first request; the V channel
+    // scales and zeros go to svc, where they wait until the segment is folded.  Launches that
+    // fill the chip keep the loads per lane: there the transfers cost throughput (cfg 4 went
+    // from 61 to 62.5 us per call with them, from 79 to 84 us with cold caches).
+    constexpr bool STAGED = (MINB == 1);
     constexpr int ESZ = (DT == ZC_F32) ? 4 : 2;
     constexpr int PA = D / 4;                           // 16-byte pieces of a parameter row
     constexpr int PR = D * ESZ / 16, RP = 64 / PR;      // 16-byte pieces of a query row; rows per transfer
@@ -748,7 +752,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     static_assert(1024 + NQ * 1024 <= kStageBytes, "the parameters fit a stage of the ring");
     const uint32_t par_lds = ring_lds + (kStages - 1) * kStageBytes;
     const uint8_t* par = ring_gen + (kStages - 1) * kStageBytes;
-    {
+    if constexpr (STAGED) {
       const int piece = lane % PA;
       const bool zeros = (lane / PA) & 1;
       gdma16(par_lds, (zeros ? a.k_cz : a.k_cs) + chan_off + 4 * piece);
@@ -766,9 +770,21 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 
     u4 qB[KS];
     float Aq, sumqcz, Aq_k[KS], sumqcz_k[KS];
-    wait_vmem<(kStages - 1) * L_STAGE>();               // the parameters have landed (the blocks need not have)
-    build_query_operand(std::integral_constant<int, BITS>{}, par + 1024, (int64_t)(nvalid ? g : 0) * D,
-                        reinterpret_cast<const float*>(par), reinterpret_cast<const float*>(par) + D, qB, Aq, sumqcz, Aq_k, sumqcz_k);
+    if constexpr (STAGED) {
+      wait_vmem<(kStages - 1) * L_STAGE>();             // the parameters have landed (the blocks need not have)
+      build_query_operand(std::integral_constant<int, BITS>{}, par + 1024, (int64_t)(nvalid ? g : 0) * D,
+                          reinterpret_cast<const float*>(par), reinterpret_cast<const float*>(par) + D, qB, Aq, sumqcz, Aq_k, sumqcz_k);
+    } else {
+      // the V channel parameters wait in this wave's part of LDS until the segment is folded
+      if (lane < D / 2) {
+        const bool zero_half = lane >= D / 4;
+        const int c4 = 4 * (zero_half ? lane - D / 4 : lane);
+        const float4 t = *reinterpret_cast<const float4*>((zero_half ? a.v_cz : a.v_cs) + chan_off + c4);
+        *reinterpret_cast<float4*>(&svc[wave][(zero_half ? D : 0) + c4]) = t;
+      }
+      build_query_operand(std::integral_constant<int, BITS>{}, a.q, (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH,
+                          a.k_cs + chan_off, a.k_cz + chan_off, qB, Aq, sumqcz, Aq_k, sumqcz_k);
+    }
     // Subnormal codes: the logit is ts (dot - tz sum(q') - sum(q' cz)), the two sums taken off
     // after the matrix instructions.  Normalized codes (fp32 tensors) add SC sum(q') to the
     // accumulator on top; there everything that is taken off is taken off k-step by k-step,
