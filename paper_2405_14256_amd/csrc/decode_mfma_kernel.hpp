@@ -303,24 +303,39 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 
   // The running maximum of a head is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
-  // accumulated so far is then rescaled.  Rare after the first half-blocks.
+  // accumulated so far is then rescaled.  Rare after the first half-blocks - but a wave of a
+  // short cache has only one or two: its first half-block, which finds nothing accumulated
+  // yet, only takes the maximum over, and the factors of the heads of a lane's output rows
+  // (columns 4 grp and 4 grp + 2; every row holds the same factors) come from row broadcasts
+  // with a row mask instead of two shuffles through the LDS crossbar.
   auto update_max = [&](float lmax, float (&a1)[4], f4 (*acc)[4], f4& acc1) {
     if (__builtin_amdgcn_ballot_w64(lmax > m_run)) {     // (unused columns sit at +inf)
       const float m_new = fmaxf(m_run, grp_max(lmax));
-      const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
-      z_part *= fac;
+      if (__builtin_amdgcn_ballot_w64(nvalid && m_run > -INFINITY)) {
+        const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
+        z_part *= fac;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) a1[v] *= fac;
-      const float f0 = __shfl(fac, 2 * g0), f1 = __shfl(fac, 2 * g1);
-      Zrun0 *= f0; Zrun1 *= f1;
+        for (int v = 0; v < 4; ++v) a1[v] *= fac;
+        const int fi = __float_as_int(fac);
+        int i0 = __builtin_amdgcn_update_dpp(0, fi, 0x150, 0x1, 0xF, false);       // row 0 <- its lane 0
+        i0 = __builtin_amdgcn_update_dpp(i0, fi, 0x154, 0x2, 0xF, false);          // row 1 <- its lane 4
+        i0 = __builtin_amdgcn_update_dpp(i0, fi, 0x158, 0x4, 0xF, false);          // row 2 <- its lane 8
+        i0 = __builtin_amdgcn_update_dpp(i0, fi, 0x15C, 0x8, 0xF, false);          // row 3 <- its lane 12
+        int i1 = __builtin_amdgcn_update_dpp(0, fi, 0x152, 0x1, 0xF, false);       // lanes 2, 6, 10, 14
+        i1 = __builtin_amdgcn_update_dpp(i1, fi, 0x156, 0x2, 0xF, false);
+        i1 = __builtin_amdgcn_update_dpp(i1, fi, 0x15A, 0x4, 0xF, false);
+        i1 = __builtin_amdgcn_update_dpp(i1, fi, 0x15E, 0x8, 0xF, false);
+        const float f0 = __int_as_float(i0), f1 = __int_as_float(i1);
+        Zrun0 *= f0; Zrun1 *= f1;
 #pragma unroll
-      for (int r = 0; r < NR; ++r)
+        for (int r = 0; r < NR; ++r)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          O[r][j][0] *= f0; O[r][j][1] *= f1;
-          acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1;
-        }
-      acc1.x *= f0; acc1.y *= f0; acc1.z *= f1; acc1.w *= f1;
+          for (int j = 0; j < 4; ++j) {
+            O[r][j][0] *= f0; O[r][j][1] *= f1;
+            acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1;
+          }
+        acc1.x *= f0; acc1.y *= f0; acc1.z *= f1; acc1.w *= f1;
+      }
       m_run = m_new;
     }
   };
