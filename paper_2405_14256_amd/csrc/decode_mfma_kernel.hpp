@@ -757,8 +757,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     // 16-byte piece of either array) and the query rows of the KV head's G heads go to the
     // ring's last stage, which is free until the block loop's first request; the V channel
     // scales and zeros go to svc, where they wait until the segment is folded.  Launches that
-    // fill the chip keep the loads per lane: there the transfers cost throughput (cfg 4 went
-    // from 61 to 62.5 us per call with them, from 79 to 84 us with cold caches).
+    // fill the chip keep the loads per lane: there the transfers cost throughput (16 prompts
+    // of 4096 tokens with 40 heads: 61 -> 62.5 us per call with them, 79 -> 84 us with cold caches).
     constexpr bool STAGED = (MINB == 1);
     constexpr int ESZ = (DT == ZC_F32) ? 4 : 2;
     constexpr int PA = D / 4;                           // 16-byte pieces of a parameter row
