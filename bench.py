@@ -652,6 +652,73 @@ def decode_sweep(args):
                       "fit_cold": {"t0_us": float(t0), "asymptotic_GBps": float(1e-3 / slope)}, "rows": rows}))
 
 
+TIMELINE_MARKS = ["entry", "arguments in registers", "query operand built", "first block in LDS", "half-blocks done",
+                  "segments folded", "at the merge barrier", "result stored", "tail units done"]
+
+
+def decode_timeline(args):
+    """One decode call in slow motion.  Loads the traced build of the library, compresses the
+    workload's prompt, replays a graph of eight decode calls a few times and reads the time
+    stamps of the last call: per mark the minimum, median and maximum over the waves that
+    reached it, in microseconds after the first wave's entry; the reduce kernel likewise; and
+    the period of a call from the same graph's HIP events."""
+    import ctypes as C
+    trace_lib = os.path.join(os.path.dirname(zb.LIB_PATH), "libzipcache_trace.so")
+    if not os.path.exists(trace_lib):
+        raise SystemExit(f"{trace_lib} is missing: run `python __graft_entry__.py`")
+    zb.LIB_PATH = trace_lib
+    lib = zb.load()
+    lib.zc_trace_fetch.restype = C.c_int
+    lib.zc_trace_fetch.argtypes = [C.c_void_p, C.c_size_t, C.c_int]
+    w = WORKLOADS[args.workload]
+    if w.dtype != "bf16":
+        raise SystemExit("--decode-timeline: only the bf16 kernels of the traced build carry time stamps")
+    hp = HotPath(w)
+    for _, fn, _, _ in hp.stages()[:3]:               # probe, select, quantize
+        fn()
+    T = min(args.tail_len, hp.tail_k.shape[2])
+    calls = 8
+
+    def call(j):
+        zb.zc_decode_attention(hp.q_all[:, :, j:j + 1], hp.Kp, hp.Vp, hp.tail_k, hp.tail_v, T, out=hp.out[j])
+
+    for j in range(3):
+        call(j)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for j in range(calls):
+            call(j)
+    SLOTS, WAVES, HEADS = 16, 8192, 2048
+    buf = np.zeros(WAVES * SLOTS + HEADS * 4, np.uint64)
+    assert lib.zc_trace_fetch(None, 0, 1) == 0        # clear what the eager calls left
+    periods = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); g.replay(); e1.record()
+        torch.cuda.synchronize()
+        periods.append(e0.elapsed_time(e1) * 1e3 / calls)
+    assert lib.zc_trace_fetch(buf.ctypes.data, buf.size, 0) == 0
+    waves = buf[:WAVES * SLOTS].reshape(WAVES, SLOTS).astype(np.int64)
+    waves = waves[waves[:, 0] != 0]
+    heads = buf[WAVES * SLOTS:].reshape(HEADS, 4).astype(np.int64)
+    heads = heads[heads[:, 0] != 0]
+    t0 = waves[:, 0].min()
+
+    def stats(col):
+        col = (col[col != 0] - t0) * 0.01             # 100 MHz counter -> microseconds
+        return None if col.size == 0 else {"waves": int(col.size), "min": round(float(col.min()), 2),
+                                           "median": round(float(np.median(col)), 2), "max": round(float(col.max()), 2)}
+
+    out = {"mode": "decode-timeline", "workload": w.name, "tail_len": int(T), "unit": "us after the first wave's entry",
+           "call_period_us": round(sorted(periods)[len(periods) // 2], 3),
+           "k_decode_mfma": {name: stats(waves[:, i]) for i, name in enumerate(TIMELINE_MARKS)},
+           "k_decode_reduce": {name: stats(heads[:, i]) for i, name in enumerate(["entry", "partials landed", "end"])},
+           "note": "time stamps of the last of eight calls in a replayed graph; the traced kernels are a little slower "
+                   "than the library's (a mark costs a scalar memory instruction and a store)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -677,6 +744,11 @@ def main():
     ap.add_argument("--decode-sweep", action="store_true",
                     help="instead of the step: time the decode entry point alone at batch 1..64 of the "
                          "workload's layer shape, cold and warm caches, and print that table as one JSON line")
+    ap.add_argument("--decode-timeline", action="store_true",
+                    help="instead of the step: what one decode call's latency is made of - time stamps the decode "
+                         "kernels of the traced build of the library (libzipcache_trace.so, bf16 workloads) write at "
+                         "their phase boundaries; medians over the waves of a call, one JSON line")
+    ap.add_argument("--tail-len", type=int, default=50, help="--decode-timeline: tokens in the full-precision tail")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -684,6 +756,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.decode_timeline:
+        decode_timeline(args)
+        return
     zb.load()
     if args.peaks:
         machine_peaks(args)

@@ -44,6 +44,32 @@
 
 namespace zc {
 
+// ---- time stamps for the latency analysis (bench.py --decode-timeline) ---------------------
+// A build with ZC_TRACE (libzipcache_trace.so; include/zc_trace.h) records the 100 MHz
+// real-time counter at the phase boundaries marked ZC_MARK below - per wave of k_decode_mfma,
+// per workgroup of k_decode_reduce - into a buffer of the library, which zc_trace_fetch copies
+// out.  In the library proper the marks are nothing.  A mark inside a segment is overwritten
+// by the wave's next segment; waves past the buffer's end share its last row.
+#ifdef ZC_TRACE
+constexpr int kTraceSlots = 16;              // marks per wave (ZC_TRACE_SLOTS of zc_trace.h)
+constexpr int kTraceWaves = 8192;            // rows for waves of k_decode_mfma (ZC_TRACE_WAVES)
+constexpr int kTraceHeads = 2048;            // rows of 4 marks for workgroups of k_decode_reduce (ZC_TRACE_HEADS)
+static __device__ unsigned long long zc_trace_buf[kTraceWaves * kTraceSlots + kTraceHeads * 4];
+#define ZC_TRACE_WAVE_ROW(wave_)                                                                        \
+  unsigned long long* zc_tp =                                                                           \
+      &zc_trace_buf[(size_t)min((int)(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (wave_)), kTraceWaves - 1) * kTraceSlots]; \
+  asm volatile("" : "+v"(zc_tp))
+#define ZC_TRACE_HEAD_ROW(head_) \
+  unsigned long long* zc_tp = &zc_trace_buf[(size_t)kTraceWaves * kTraceSlots + (size_t)min((int)(head_), kTraceHeads - 1) * 4]
+#define ZC_MARK(i) do { if ((threadIdx.x & 63) == 0) zc_tp[(i)] = wall_clock64(); } while (0)
+#define ZC_MARK_LOADED(i) do { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); ZC_MARK(i); } while (0)
+#else
+#define ZC_TRACE_WAVE_ROW(wave_) ((void)0)
+#define ZC_TRACE_HEAD_ROW(head_) ((void)0)
+#define ZC_MARK(i) ((void)0)
+#define ZC_MARK_LOADED(i) ((void)0)
+#endif
+
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -227,6 +253,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int n = lane & 15, grp = lane >> 4;
   const int G = a.G;
+  ZC_TRACE_WAVE_ROW(wave);
+  ZC_MARK(0);                                   // entry
   const int g = n >> 1, part = n & 1;
   const bool nvalid = n < 2 * G;
   const int g0 = 2 * grp, g1 = 2 * grp + 1;      // heads of this lane's rows in the output tiles
@@ -272,6 +300,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
                  "s"(p7), "s"(p8), "s"(p9), "s"(p10), "s"(p11), "s"(p12), "s"(p13));
   }
 
+  ZC_MARK(1);                                   // the first batch of arguments is in registers
   // The chunk table that travels in the kernel arguments, one entry per lane: fetched once,
   // here, with the other arguments; the chunk loop then takes its rows from the lanes (a
   // scalar load per row would be a dependent round trip per segment the wave looks at).
@@ -682,6 +711,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     }
   }
 
+  if (tail_wave) ZC_MARK(8);                    // a tail wave has finished its units
   int cursor = 0;
   // ---------------- packed segments --------------------------------------------------
   auto segment = [&](auto bits_c, int ci, int sub, int begin, int len, int lo, int hi) {
@@ -800,6 +830,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       build_query_operand(std::integral_constant<int, BITS>{}, a.q, (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH,
                           a.k_cs + chan_off, a.k_cz + chan_off, qB, Aq, sumqcz, Aq_k, sumqcz_k);
     }
+    ZC_MARK(2);                                 // the segment's query operand is built
     // Subnormal codes: the logit is ts (dot - tz sum(q') - sum(q' cz)), the two sums taken off
     // after the matrix instructions.  Normalized codes (fp32 tensors) add SC sum(q') to the
     // accumulator on top; there everything that is taken off is taken off k-step by k-step,
@@ -969,6 +1000,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       dma_reuse_fence();                         // the reads of the buffer about to be refilled are complete
       issue(dst_ahead, bi + kStages - 1, bi + kStages - 1 < bl_hi);
       wait_vmem<(kStages - 1) * L_STAGE>();
+      if (bi == bl_lo) ZC_MARK(3);              // the segment's first block has landed
       if constexpr (NH == 1) {
         half_block(std::integral_constant<int, 0>{}, bi);
       } else {
@@ -982,6 +1014,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       dst_ahead = (st_ahead == kStages - 1) ? ring_lds : dst_ahead + kStageBytes;
       st_ahead = (st_ahead == kStages - 1) ? 0 : st_ahead + 1;
     }
+    ZC_MARK(4);                                 // the segment's half-blocks are done
     wait_vmem<0>();                              // the out-of-range requests have landed too
     dma_reuse_fence();                           // the ring is reused (next segment, merge)
     // ---- fold the segment into O ----
@@ -1044,6 +1077,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       }
     }
 
+    ZC_MARK(5);                                 // the segments are folded
     // ---------------- this wave's partial, for the merge of the four waves ---------------
     if constexpr (WSPLIT) {
       const float z_tot = grp_sum(z_part);
@@ -1064,8 +1098,10 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         if (g1 < G) mO(wave, g1, c) = O[r][j][1];
       }
   }
+  ZC_MARK(6);                                   // at the barrier before the merge
   __syncthreads();
   write_result();
+  ZC_MARK(7);                                   // the workgroup's result is stored
 }
 
 // Reduces the partial (m, Z, o) of the workgroups of one query head.  The call's latency is
@@ -1085,12 +1121,15 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
   const int64_t hq = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
   const int c = threadIdx.x, lane = c & 63;
   const int last = S - 1;
+  ZC_TRACE_HEAD_ROW(hq);
+  if (c == 0) ZC_MARK(0);                       // entry
   const int64_t row = hq * S;
   float pmv = part_m[row + min(lane, last)], pzv = part_z[row + min(lane, last)];
   float po[NMAX];
 #pragma unroll
   for (int ss = 0; ss < NMAX; ++ss) po[ss] = part_o[(row + min(ss, last)) * D + c];
   if (lane > last) { pmv = -INFINITY; pzv = 0.f; }
+  if (c == 0) ZC_MARK_LOADED(1);                // the partials have landed (the trace build waits for them here)
   // maximum over the lanes: inside the rows of 16, then row to row into lane 63 (vector
   // instructions with lane permutation; no round trips through the LDS crossbar)
   float M = pmv;
@@ -1112,6 +1151,7 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
   }
   store1<DT>(out, hq * D + c, z > 0.f ? o / z : 0.f);
   if (lse_out && c == 0) lse_out[hq] = (M + log2f(z)) * kLn2;
+  if (c == 0) ZC_MARK(2);                       // end
 }
 
 template <int DT>

@@ -31,6 +31,24 @@ def test_library_exports_every_declared_symbol():
     assert b"workspace" in lib.zc_status_string(-3)
 
 
+def test_traced_library_exports_both_headers():
+    """libzipcache_trace.so (bench.py --decode-timeline) is the library with time stamps in the
+    bf16 decode kernels: everything zipcache.h declares, plus zc_trace.h."""
+    src = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "zc_trace.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(zc_trace_[a-z_]+)\s*\(", src)))
+    assert names == ["zc_trace_fetch"]
+    lib = C.CDLL(os.path.join(ROOT, "paper_2405_14256_amd", "libzipcache_trace.so"))
+    for n in names + declared_functions():
+        assert hasattr(lib, n), f"{n} is not exported by the traced library"
+    assert not hasattr(zb.load(), "zc_trace_fetch")          # the library proper records nothing
+    lib.zc_trace_fetch.argtypes = [C.c_void_p, C.c_size_t, C.c_int]
+    slots = 16 * 8192 + 4 * 2048
+    assert re.search(r"#define ZC_TRACE_SLOTS 16\b", src) and re.search(r"#define ZC_TRACE_WAVES 8192\b", src) \
+        and re.search(r"#define ZC_TRACE_HEADS 2048\b", src)
+    assert lib.zc_trace_fetch(None, slots + 1, 0) == -1      # refused on the host: larger than the buffer
+    assert lib.zc_trace_fetch(None, 8, 0) == -1              # ... no destination
+
+
 def test_peak_probe_library_exports_its_header_and_checks_arguments():
     """The machine-peak probes of bench.py --peaks live in a library of their own."""
     src = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "zc_peaks.h")).read(), flags=re.S)

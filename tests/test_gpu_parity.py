@@ -1,5 +1,7 @@
 """GPU parity tests: every stage of the hot path, called through the C ABI,
 against the float64 oracle on the same seeded inputs."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -794,3 +796,25 @@ def test_results_are_deterministic():
         outs.append((sc.clone(), sal.clone(), Kp.codes_lo.clone(), Vp.codes_hi.clone(), Vp.tok_scale_lo.clone(), o.clone()))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_decode_timeline_mode_of_the_benchmark():
+    """bench.py --decode-timeline: the traced build of the library runs a decode call and its
+    time stamps come out in order (entry <= arguments <= operand <= first block <= half-blocks
+    done <= folded <= barrier <= stored; the reduce kernel after the first kernel's last store)."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--decode-timeline"], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr[-2000:]
+    d = json.loads([ln for ln in out.stdout.splitlines() if ln.startswith("{")][-1])
+    m = d["k_decode_mfma"]
+    order = ["entry", "arguments in registers", "query operand built", "first block in LDS", "half-blocks done",
+             "segments folded", "at the merge barrier", "result stored"]
+    med = [m[k]["median"] for k in order]
+    assert all(a <= b for a, b in zip(med, med[1:])), med
+    assert m["entry"]["min"] == 0.0 and m["result stored"]["max"] < 50.0
+    r = d["k_decode_reduce"]
+    assert m["result stored"]["max"] <= r["entry"]["min"] <= r["partials landed"]["median"] <= r["end"]["median"]
+    assert 1.0 < d["call_period_us"] < 100.0
