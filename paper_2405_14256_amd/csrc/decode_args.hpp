@@ -8,6 +8,7 @@ namespace zc {
 constexpr int kTailUnit = 16;    // tail tokens per work unit of the MFMA decode kernel (a multiple of 16)
 constexpr int kMaxSplits = 128;
 constexpr int kTailSplits = 8;    // 4 * kTailSplits: most waves per (batch, KV head) that share the tail
+constexpr int kStagedRun = 16;   // packed waves with fewer cost units than this get the staged operand inputs
 constexpr int kSegCost = 3;        // cost, in blocks, charged for starting a segment (query operand)
 constexpr int kInlineChunks = 12;  // chunk-table rows that travel in the kernel arguments
 

@@ -227,7 +227,9 @@ __device__ inline void raw_to_float(const Raw8<DT>& r, float (&v)[8]) {
 // MINB: workgroups per CU the register budget is sized for.  2 for launches that
 // fill the chip; 1 (the whole register file, nothing spilled to scratch) for
 // launches of at most one workgroup per CU, where only latency counts.
-template <int DT, int D, bool KTOK, bool VTOK, int MINB>
+// STG: the operand's inputs reach LDS by transfers of their own (see the segment): for waves
+// with short runs, where a segment's start is a large part of a wave's time.
+template <int DT, int D, bool KTOK, bool VTOK, int MINB, bool STG>
 __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   constexpr int KS = D / 32;     // k-steps of the logit product
   constexpr int NR = D / 64;     // 16-byte V loads per lane and block
@@ -780,7 +782,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         dma4(dst + 2 * kCodeBytes + 768, rs_ktz, v4, to);
       }
     };
-    // Launches of at most one workgroup per CU, where only latency counts (MINB == 1): what the
+    // Launches whose waves have short runs (STG; always when only latency counts): what the
     // query operand is built from goes to LDS by three or four transfers of its own (with a
     // load per lane and k-step - some thirty of them, each with its address arithmetic - a wave
     // needed 0.8 us just to issue them): the K channel scales and zeros (1 KB: lanes pick their
@@ -789,7 +791,7 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     // scales and zeros go to svc, where they wait until the segment is folded.  Launches that
     // fill the chip keep the loads per lane: there the transfers cost throughput (16 prompts
     // of 4096 tokens with 40 heads: 61 -> 62.5 us per call with them, 79 -> 84 us with cold caches).
-    constexpr bool STAGED = (MINB == 1);
+    constexpr bool STAGED = STG;
     constexpr int ESZ = (DT == ZC_F32) ? 4 : 2;
     constexpr int PA = D / 4;                           // 16-byte pieces of a parameter row
     constexpr int PR = D * ESZ / 16, RP = 64 / PR;      // 16-byte pieces of a query row; rows per transfer
@@ -1158,14 +1160,17 @@ template <int DT>
 static int launch_decode_mfma_dt(const DecArgs& a, hipStream_t st) {
   dim3 grid(a.S, a.Hkv, a.B), block(256);
   const bool small = (int64_t)a.S * a.Hkv * a.B <= a.n_cu;
+  const bool staged = small || a.pw_q < kStagedRun;          // cost units per packed wave
 #define ZC_L(KT, VT)                                                                                          \
   do {                                                                                                        \
     if (a.D == 128) {                                                                                         \
-      if (small) hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 1>), grid, block, 0, st, a);              \
-      else hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 2>), grid, block, 0, st, a);                    \
+      if (small) hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 1, true>), grid, block, 0, st, a);        \
+      else if (staged) hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 2, true>), grid, block, 0, st, a);  \
+      else hipLaunchKernelGGL((k_decode_mfma<DT, 128, KT, VT, 2, false>), grid, block, 0, st, a);             \
     } else {                                                                                                  \
-      if (small) hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 1>), grid, block, 0, st, a);               \
-      else hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 2>), grid, block, 0, st, a);                     \
+      if (small) hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 1, true>), grid, block, 0, st, a);         \
+      else if (staged) hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 2, true>), grid, block, 0, st, a);   \
+      else hipLaunchKernelGGL((k_decode_mfma<DT, 64, KT, VT, 2, false>), grid, block, 0, st, a);              \
     }                                                                                                         \
   } while (0)
   if (a.k_tok && a.v_tok) ZC_L(true, true);
