@@ -279,35 +279,49 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) { O[r][j][0] = 0.f; O[r][j][1] = 0.f; }
 
+  // The chunk table that travels in the kernel arguments, one entry per lane: requested first
+  // of all (a vector load takes longer than the scalar loads below; whether the table is in
+  // the arguments or in memory, these words exist) and used by the chunk loop, which takes its
+  // rows from the lanes (a scalar load per row would be a dependent round trip per segment).
+  const int rows_v = a.chunk_rows[min(lane, 4 * kInlineChunks - 1)];
+  // Likewise the first 64 words of the arguments (everything up to the chunk table), word i in
+  // lane i: what a segment starts from - the arrays of its subset, the channel parameters, the
+  // query - is read from these lanes, a register read each.  As scalar arguments they cost
+  // either registers the kernel does not have (some forty, held from the start) or, fetched
+  // where they are used, a round trip per segment; and a choice between the two subsets'
+  // arrays is compiled as a choice between the ADDRESSES of the two arguments followed by a
+  // load and a wait (per lane, for the channel parameters: three dependent round trips before
+  // a segment's first transfer could be issued).
+  static_assert(offsetof(DecArgs, chunk_rows) <= 256 && sizeof(DecArgs) >= 256, "the lane table covers the fields before the chunk table");
+  // (Only where latency counts, STG: on a compute unit that streams a long cache the answer to
+  // a vector load queues behind the other waves' transfers, and a scalar load does not - 16
+  // prompts of 4096 tokens with 40 heads took 63.1 us per call this way against 60.9.)
+  int args_v = 0;
+  if constexpr (STG) args_v = ((const __attribute__((address_space(4))) int*)__builtin_amdgcn_kernarg_segment_ptr())[lane];
+  auto arg32 = [&](size_t byte_off) { return __builtin_amdgcn_readlane(args_v, (int)(byte_off / 4)); };
+  auto arg64 = [&](size_t byte_off) {
+    return (uint64_t)(uint32_t)__builtin_amdgcn_readlane(args_v, (int)(byte_off / 4)) |
+           ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(args_v, (int)(byte_off / 4) + 1) << 32);
+  };
   // Everything the start of a wave needs from the kernel arguments is requested here, in
   // one batch of scalar loads: left to itself the compiler fetches each field where the
   // control flow first needs it, a dozen dependent round trips before the first load of data.
   {
     int i0 = a.S, i1 = a.n_pw, i2 = a.n_tw, i3 = a.tw_full, i4 = a.tw_rem, i5 = a.tail_alone, i6 = a.pw_q, i7 = a.pw_r,
         i8 = a.tu_q, i9 = a.tu_r, i10 = a.n_chunks, i11 = a.chunks_inline, i12 = a.G, i13 = a.Hq, i14 = a.Hkv, i15 = a.B,
-        i16 = a.tail_len, i17 = a.bits[0], i18 = a.bits[1], i19 = a.chunk_rows[0], i20 = a.chunk_rows[1],
-        i21 = a.chunk_rows[2], i22 = a.chunk_rows[3];
+        i16 = a.tail_len;
     float f0 = a.scale_log2;
-    int64_t l0 = a.q_sB, l1 = a.q_sH, l2 = a.cap[0], l3 = a.cap[1];
-    const void *p0 = a.q, *p1 = a.kc[0], *p2 = a.kc[1], *p3 = a.vc[0], *p4 = a.vc[1], *p5 = a.k_cs, *p6 = a.k_cz,
-               *p7 = a.v_cs, *p8 = a.v_cz, *p9 = a.v_ts[0], *p10 = a.v_ts[1], *p11 = a.v_tz[0], *p12 = a.v_tz[1],
-               *p13 = a.chunk_table;
+    int64_t l0 = a.q_sB, l1 = a.q_sH;
+    const void *p0 = a.q, *p13 = a.chunk_table;
     asm volatile("" :: "s"(i0), "s"(i1), "s"(i2), "s"(i3), "s"(i4), "s"(i5), "s"(i6), "s"(i7), "s"(i8), "s"(i9), "s"(i10),
-                 "s"(i11), "s"(i12), "s"(i13), "s"(i14), "s"(i15), "s"(i16), "s"(i17), "s"(i18), "s"(i19), "s"(i20), "s"(i21),
-                 "s"(i22), "s"(f0));
+                 "s"(i11), "s"(i12), "s"(i13), "s"(i14), "s"(i15), "s"(i16), "s"(f0));
     int64_t t0 = a.tk_sB, t1 = a.tk_sH, t2 = a.tk_sL, t3 = a.tv_sB, t4 = a.tv_sH, t5 = a.tv_sL;
     const void *t6 = a.tail_k, *t7 = a.tail_v;
     asm volatile("" :: "s"(t0), "s"(t1), "s"(t2), "s"(t3), "s"(t4), "s"(t5), "s"(t6), "s"(t7));
-    asm volatile("" :: "s"(l0), "s"(l1), "s"(l2), "s"(l3), "s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6),
-                 "s"(p7), "s"(p8), "s"(p9), "s"(p10), "s"(p11), "s"(p12), "s"(p13));
+    asm volatile("" :: "s"(l0), "s"(l1), "s"(p0), "s"(p13));
   }
 
   ZC_MARK(1);                                   // the first batch of arguments is in registers
-  // The chunk table that travels in the kernel arguments, one entry per lane: fetched once,
-  // here, with the other arguments; the chunk loop then takes its rows from the lanes (a
-  // scalar load per row would be a dependent round trip per segment the wave looks at).
-  int rows_v = 0;
-  if (a.chunks_inline) rows_v = a.chunk_rows[min(lane, 4 * kInlineChunks - 1)];
   // What the packed waves need again at their chunk loop: held in scalar registers from here
   // on (as outputs of an empty asm statement they cannot be fetched again where they are used,
   // which the compiler otherwise does - two more dependent round trips before the loop).
@@ -323,14 +337,18 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // has only so many misses in flight.
   // (tail_alone, for launches well below one workgroup per CU where only latency counts:
   // the last n_tw workgroups carry one tail wave each and nothing else)
-  const int my_tails = a.tail_alone ? (s >= a.S - a.n_tw ? 4 : 0) : a.tw_full + (s >= a.S - a.tw_rem ? 1 : 0);
+  // (the split's parameters, pinned like the ones above: the compiler would rather fetch an
+  // argument again than keep it in a register, a dependent round trip before the wave knows its run)
+  int p_S = a.S, p_n_tw = a.n_tw, p_tw_full = a.tw_full, p_tw_rem = a.tw_rem, p_alone = a.tail_alone, p_pw_q = a.pw_q, p_pw_r = a.pw_r;
+  asm volatile("" : "+s"(p_S), "+s"(p_n_tw), "+s"(p_tw_full), "+s"(p_tw_rem), "+s"(p_alone), "+s"(p_pw_q), "+s"(p_pw_r));
+  const int my_tails = p_alone ? (s >= p_S - p_n_tw ? 4 : 0) : p_tw_full + (s >= p_S - p_tw_rem ? 1 : 0);
   const bool tail_wave = wave >= 4 - my_tails;
-  const int pw = a.tail_alone ? 4 * s + wave
-                              : 4 * s - a.tw_full * s - max(0, s - (a.S - a.tw_rem)) + wave;    // index among the packed waves
+  const int pw = p_alone ? 4 * s + wave
+                         : 4 * s - p_tw_full * s - max(0, s - (p_S - p_tw_rem)) + wave;    // index among the packed waves
   // (unit j of the line belongs to packed wave j / q for the first r * (q + 1) units, where the
   // host has divided n_units = q * n_pw + r: the first r waves take one unit more; no division here)
-  const int u0 = tail_wave ? 0 : a.pw_q * pw + min(pw, a.pw_r);
-  const int u1 = tail_wave ? 0 : a.pw_q * (pw + 1) + min(pw + 1, a.pw_r);
+  const int u0 = tail_wave ? 0 : p_pw_q * pw + min(pw, p_pw_r);
+  const int u1 = tail_wave ? 0 : p_pw_q * (pw + 1) + min(pw + 1, p_pw_r);
 
   // The running maximum of a head is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
@@ -733,11 +751,39 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     const int64_t bh = (int64_t)b * p_Hkv + hk;
     // (selects between the two subsets' kernel arguments, which are in registers already:
     // an index would be another scalar load and another wait)
-    const int64_t cap = sub ? a.cap[1] : a.cap[0];
-    const uint8_t* kc = sub ? a.kc[1] : a.kc[0];
-    const uint32_t* vc = sub ? a.vc[1] : a.vc[0];
-    const float *k_ts = sub ? a.k_ts[1] : a.k_ts[0], *k_tz = sub ? a.k_tz[1] : a.k_tz[0];
-    const float *v_ts = sub ? a.v_ts[1] : a.v_ts[0], *v_tz = sub ? a.v_tz[1] : a.v_tz[0];
+    int64_t cap, p_qsB, p_qsH;
+    const uint8_t* kc;
+    const uint32_t* vc;
+    const float *k_ts = nullptr, *k_tz = nullptr, *v_ts = nullptr, *v_tz = nullptr, *p_kcs, *p_kcz, *p_vcs, *p_vcz;
+    const void* p_q;
+    if constexpr (STG) {
+      const size_t so = 8 * (size_t)sub;                // (a lane index in a scalar register)
+      cap = (int64_t)arg64(offsetof(DecArgs, cap) + so);
+      kc = reinterpret_cast<const uint8_t*>(arg64(offsetof(DecArgs, kc) + so));
+      vc = reinterpret_cast<const uint32_t*>(arg64(offsetof(DecArgs, vc) + so));
+      if constexpr (KTOK) {
+        k_ts = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, k_ts) + so));
+        k_tz = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, k_tz) + so));
+      }
+      if constexpr (VTOK) {
+        v_ts = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, v_ts) + so));
+        v_tz = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, v_tz) + so));
+      }
+      p_kcs = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, k_cs)));
+      p_kcz = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, k_cz)));
+      p_vcs = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, v_cs)));
+      p_vcz = reinterpret_cast<const float*>(arg64(offsetof(DecArgs, v_cz)));
+      p_q = reinterpret_cast<const void*>(arg64(offsetof(DecArgs, q)));
+      p_qsB = (int64_t)arg64(offsetof(DecArgs, q_sB)); p_qsH = (int64_t)arg64(offsetof(DecArgs, q_sH));
+    } else {
+      cap = sub ? a.cap[1] : a.cap[0];
+      kc = sub ? a.kc[1] : a.kc[0];
+      vc = sub ? a.vc[1] : a.vc[0];
+      k_ts = sub ? a.k_ts[1] : a.k_ts[0]; k_tz = sub ? a.k_tz[1] : a.k_tz[0];
+      v_ts = sub ? a.v_ts[1] : a.v_ts[0]; v_tz = sub ? a.v_tz[1] : a.v_tz[0];
+      p_kcs = a.k_cs; p_kcz = a.k_cz; p_vcs = a.v_cs; p_vcz = a.v_cz;
+      p_q = a.q; p_qsB = a.q_sB; p_qsH = a.q_sH;
+    }
     const uint32_t code_bytes = (uint32_t)(cap * ROWB);
     const uint32_t tok_bytes = (uint32_t)(cap * 4);
     constexpr int kRsrcFlags = 0x00020000;              // raw 32-bit data, no swizzle
@@ -802,14 +848,14 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     if constexpr (STAGED) {
       const int piece = lane % PA;
       const bool zeros = (lane / PA) & 1;
-      gdma16(par_lds, (zeros ? a.k_cz : a.k_cs) + chan_off + 4 * piece);
+      gdma16(par_lds, (zeros ? p_kcz : p_kcs) + chan_off + 4 * piece);
       gdma16((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)&svc[wave][0],
-             (zeros ? a.v_cz : a.v_cs) + chan_off + 4 * piece);
-      const uint8_t* qrows = reinterpret_cast<const uint8_t*>(a.q) + ((int64_t)b * a.q_sB + (int64_t)hk * G * a.q_sH) * ESZ + 16 * (lane % PR);
+             (zeros ? p_vcz : p_vcs) + chan_off + 4 * piece);
+      const uint8_t* qrows = reinterpret_cast<const uint8_t*>(p_q) + ((int64_t)b * p_qsB + (int64_t)hk * G * p_qsH) * ESZ + 16 * (lane % PR);
 #pragma unroll
       for (int t = 0; t < NQ; ++t)
         if (t * RP < G)                                 // (wave-uniform; rows past the last head repeat it)
-          gdma16(par_lds + 1024 + t * 1024, qrows + (int64_t)min(t * RP + lane / PR, G - 1) * a.q_sH * ESZ);
+          gdma16(par_lds + 1024 + t * 1024, qrows + (int64_t)min(t * RP + lane / PR, G - 1) * p_qsH * ESZ);
     }
     // the first blocks are in flight while the operand is built
 #pragma unroll
@@ -826,11 +872,11 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       if (lane < D / 2) {
         const bool zero_half = lane >= D / 4;
         const int c4 = 4 * (zero_half ? lane - D / 4 : lane);
-        const float4 t = *reinterpret_cast<const float4*>((zero_half ? a.v_cz : a.v_cs) + chan_off + c4);
+        const float4 t = *reinterpret_cast<const float4*>((zero_half ? p_vcz : p_vcs) + chan_off + c4);
         *reinterpret_cast<float4*>(&svc[wave][(zero_half ? D : 0) + c4]) = t;
       }
-      build_query_operand(std::integral_constant<int, BITS>{}, a.q, (int64_t)b * a.q_sB + (int64_t)(hk * G + (nvalid ? g : 0)) * a.q_sH,
-                          a.k_cs + chan_off, a.k_cz + chan_off, qB, Aq, sumqcz, Aq_k, sumqcz_k);
+      build_query_operand(std::integral_constant<int, BITS>{}, p_q, (int64_t)b * p_qsB + (int64_t)(hk * G + (nvalid ? g : 0)) * p_qsH,
+                          p_kcs + chan_off, p_kcz + chan_off, qB, Aq, sumqcz, Aq_k, sumqcz_k);
     }
     ZC_MARK(2);                                 // the segment's query operand is built
     // Subnormal codes: the logit is ts (dot - tz sum(q') - sum(q' cz)), the two sums taken off
@@ -1066,7 +1112,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
           len = __builtin_amdgcn_readfirstlane(a.chunk_table[4 * ci + 2 * sub + 1]);
           asm volatile("" : "+s"(begin), "+s"(len));
         }
-        const int bits = sub ? a.bits[1] : a.bits[0];
+        int bits;
+        if constexpr (STG) bits = arg32(offsetof(DecArgs, bits) + 4 * (size_t)sub);
+        else bits = sub ? a.bits[1] : a.bits[0];
         const int TB = 4 * (32 / bits);
         const int nb = ceil_div(len, 32);          // half-blocks of 32 slots (equal compute at either width)
         if (nb == 0) continue;
