@@ -357,6 +357,21 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   // yet, only takes the maximum over, and the factors of the heads of a lane's output rows
   // (columns 4 grp and 4 grp + 2; every row holds the same factors) come from row broadcasts
   // with a row mask instead of two shuffles through the LDS crossbar.
+  // x of this lane's row at columns 4 grp and 4 grp + 2 (the value columns of heads g0 and g1):
+  // row broadcasts under a row mask (a value that is the same in every row comes out the same
+  // way a shuffle from lanes 2 g0 and 2 g1 would deliver it, without the trip through LDS).
+  auto head_columns = [&](float x, float& c0, float& c1) {
+    const int xi = __float_as_int(x);
+    int i0 = __builtin_amdgcn_update_dpp(0, xi, 0x150, 0x1, 0xF, false);       // row 0 <- its lane 0
+    i0 = __builtin_amdgcn_update_dpp(i0, xi, 0x154, 0x2, 0xF, false);          // row 1 <- its lane 4
+    i0 = __builtin_amdgcn_update_dpp(i0, xi, 0x158, 0x4, 0xF, false);          // row 2 <- its lane 8
+    i0 = __builtin_amdgcn_update_dpp(i0, xi, 0x15C, 0x8, 0xF, false);          // row 3 <- its lane 12
+    int i1 = __builtin_amdgcn_update_dpp(0, xi, 0x152, 0x1, 0xF, false);       // lanes 2, 6, 10, 14
+    i1 = __builtin_amdgcn_update_dpp(i1, xi, 0x156, 0x2, 0xF, false);
+    i1 = __builtin_amdgcn_update_dpp(i1, xi, 0x15A, 0x4, 0xF, false);
+    i1 = __builtin_amdgcn_update_dpp(i1, xi, 0x15E, 0x8, 0xF, false);
+    c0 = __int_as_float(i0); c1 = __int_as_float(i1);
+  };
   auto update_max = [&](float lmax, float (&a1)[4], f4 (*acc)[4], f4& acc1) {
     if (__builtin_amdgcn_ballot_w64(lmax > m_run)) {     // (unused columns sit at +inf)
       const float m_new = fmaxf(m_run, grp_max(lmax));
@@ -365,16 +380,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         z_part *= fac;
 #pragma unroll
         for (int v = 0; v < 4; ++v) a1[v] *= fac;
-        const int fi = __float_as_int(fac);
-        int i0 = __builtin_amdgcn_update_dpp(0, fi, 0x150, 0x1, 0xF, false);       // row 0 <- its lane 0
-        i0 = __builtin_amdgcn_update_dpp(i0, fi, 0x154, 0x2, 0xF, false);          // row 1 <- its lane 4
-        i0 = __builtin_amdgcn_update_dpp(i0, fi, 0x158, 0x4, 0xF, false);          // row 2 <- its lane 8
-        i0 = __builtin_amdgcn_update_dpp(i0, fi, 0x15C, 0x8, 0xF, false);          // row 3 <- its lane 12
-        int i1 = __builtin_amdgcn_update_dpp(0, fi, 0x152, 0x1, 0xF, false);       // lanes 2, 6, 10, 14
-        i1 = __builtin_amdgcn_update_dpp(i1, fi, 0x156, 0x2, 0xF, false);
-        i1 = __builtin_amdgcn_update_dpp(i1, fi, 0x15A, 0x4, 0xF, false);
-        i1 = __builtin_amdgcn_update_dpp(i1, fi, 0x15E, 0x8, 0xF, false);
-        const float f0 = __int_as_float(i0), f1 = __int_as_float(i1);
+        float f0, f1;
+        head_columns(fac, f0, f1);
         Zrun0 *= f0; Zrun1 *= f1;
 #pragma unroll
         for (int r = 0; r < NR; ++r)
@@ -1079,8 +1086,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       float a1s = 0.f;
 #pragma unroll
       for (int v = 0; v < 4; ++v) a1s = fmaf(a1[v], WSPLIT ? 1.f : 1.f / wcomp[v], a1s);
-      a1s = grp_sum(a1s);
-      a10 = __shfl(a1s, 2 * g0); a11 = __shfl(a1s, 2 * g1);
+      a1s = grp_sum(a1s);                          // (the same in every row)
+      head_columns(a1s, a10, a11);
     }
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
@@ -1134,19 +1141,18 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
     } else {
       if (nvalid && part == 0 && grp == 0) mM[wave][g] = m_run;
-      if (n == 0) {
-        if (g0 < G) mZ[wave][g0] = Zrun0;
-        if (g1 < G) mZ[wave][g1] = Zrun1;
-      }
+      if (n == 0) { mZ[wave][g0] = Zrun0; mZ[wave][g1] = Zrun1; }      // (rows below G are read)
     }
+    // (four consecutive channels a store, and no condition on the head: the ring has rows for
+    // ZC_MAX_GROUP heads, the merge reads those below G - 32 single stores, each with a branch
+    // around it, were 0.4 us at the end of every wave's path)
+    static_assert(2 * 3 + 1 < MG, "rows g0, g1 of every lane exist in the ring");
 #pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int c = 4 * (n + 16 * r) + j;
-        if (g0 < G) mO(wave, g0, c) = O[r][j][0];
-        if (g1 < G) mO(wave, g1, c) = O[r][j][1];
-      }
+    for (int r = 0; r < NR; ++r) {
+      const int c = 4 * (n + 16 * r);
+      *reinterpret_cast<float4*>(&mO(wave, g0, c)) = make_float4(O[r][0][0], O[r][1][0], O[r][2][0], O[r][3][0]);
+      *reinterpret_cast<float4*>(&mO(wave, g1, c)) = make_float4(O[r][0][1], O[r][1][1], O[r][2][1], O[r][3][1]);
+    }
   }
   ZC_MARK(6);                                   // at the barrier before the merge
   __syncthreads();
