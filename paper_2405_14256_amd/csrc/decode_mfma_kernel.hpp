@@ -1167,8 +1167,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 // past the last one repeat it, with weight 0), and the weights 2^(m - M) come from one
 // exponential over the lanes, handed round as scalars.  (With a branch per split - which
 // loads exist depends on S - the loads took 1.6 us to issue and land, against 0.8 us here.)
-// NMAX: the most splits this instance handles (8 for launches that fill the chip, whose heads
-// have few splits each; kCombineMax otherwise).
+// NMAX: the most splits this instance handles (8, 16, 24 or kCombineMax: the smallest that holds S -
+// an output partial that does not exist still costs its load and its two instructions).
 template <int DT, int D, int NMAX>
 __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ part_m, const float* __restrict__ part_z,
                                                       const float* __restrict__ part_o, int S,
@@ -1197,14 +1197,18 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
   M = fmaxf(M, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(M), __float_as_int(M), 0x143, 0xC, 0xF, false)));   // row_bcast:31
   M = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(M), 63));
   const float fv = (pmv > -INFINITY) ? fast_exp2(pmv - M) : 0.f;
-  float o = 0.f, z = 0.f;
+  // the denominator: one product per lane, summed the way the maximum was taken
+  float z = pzv * fv;
+  z += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x111, 0xF, 0xF, false));    // row_shr:1 (0 shifted in)
+  z += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x112, 0xF, 0xF, false));    // row_shr:2
+  z += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x114, 0xF, 0xF, false));    // row_shr:4
+  z += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x118, 0xF, 0xF, false));    // row_shr:8
+  z += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x142, 0xA, 0xF, false));    // row_bcast:15
+  z += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x143, 0xC, 0xF, false));    // row_bcast:31
+  z = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z), 63));
+  float o = 0.f;
 #pragma unroll
-  for (int ss = 0; ss < NMAX; ++ss) {
-    const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fv), ss));
-    const float pz = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pzv), ss));
-    o = fmaf(po[ss], f, o);
-    z = fmaf(pz, f, z);
-  }
+  for (int ss = 0; ss < NMAX; ++ss) o = fmaf(po[ss], __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fv), ss)), o);
   store1<DT>(out, hq * D + c, z > 0.f ? o / z : 0.f);
   if (lse_out && c == 0) lse_out[hq] = (M + log2f(z)) * kLn2;
   if (c == 0) ZC_MARK(2);                       // end
@@ -1235,8 +1239,8 @@ static int launch_decode_mfma_dt(const DecArgs& a, hipStream_t st) {
   ZC_LAUNCH_CHECK();
   if (a.S > 1) {
 #define ZC_R(DD, NM) hipLaunchKernelGGL((k_decode_reduce<DT, DD, NM>), dim3(a.Hq, a.B), dim3(DD), 0, st, a.part_m, a.part_z, a.part_o, a.S, a.out, a.lse_out)
-    if (a.D == 128) { if (a.S <= 8) ZC_R(128, 8); else ZC_R(128, kCombineMax); }
-    else { if (a.S <= 8) ZC_R(64, 8); else ZC_R(64, kCombineMax); }
+    if (a.D == 128) { if (a.S <= 8) ZC_R(128, 8); else if (a.S <= 16) ZC_R(128, 16); else if (a.S <= 24) ZC_R(128, 24); else ZC_R(128, kCombineMax); }
+    else { if (a.S <= 8) ZC_R(64, 8); else if (a.S <= 16) ZC_R(64, 16); else if (a.S <= 24) ZC_R(64, 24); else ZC_R(64, kCombineMax); }
 #undef ZC_R
     ZC_LAUNCH_CHECK();
   }
