@@ -1163,8 +1163,8 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 // Reduces the partial (m, Z, o) of the workgroups of one query head.  The call's latency is
 // this kernel's too, so nothing here branches: lane ss of every wave fetches (m, Z) of split
 // ss with one load each (lanes past the last split repeat the last one and count as empty),
-// the 32 possible output partials of this thread's channel are requested back to back (splits
-// past the last one repeat it, with weight 0), and the weights 2^(m - M) come from one
+// the NMAX possible output partials of this thread's channel are requested back to back (splits
+// past the last one are out of range of the buffer: zeros, with weight 0), and the weights 2^(m - M) come from one
 // exponential over the lanes, handed round as scalars.  (With a branch per split - which
 // loads exist depends on S - the loads took 1.6 us to issue and land, against 0.8 us here.)
 // NMAX: the most splits this instance handles (8, 16, 24 or kCombineMax: the smallest that holds S -
@@ -1181,9 +1181,14 @@ __global__ __launch_bounds__(D) void k_decode_reduce(const float* __restrict__ p
   if (c == 0) ZC_MARK(0);                       // entry
   const int64_t row = hq * S;
   float pmv = part_m[row + min(lane, last)], pzv = part_z[row + min(lane, last)];
+  // (through a buffer descriptor over this head's S rows: a row past the last is out of range
+  // and arrives as zero - its weight is zero too - and the row's offset is a constant of the
+  // instruction; with plain loads each address took six instructions, 0.3 us of them in
+  // front of the first load)
+  const auto rs_o = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(part_o + row * D), 0, (uint32_t)S * D * 4u, 0x00020000);
   float po[NMAX];
 #pragma unroll
-  for (int ss = 0; ss < NMAX; ++ss) po[ss] = part_o[(row + min(ss, last)) * D + c];
+  for (int ss = 0; ss < NMAX; ++ss) po[ss] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_o, 4 * c + ss * (D * 4), 0, 0));
   if (lane > last) { pmv = -INFINITY; pzv = 0.f; }
   if (c == 0) ZC_MARK_LOADED(1);                // the partials have landed (the trace build waits for them here)
   // maximum over the lanes: inside the rows of 16, then row to row into lane 63 (vector
