@@ -641,6 +641,33 @@ def test_decode_randomized_shapes():
         assert np.abs(lse[bsel].cpu().numpy() - lse_o).max() <= max(atol, 1e-3) * 0.5, what
 
 
+@pytest.mark.parametrize("L", [600, 2000, 2700, 3300, 4300, 5600, 7000, 9000])
+def test_decode_every_instance_of_the_reduce_kernel(L):
+    """One prompt, two KV heads: the number of workgroups per head grows with the cache (about one
+    per eight half-blocks, up to 32), and the reduce kernel has an instance for up to 8, 16, 24
+    and 32 of them; without a tail the count is the cache's alone.  Every length against the
+    oracle's attention over the de-quantized GPU codes, output and log-sum-exp."""
+    from tests.pipeline_check import packed_to_chunks
+    Hq, Hkv, d = 8, 2, 128
+    g = torch.Generator().manual_seed(9000 + L)
+    K = torch.randn(1, Hkv, L, d, generator=g).to(torch.bfloat16)
+    V = torch.randn(1, Hkv, L, d, generator=g).to(torch.bfloat16)
+    q = torch.randn(1, Hq, d, generator=g).to(torch.bfloat16)
+    lib = zb.load()
+    k = int(0.4 * L)
+    sal, reg = zb.zc_select_salient(torch.rand(1, L, generator=g).to(DEV), k)
+    Kp = zb.PackedTensor(1, Hkv, d, lib.zc_arena_slots(k, 1), lib.zc_arena_slots(L - k, 1), 4, 2, "channel", zb.ZC_LAYOUT_ROW, max_chunks=1, device=DEV)
+    Vp = zb.PackedTensor(1, Hkv, d, lib.zc_arena_slots(k, 1), lib.zc_arena_slots(L - k, 1), 4, 2, "cst", zb.ZC_LAYOUT_TGROUP, max_chunks=1, device=DEV)
+    zb.zc_quantize_pack(K.to(DEV), sal, reg, Kp)
+    zb.zc_quantize_pack(V.to(DEV), sal, reg, Vp)
+    lse = torch.empty(1, Hq, dtype=torch.float32, device=DEV)
+    out = zb.zc_decode_attention(q.to(DEV), Kp, Vp, None, None, 0, lse_out=lse)
+    Kc, Vc = zo.cache_matrices(packed_to_chunks(Kp, [0]), packed_to_chunks(Vp, [0]), Hkv, None, None)
+    ref, lse_o, _ = zo.decode_attention(q.double().numpy(), Kc, Vc)
+    assert np.abs(out.cpu().double().numpy() - ref).max() <= 2e-2
+    assert np.abs(lse.cpu().numpy() - lse_o).max() <= 1e-3
+
+
 def test_decode_same_answer_under_any_split():
     """The same sequence alone (few workgroups: many waves per head, a workgroup per tail
     unit) and replicated 48 times (more heads than CUs: two or three workgroups per
