@@ -515,19 +515,21 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   auto write_result = [&]() {
     const bool direct = a.S == 1;
     constexpr int NIT = MG * D / 256;               // most elements per thread
+    static_assert(256 % D == 0, "a thread's elements share their channel");
+    const int c = tid % D, g_first = tid / D;       // (tid is below 256: shifts and masks)
+    const int64_t hq0 = (int64_t)b * a.Hq + hk * G; // first head of this KV head's group
     float pm[NIT][4], pz[NIT][4], po[NIT][4];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       if (256 * it >= G * D) break;                 // (wave-uniform)
-      const int i = min(tid + 256 * it, G * D - 1), gg = i / D, c = i % D;
+      const int gg = min(g_first + it * (256 / D), G - 1);       // (element tid + 256 it: head gg, channel c)
 #pragma unroll
       for (int w = 0; w < 4; ++w) { pm[it][w] = mM[w][gg]; pz[it][w] = mZ[w][gg]; po[it][w] = mO(w, gg, c); }
     }
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const int i = tid + 256 * it;
-      if (i >= G * D) break;
-      const int gg = i / D, c = i % D;
+      const int gg = g_first + it * (256 / D);
+      if (gg >= G) break;
       const float M = fmaxf(fmaxf(pm[it][0], pm[it][1]), fmaxf(pm[it][2], pm[it][3]));
       float o = 0.f, z = 0.f;
 #pragma unroll
@@ -536,13 +538,14 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         o = fmaf(po[it][w], f, o);
         z = fmaf(pz[it][w], f, z);
       }
-      const int64_t hq = (int64_t)b * a.Hq + hk * G + gg;
+      // (the uniform part of every index in scalar registers, the thread's own part in 32 bits)
       if (direct) {
-        store1<DT>(a.out, hq * D + c, z > 0.f ? o / z : 0.f);
-        if (a.lse_out && c == 0) a.lse_out[hq] = (M + log2f(z)) * kLn2;
+        store1<DT>(a.out, hq0 * D + (gg * D + c), z > 0.f ? o / z : 0.f);
+        if (a.lse_out && c == 0) a.lse_out[hq0 + gg] = (M + log2f(z)) * kLn2;
       } else {
-        a.part_o[(hq * a.S + s) * D + c] = o;
-        if (c == 0) { a.part_m[hq * a.S + s] = M; a.part_z[hq * a.S + s] = z; }
+        const int64_t row0 = hq0 * a.S + s;
+        a.part_o[row0 * D + ((gg * a.S) * D + c)] = o;
+        if (c == 0) { a.part_m[row0 + gg * a.S] = M; a.part_z[row0 + gg * a.S] = z; }
       }
     }
   };
