@@ -350,13 +350,13 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
   const int u0 = tail_wave ? 0 : p_pw_q * pw + min(pw, p_pw_r);
   const int u1 = tail_wave ? 0 : p_pw_q * (pw + 1) + min(pw + 1, p_pw_r);
 
-  // The running maximum of a head is only touched when some slot of the
+  // The running reference of a head's softmax is only touched when some slot of the
   // half-block exceeds it (a ballot, no data movement otherwise); everything
   // accumulated so far is then rescaled.  Rare after the first half-blocks - but a wave of a
   // short cache has only one or two: its first half-block, which finds nothing accumulated
   // yet, only takes the maximum over, and the factors of the heads of a lane's output rows
   // (columns 4 grp and 4 grp + 2; every row holds the same factors) come from row broadcasts
-  // with a row mask instead of two shuffles through the LDS crossbar.
+  // with a row mask instead of two shuffles through the LDS crossbar (head_columns, update_ref).
   // x of this lane's row at columns 4 grp and 4 grp + 2 (the value columns of heads g0 and g1):
   // row broadcasts under a row mask (a value that is the same in every row comes out the same
   // way a shuffle from lanes 2 g0 and 2 g1 would deliver it, without the trip through LDS).
@@ -372,11 +372,22 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     i1 = __builtin_amdgcn_update_dpp(i1, xi, 0x15E, 0x8, 0xF, false);
     c0 = __int_as_float(i0); c1 = __int_as_float(i1);
   };
-  auto update_max = [&](float lmax, float (&a1)[4], f4 (*acc)[4], f4& acc1) {
-    if (__builtin_amdgcn_ballot_w64(lmax > m_run)) {     // (unused columns sit at +inf)
-      const float m_new = fmaxf(m_run, grp_max(lmax));
-      if (__builtin_amdgcn_ballot_w64(nvalid && m_run > -INFINITY)) {
-        const float fac = (nvalid && m_run > -INFINITY) ? fast_exp2(m_run - m_new) : 0.f;
+  // The packed waves keep their logits relative to the running reference m_ref of their column:
+  // the reference is folded into the constant that the logit's last multiply-add adds anyway
+  // (shift[v] - m_ref), so a weight is exp2 of what that instruction delivers - no subtraction
+  // per logit - and "a slot exceeds the reference" is "a relative logit above 0".  The first
+  // half-block of a wave takes its maximum over as the reference (nothing is accumulated yet);
+  // later ones only raise it, rescaling what is accumulated.  lg: this half-block's relative
+  // logits, re-referenced here when the reference moves; rel[v] = base[v] - m_ref.
+  float m_ref = nvalid ? 0.f : INFINITY;       // (unused columns: every relative logit -inf, weight 0)
+  bool seen = false;                            // (wave-uniform) a half-block has been taken in
+  auto update_ref = [&](float lmax, float (&lg)[2][4], float (&rel)[4], const float (&base)[4], float (&a1)[4], f4 (*acc)[4],
+                        f4& acc1) {
+    if (!seen || __builtin_amdgcn_ballot_w64(lmax > 0.f)) {
+      float delta = grp_max(lmax);
+      if (seen) {
+        delta = fmaxf(delta, 0.f);              // (0 where nothing moved, and in unused columns)
+        const float fac = fast_exp2(-delta);
         z_part *= fac;
 #pragma unroll
         for (int v = 0; v < 4; ++v) a1[v] *= fac;
@@ -391,8 +402,17 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
             acc[r][j].x *= f0; acc[r][j].y *= f0; acc[r][j].z *= f1; acc[r][j].w *= f1;
           }
         acc1.x *= f0; acc1.y *= f0; acc1.z *= f1; acc1.w *= f1;
+      } else {
+        delta = nvalid ? delta : 0.f;           // (the first reference may lie below 0)
       }
-      m_run = m_new;
+      m_ref += delta;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) rel[v] = base[v] - m_ref;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) lg[jj][v] -= delta;
+      seen = true;
     }
   };
 
@@ -913,11 +933,14 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
     // Unsplit weights: that factor (a power of two) is folded into the logit, so exp2
     // delivers p times the factor; the running maximum is then the maximum of the
     // shifted logits, which is as good a reference point as the true one.
-    float lshift[4], kshift[4];
+    // base[v]: what the last multiply-add of a logit adds (tokenwise keys: the factor's power;
+    // else that plus the segment's constant); rel[v] = base[v] - m_ref is what it adds here.
+    float base[4], rel[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      lshift[v] = WSPLIT ? 0.f : (float)code_comp_log2<BITS, SUBN>(v);
-      kshift[v] = kconst + lshift[v];
+      const float lshift = WSPLIT ? 0.f : (float)code_comp_log2<BITS, SUBN>(v);
+      base[v] = KTOK ? lshift : kconst + lshift;
+      rel[v] = base[v] - m_ref;
     }
     // B operand that sums the weights: 1 / factor of each operand register
     // (normalized codes: plain ones, the sum then carries SC and is also the "1" term of the output product)
@@ -990,9 +1013,9 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
         for (int v = 0; v < 4; ++v) {
           float x;
           const float dot = QSPLIT ? own[v] + xor1(own[v]) : own[v];     // value + residual column
-          if constexpr (KTOK && !SUBN) x = fmaf(kts[v], dot * UNSCALE, lshift[v]);        // already centred
-          else if constexpr (KTOK) x = fmaf(kts[v], fmaf(-ktz[v], Aq, fmaf(dot, UNSCALE, kconst)), lshift[v]);
-          else x = fmaf(dot, UNSCALE, kshift[v]);
+          if constexpr (KTOK && !SUBN) x = fmaf(kts[v], dot * UNSCALE, rel[v]);        // already centred
+          else if constexpr (KTOK) x = fmaf(kts[v], fmaf(-ktz[v], Aq, fmaf(dot, UNSCALE, kconst)), rel[v]);
+          else x = fmaf(dot, UNSCALE, rel[v]);
           lg[jj][v] = x;
         }
       }
@@ -1011,14 +1034,14 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
       }
       const float lmax = fmaxf(fmaxf(fmaxf(fmaxf(lg[0][0], lg[0][1]), lg[0][2]), fmaxf(fmaxf(lg[0][3], lg[1][0]), lg[1][1])),
                                fmaxf(lg[1][2], lg[1][3]));       // three v_max3 and one v_max
-      update_max(lmax, a1, acc, acc1);
+      update_ref(lmax, lg, rel, base, a1, acc, acc1);
       // weights w = p ts and the A operand of the output product
       float w2[2][4];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const float p = fast_exp2(lg[jj][v] - m_run);      // 0 for masked slots and unused columns
+          const float p = fast_exp2(lg[jj][v]);              // 0 for masked slots and unused columns
           float w = p;
           if constexpr (VTOK) {
             w = p * vts[jj][v];
@@ -1139,11 +1162,12 @@ __global__ __launch_bounds__(256, MINB) void k_decode_mfma(DecArgs a) {
 
     ZC_MARK(5);                                 // the segments are folded
     // ---------------- this wave's partial, for the merge of the four waves ---------------
+    const float m_out = seen ? m_ref : -INFINITY;    // (a wave without a half-block: empty)
     if constexpr (WSPLIT) {
       const float z_tot = grp_sum(z_part);
-      if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_run; mZ[wave][g] = z_tot; }
+      if (nvalid && part == 0 && grp == 0) { mM[wave][g] = m_out; mZ[wave][g] = z_tot; }
     } else {
-      if (nvalid && part == 0 && grp == 0) mM[wave][g] = m_run;
+      if (nvalid && part == 0 && grp == 0) mM[wave][g] = m_out;
       if (n == 0) { mZ[wave][g0] = Zrun0; mZ[wave][g1] = Zrun1; }      // (rows below G are read)
     }
     // (four consecutive channels a store, and no condition on the head: the ring has rows for
